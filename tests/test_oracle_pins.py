@@ -1,0 +1,322 @@
+"""Pins for the CPU oracle: closed forms, identities of Sections 2.3 and 3, exact rational arithmetic
+on tiny inputs, special cases that reduce to an exact product, and the accuracy behaviour the paper
+describes.  Everything here runs without a GPU and uses Python integers / Fractions as the independent
+arithmetic."""
+import math
+import os
+from fractions import Fraction
+
+import numpy as np
+import pytest
+
+from oracle import oracle as orc
+from paper_2504_08009_amd import inputs
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def paper_moduli_s16():
+    with open(os.path.join(GOLDEN, "moduli_s16_paper.txt")) as f:
+        for line in f:
+            if not line.startswith("#"):
+                return [int(x) for x in line.split()]
+
+
+# ------------------------------------------------------------------ Section 2.1: symmetric modulo
+def test_sym_mod_named_values():
+    # nearest-to-zero representative; the even modulus sends +p/2 to -p/2
+    assert orc.sym_mod(128, 256) == -128
+    assert orc.sym_mod(-128, 256) == -128
+    assert orc.sym_mod(127, 256) == 127
+    assert orc.sym_mod(128, 255) == -127
+    assert orc.sym_mod(127, 255) == 127
+    assert orc.sym_mod(0, 199) == 0
+
+
+def test_sym_mod_bruteforce_against_definition():
+    # r = a - p*floor(a/p + 1/2) with exact rationals, and the characterisation "closest to zero"
+    for p in orc.moduli(26) + [2, 3, 4]:
+        for a in list(range(-700, 701)) + [2**40 + 12345, -(2**40) - 777, 2**62 - 1, -(2**62)]:
+            want = a - p * math.floor(Fraction(a, p) + Fraction(1, 2))
+            got = orc.sym_mod(a, p)
+            assert got == want
+            assert (got - a) % p == 0 and -p / 2 <= got < p / 2
+
+
+# ------------------------------------------------------------------ Section 3.1: moduli
+def test_moduli_pairwise_coprime_and_greedy():
+    mods = orc.moduli(26)
+    assert mods[0] == 256 and all(2 <= p <= 256 for p in mods)
+    assert mods == sorted(mods, reverse=True)
+    for i in range(len(mods)):
+        for j in range(i):
+            assert math.gcd(mods[i], mods[j]) == 1
+    # "largest possible": every skipped value shares a factor with a larger kept one
+    for c in range(mods[-1], 257):
+        if c not in mods:
+            assert any(math.gcd(c, p) != 1 for p in mods if p > c)
+    # prefix property: N moduli are the first N of the one table
+    assert orc.moduli(7) == mods[:7]
+
+
+def test_paper_printed_list_properties():
+    pm = paper_moduli_s16()
+    assert len(pm) == 16 and pm[0] == 256 and pm[-1] == 191
+    assert abs(pm[-1] / pm[0] - 0.74) < 0.01  # the ratio the paper quotes
+    for i in range(16):
+        for j in range(i):
+            assert math.gcd(pm[i], pm[j]) == 1
+    # the greedy table differs from the printed one only by containing 241
+    g = orc.moduli(17)
+    assert sorted(set(g) - set(pm)) == [241]
+
+
+# ------------------------------------------------------------------ Section 2.3: CRT constants
+@pytest.mark.parametrize("N", [2, 3, 8, 16, 20, 26])
+def test_crt_weights_identities(N):
+    mods = orc.moduli(N)
+    M, W = orc.crt_constants(N)
+    assert M == math.prod(mods)
+    for t, p in enumerate(mods):
+        assert 0 < W[t] < M
+        assert W[t] % p == 1
+        assert W[t] % (M // p) == 0
+        for u, q in enumerate(mods):
+            if u != t:
+                assert W[t] % q == 0
+    assert sum(W) % M == 1
+
+
+def test_crt_closed_form_two_moduli():
+    M, W = orc.crt_constants(2)
+    assert M == 256 * 255 and W == [255 * 255, 256]
+
+
+def test_crt_round_trip_paper_list():
+    pm = paper_moduli_s16()
+    M, W = orc.crt_constants(16, pm)
+    rng = np.random.default_rng(5)
+    for _ in range(200):
+        x = int(rng.integers(-2**62, 2**62)) * int(rng.integers(1, 2**60)) % M - M // 2
+        y = sum((x % p) * w for p, w in zip(pm, W)) % M
+        if y >= M - M // 2:
+            y -= M
+        assert y == x
+
+
+# ------------------------------------------------------------------ Section 3: bit budget kappa
+def test_kappa_invariant_and_table():
+    for N in range(2, 27):
+        M, _ = orc.crt_constants(N)
+        for k in [1, 2, 255, 256, 1024, 4096, 16384, 65536, 2**17]:
+            kap = orc.kappa(N, k)
+            if kap < 0:
+                assert k > M // 2 - 1
+                continue
+            assert k * 4**kap <= M // 2 - 1 < k * 4 ** (kap + 1)
+            # same number from the printed formula, evaluated with exact integer logarithms
+            assert kap == (((M // 2 - 1) // k).bit_length() - 1) // 2
+    assert [orc.kappa(N, 1024) for N in range(8, 21)] == [26, 30, 34, 38, 41, 45, 49, 53, 57, 60, 64, 68, 72]
+
+
+def test_kappa_sixteen_moduli_reach_53_bits():
+    # Section 3.1: with s = 16 the budget reaches 53 bits for p = q = r in {1024, 4096, 16384};
+    # fifteen moduli do not at every size.  Holds for the greedy table and for the printed list.
+    pm = paper_moduli_s16()
+    sizes = [1024, 4096, 16384]
+    assert min(orc.kappa(16, k) for k in sizes) >= 53
+    assert min(orc.kappa(15, k) for k in sizes) < 53
+    assert min(orc.kappa(16, k, pm) for k in sizes) >= 53
+    assert min(orc.kappa(15, k, pm[:15]) for k in sizes) < 53
+
+
+def test_int32_exactness_limit():
+    # Section 3.1: no INT32 overflow for q < 2^17
+    assert (2**17 - 1) * 128 * 128 < 2**31 <= 2**17 * 128 * 128
+
+
+# ------------------------------------------------------------------ Algorithm 1 on tiny inputs, exact arithmetic
+def _tiny(seed, m, n, k, phi):
+    rng = np.random.default_rng(seed)
+    A = (rng.random((m, k)) - 0.5) * np.exp(phi * rng.standard_normal((m, k)))
+    B = (rng.random((k, n)) - 0.5) * np.exp(phi * rng.standard_normal((k, n)))
+    return A, B
+
+
+@pytest.mark.parametrize("N,phi,use_paper_list", [(3, 0.5, False), (8, 0.5, False), (14, 1.0, False),
+                                                  (16, 0.5, True), (20, 4.0, False), (26, 4.0, False)])
+def test_every_step_against_exact_rationals(N, phi, use_paper_list):
+    m, n, k = 5, 4, 7
+    A, B = _tiny(100 + N, m, n, k, phi)
+    A[2, 3] = 0.0
+    mods = paper_moduli_s16() if use_paper_list else orc.moduli(N)
+    M = math.prod(mods)
+    kap = orc.kappa(N, k, mods)
+    r = orc.dgemm(A, B, N, mods=mods, want=("C", "shifts", "Ap", "Bp", "Ares", "Bres", "Cprod", "Cres", "X"))
+
+    # line 1: the row/column maximum lands in [2^(kappa-1), 2^kappa)
+    for i in range(m):
+        mx = max(abs(Fraction(float(x))) for x in A[i, :]) * Fraction(2) ** int(r.sa[i])
+        assert Fraction(2) ** (kap - 1) <= mx < Fraction(2) ** kap
+    for j in range(n):
+        mx = max(abs(Fraction(float(x))) for x in B[:, j]) * Fraction(2) ** int(r.sb[j])
+        assert Fraction(2) ** (kap - 1) <= mx < Fraction(2) ** kap
+
+    # lines 2-3: truncation toward zero of the exactly scaled value
+    for i in range(m):
+        for l in range(k):
+            assert r.Ap[i][l] == math.trunc(Fraction(float(A[i, l])) * Fraction(2) ** int(r.sa[i]))
+    for l in range(k):
+        for j in range(n):
+            assert r.Bp[l][j] == math.trunc(Fraction(float(B[l, j])) * Fraction(2) ** int(r.sb[j]))
+
+    # uniqueness premise of Section 3: (|A'||B'|)_ij < M/2
+    for i in range(m):
+        for j in range(n):
+            assert sum(abs(r.Ap[i][l]) * abs(r.Bp[l][j]) for l in range(k)) < M // 2
+
+    for t, p in enumerate(mods):
+        for i in range(m):
+            for l in range(k):
+                a = int(r.Ares[t, i, l])
+                assert (a - r.Ap[i][l]) % p == 0 and -p / 2 <= a < p / 2 and -128 <= a <= 127
+        for j in range(n):
+            for l in range(k):
+                b = int(r.Bres[t, j, l])
+                assert (b - r.Bp[l][j]) % p == 0 and -p / 2 <= b < p / 2
+        for i in range(m):
+            for j in range(n):
+                # line 6 and the congruence of Section 2.3
+                cp = sum(int(r.Ares[t, i, l]) * int(r.Bres[t, j, l]) for l in range(k))
+                assert int(r.Cprod[t, i, j]) == cp
+                exact_ij = sum(r.Ap[i][l] * r.Bp[l][j] for l in range(k))
+                assert int(r.Cres[t, i, j]) == exact_ij % p  # line 7, floor-mod in [0, p)
+
+    # lines 8-10: the CRT recovers the integer product itself
+    for i in range(m):
+        for j in range(n):
+            exact_ij = sum(r.Ap[i][l] * r.Bp[l][j] for l in range(k))
+            assert r.X[i][j] == exact_ij
+            # line 11: one correctly rounded conversion, then an exact scaling
+            want = float(Fraction(exact_ij, 1) / Fraction(2) ** (int(r.sa[i]) + int(r.sb[j])))
+            assert r.C[i, j] == want
+
+
+def test_small_integer_matrices_are_multiplied_exactly():
+    # |a|,|b| < 2^10 and k*2^20 < 2^53: nothing is truncated once kappa >= 11, so C == A B exactly
+    rng = np.random.default_rng(7)
+    m, n, k = 9, 11, 33
+    A = rng.integers(-1023, 1024, (m, k)).astype(np.float64)
+    B = rng.integers(-1023, 1024, (k, n)).astype(np.float64)
+    A[:, 0] = 1023.0  # make every row/column maximum sit in the same binade
+    B[0, :] = 1023.0
+    want = (A.astype(np.int64) @ B.astype(np.int64)).astype(np.float64)
+    for N in [5, 8, 16]:
+        assert orc.kappa(N, k) >= 11
+        assert np.array_equal(orc.dgemm(A, B, N).C, want)
+
+
+def test_large_moduli_count_gives_correctly_rounded_product():
+    # When kappa exceeds 53 plus the exponent spread of every row/column nothing is truncated and the
+    # result is the exact product rounded once.
+    m, n, k = 6, 5, 16
+    A, B = _tiny(11, m, n, k, 0.5)
+    N = 26
+    r = orc.dgemm(A, B, N, want=("C", "shifts"))
+    for i in range(m):
+        for j in range(n):
+            s = sum(Fraction(float(A[i, l])) * Fraction(float(B[l, j])) for l in range(k))
+            assert r.C[i, j] == float(s)
+
+
+def test_zero_rows_columns_and_k_zero():
+    A, B = _tiny(3, 4, 3, 6, 0.5)
+    A[1, :] = 0.0
+    B[:, 2] = 0.0
+    r = orc.dgemm(A, B, 10, want=("C", "shifts"))
+    assert r.sa[1] == 0 and r.sb[2] == 0
+    assert np.all(r.C[1, :] == 0.0) and np.all(r.C[:, 2] == 0.0)
+    r0 = orc.dgemm(np.zeros((3, 0)), np.zeros((0, 2)), 10)
+    assert r0.C.shape == (3, 2) and np.all(r0.C == 0.0)
+
+
+def test_subset_equals_full():
+    A, B = _tiny(21, 12, 10, 20, 1.0)
+    full = orc.dgemm(A, B, 12).C
+    rows, cols = [11, 0, 5], [9, 3]
+    sub = orc.dgemm(A, B, 12, rows=rows, cols=cols).C
+    assert np.array_equal(sub, full[np.ix_(rows, cols)])
+
+
+def test_exact_reference_against_fractions():
+    A, B = _tiny(31, 4, 3, 50, 2.0)
+    C, S = orc.exact(A, B)
+    for i in range(4):
+        for j in range(3):
+            s = sum(Fraction(float(A[i, l])) * Fraction(float(B[l, j])) for l in range(50))
+            sa = sum(abs(Fraction(float(A[i, l])) * Fraction(float(B[l, j]))) for l in range(50))
+            assert C[i, j] == float(s) and S[i, j] == float(sa)
+
+
+# ------------------------------------------------------------------ accuracy behaviour (Sections 3 and 4.1)
+def test_error_bound_and_decay_with_moduli():
+    cfg = inputs.CONFIGS["c2"]
+    k = cfg["k"]
+    rows = np.arange(0, 1024, 16)
+    cols = np.arange(3, 1024, 16)
+    A = inputs.block(cfg["seed"], 0, cfg["m"], k, cfg["phi"], row_idx=rows)
+    B = inputs.block(cfg["seed"], 1, k, cfg["n"], cfg["phi"], col_idx=cols)
+    Cx, S = orc.exact(A, B)
+    native = np.max(np.abs(A @ B - Cx) / S)
+    errs = {}
+    for N in range(8, 21):
+        r = orc.dgemm(A, B, N, want=("C", "shifts"))
+        err = np.abs(r.C - Cx)
+        # truncation bound from the scaling equations: each a' differs from a*2^sa by less than one unit;
+        # plus one final rounding of the result and one of the reference
+        sumA = np.sum(np.abs(A), axis=1)[:, None]
+        sumB = np.sum(np.abs(B), axis=0)[None, :]
+        ea = np.ldexp(1.0, -r.sa.astype(np.int64))[:, None]
+        eb = np.ldexp(1.0, -r.sb.astype(np.int64))[None, :]
+        bound = ea * sumB + eb * sumA + k * ea * eb + 2.0**-53 * (np.abs(r.C) + np.abs(Cx))
+        assert np.all(err <= bound * (1 + 1e-12))
+        errs[N] = float(np.max(err / S))
+    # error falls monotonically until it reaches the final-rounding floor
+    for N in range(9, 21):
+        assert errs[N] <= errs[N - 1] * 1.0001 or errs[N] < 2.0**-52
+    assert errs[8] > 1e-9 and errs[20] < 2.0**-53 * 1.01
+    # Section 4.1: at phi = 0.5 fourteen or fifteen moduli reach the accuracy of native FP64
+    assert errs[13] > native
+    assert errs[15] <= 2 * native
+    assert errs[16] < native
+
+
+def test_planted_mistakes_are_caught_by_the_pins():
+    # a Python model of the CRT step with a wrong weight, a wrong sign convention or a missing modulus
+    # fails the identity X == A'B'; this guards the pins themselves against being vacuous
+    A, B = _tiny(41, 3, 3, 5, 0.5)
+    N = 6
+    mods = orc.moduli(N)
+    M, W = orc.crt_constants(N)
+    r = orc.dgemm(A, B, N, want=("Ap", "Bp", "Cres", "X"))
+
+    def rebuild(weights, residues, symmetric=True):
+        out = []
+        for i in range(3):
+            row = []
+            for j in range(3):
+                y = sum(int(residues[t, i, j]) * weights[t] for t in range(N)) % M
+                if symmetric and y >= M - M // 2:
+                    y -= M
+                row.append(y)
+            out.append(row)
+        return out
+
+    assert rebuild(W, r.Cres) == r.X
+    bad_w = list(W)
+    bad_w[2] += M // mods[2]
+    assert rebuild(bad_w, r.Cres) != r.X
+    assert rebuild(W, r.Cres, symmetric=False) != r.X
+    shifted = r.Cres.copy()
+    shifted[1] = (shifted[1].astype(np.int64) + 1) % mods[1]
+    assert rebuild(W, shifted) != r.X
