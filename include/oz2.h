@@ -1,0 +1,107 @@
+/* oz2.h -- C ABI of the MI355X (gfx950) library for Ozaki scheme II: FP64 matrix multiplication
+ * C = A*B emulated with INT8 matrix products and the Chinese Remainder Theorem
+ * (arXiv 2504.08009, Algorithm 1 and Sections 2.3, 3, 3.1).
+ *
+ * Conventions for every call
+ *   - Matrices are column-major with leading dimensions (BLAS convention).
+ *   - A, B, C and the workspace are DEVICE pointers owned by the caller; the library never frees them.
+ *     A and B are read-only, C is overwritten, A/B must not overlap C or the workspace.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls only enqueue work;
+ *     they return without waiting for the GPU.
+ *   - Return value: 0 success; -i = the i-th argument is invalid (1-based, LAPACK style);
+ *     OZ2_ERR_WORKSPACE (1) workspace missing or too small; OZ2_ERR_BUDGET (2) the moduli product is
+ *     too small for this inner dimension (kappa < 1); OZ2_ERR_HIP (3) a HIP call failed.
+ *     Nothing is printed and nothing throws across this boundary.
+ *   - Inputs must be finite.  NaN, infinities and signed zeros are outside the method (Section 3, last
+ *     paragraph); so are inputs whose scaled products leave the FP64 exponent range.
+ *   - The library keeps one workspace registration per process (oz2_set_workspace).  Calls that use it
+ *     must not overlap in time on different streams.
+ */
+#ifndef OZ2_H
+#define OZ2_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define OZ2_OK 0
+#define OZ2_ERR_WORKSPACE 1
+#define OZ2_ERR_BUDGET 2
+#define OZ2_ERR_HIP 3
+
+/* Smallest and largest supported number of moduli (Section 3.1: the table starts at s = 2). */
+int oz2_min_moduli(void);
+int oz2_max_moduli(void);
+
+/* Moduli table and bit budget (Section 3.1, "largest possible" pairwise-coprime values <= 256, taken
+ * greedily downwards from 256; Section 3, the second equation for k_A = k_B evaluated with integers:
+ * the largest kappa with k * 4^kappa <= M/2 - 1).
+ * moduli_out: host array of num_moduli ints, or NULL.  kappa_out: host int, or NULL; receives -1 when
+ * even kappa = 0 breaks the bound.  k >= 1.  Returns 0 or a negative argument code. */
+int oz2_get_moduli(int num_moduli, int* moduli_out, int* kappa_out, int64_t k);
+
+/* Workspace size in bytes for a problem, 0 on invalid arguments.  Holds the shift vectors, the INT8
+ * residue planes of A and B and the INT32 product planes (Algorithm 1, lines 1-6). */
+size_t oz2_workspace_bytes(int64_t m, int64_t n, int64_t k, int num_moduli);
+
+/* Register a caller-owned device buffer (256-byte aligned) as the workspace for later calls.
+ * NULL/0 unregisters.  Returns 0 or -1 (bad alignment or NULL with nonzero size). */
+int oz2_set_workspace(void* dev_ptr, size_t bytes);
+
+/* Where each intermediate lives inside the workspace, so that a test can read every stage's output.
+ * offsets[0..6] (bytes from the workspace start):
+ *   0 rowmax  : m_pad uint64, bit pattern of max_l |a_il| per row of A
+ *   1 colmax  : n_pad uint64, same per column of B
+ *   2 sa      : m_pad int32 shifts of A's rows      (Algorithm 1 line 1)
+ *   3 sb      : n_pad int32 shifts of B's columns
+ *   4 A planes: num_moduli x m_pad x k_pad int8, plane t row i at ((t*m_pad)+i)*k_pad, k contiguous
+ *   5 B planes: num_moduli x n_pad x k_pad int8, plane t column j at ((t*n_pad)+j)*k_pad, k contiguous
+ *   6 C planes: num_moduli x n_pad x m_pad int32, plane t element (i,j) at ((t*n_pad)+j)*m_pad + i
+ * dims[0..2] = m_pad, n_pad, k_pad (m, n rounded up to the GEMM tile, k to the k-tile; padding holds
+ * zeros).  Returns 0 or a negative argument code. */
+int oz2_workspace_layout(int64_t m, int64_t n, int64_t k, int num_moduli, size_t offsets[7], int64_t dims[3]);
+
+/* The whole of Algorithm 1:  C := A*B  with num_moduli INT8 products.
+ *   A: m x k, lda >= max(1,m);  B: k x n, ldb >= max(1,k);  C: m x n, ldc >= max(1,m).
+ * m == 0 or n == 0: nothing to do.  k == 0: C := 0.  Needs a registered workspace of at least
+ * oz2_workspace_bytes(m,n,k,num_moduli).  Row-major callers pass (n,m,k,B,ldb,A,lda,C,ldc). */
+int oz2_dgemm(int64_t m, int64_t n, int64_t k, const double* A, int64_t lda, const double* B, int64_t ldb,
+              double* C, int64_t ldc, int num_moduli, void* stream);
+
+/* The three device stages of oz2_dgemm as separate calls (same kernels, same workspace); running them
+ * in order is identical to oz2_dgemm.  They exist so that each stage can be tested and timed alone.
+ *   oz2_stage1_convert : Algorithm 1 lines 1-5 (shifts, truncation, INT8 residues of A and B)
+ *   oz2_stage2_gemm    : line 6 (INT32 products of the residue planes, all moduli)
+ *   oz2_stage3_crt     : lines 7-11 (residues of the products, CRT accumulation, mod M, inverse scaling) */
+int oz2_stage1_convert(int64_t m, int64_t n, int64_t k, const double* A, int64_t lda, const double* B,
+                       int64_t ldb, int num_moduli, void* stream);
+int oz2_stage2_gemm(int64_t m, int64_t n, int64_t k, int num_moduli, void* stream);
+int oz2_stage3_crt(int64_t m, int64_t n, int64_t k, double* C, int64_t ldc, int num_moduli, void* stream);
+
+/* Inner-dimension block length for line 6.  INT32 accumulation is exact for fewer than 2^17 terms
+ * (Section 3.1); longer inner dimensions are processed in blocks and the accumulators are reduced
+ * modulo p_t between blocks.  kblock must be a positive multiple of 128 and at most 65536 (the default).
+ * With blocking active the INT32 planes hold a value congruent to the exact product modulo p_t.
+ * Returns 0 or -1. */
+int oz2_set_kblock(int64_t kblock);
+
+/* Host-side evaluation of the device routine for lines 7-10 and the final rounding (same source,
+ * compiled for the host), for unit tests of the exact-arithmetic design: given the num_moduli INT32
+ * products of one output element it returns the double nearest to X = (sum_t c''_t W_t) mod M and
+ * writes nothing else.  No GPU is touched.  Returns 0 or a negative argument code. */
+int oz2_host_crt_element(int num_moduli, const int32_t* cprod, double* x_out);
+
+/* Host-side evaluation of the device routine for lines 2-5 on one element: residues of
+ * trunc(a * 2^shift) for all moduli (int8, num_moduli entries).  kappa tells the routine which of its
+ * two splitting depths to use, as the kernels do.  No GPU is touched. */
+int oz2_host_residues(int num_moduli, int kappa, double a, int shift, int8_t* res_out);
+
+const char* oz2_status_string(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* OZ2_H */

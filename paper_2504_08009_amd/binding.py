@@ -1,0 +1,161 @@
+"""ctypes binding of liboz2.so.  Function names follow include/oz2.h; arguments are marshalled only."""
+import ctypes
+import os
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "liboz2.so")
+_lib = None
+
+SYMBOLS = [
+    "oz2_min_moduli", "oz2_max_moduli", "oz2_get_moduli", "oz2_workspace_bytes", "oz2_set_workspace",
+    "oz2_workspace_layout", "oz2_dgemm", "oz2_stage1_convert", "oz2_stage2_gemm", "oz2_stage3_crt",
+    "oz2_set_kblock", "oz2_host_crt_element", "oz2_host_residues", "oz2_status_string",
+]
+
+
+class Oz2Error(RuntimeError):
+    pass
+
+
+def lib():
+    """Load liboz2.so (built by paper_2504_08009_amd/build.py).  Raises if it has not been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_LIB_PATH):
+            raise Oz2Error("liboz2.so is missing: run `python -c 'import __graft_entry__ as g; g.build()'` first")
+        L = ctypes.CDLL(_LIB_PATH)
+        i64, vp, ci = ctypes.c_int64, ctypes.c_void_p, ctypes.c_int
+        L.oz2_get_moduli.argtypes = [ci, vp, vp, i64]
+        L.oz2_workspace_bytes.restype = ctypes.c_size_t
+        L.oz2_workspace_bytes.argtypes = [i64, i64, i64, ci]
+        L.oz2_set_workspace.argtypes = [vp, ctypes.c_size_t]
+        L.oz2_workspace_layout.argtypes = [i64, i64, i64, ci, vp, vp]
+        L.oz2_dgemm.argtypes = [i64, i64, i64, vp, i64, vp, i64, vp, i64, ci, vp]
+        L.oz2_stage1_convert.argtypes = [i64, i64, i64, vp, i64, vp, i64, ci, vp]
+        L.oz2_stage2_gemm.argtypes = [i64, i64, i64, ci, vp]
+        L.oz2_stage3_crt.argtypes = [i64, i64, i64, vp, i64, ci, vp]
+        L.oz2_set_kblock.argtypes = [i64]
+        L.oz2_host_crt_element.argtypes = [ci, vp, vp]
+        L.oz2_host_residues.argtypes = [ci, ci, ctypes.c_double, ci, vp]
+        L.oz2_status_string.restype = ctypes.c_char_p
+        L.oz2_status_string.argtypes = [ci]
+        _lib = L
+    return _lib
+
+
+def _check(rc, what):
+    if rc != 0:
+        raise Oz2Error("%s failed: status %d (%s)" % (what, rc, lib().oz2_status_string(rc).decode()))
+
+
+def min_moduli():
+    return lib().oz2_min_moduli()
+
+
+def max_moduli():
+    return lib().oz2_max_moduli()
+
+
+def get_moduli(num_moduli, k=1):
+    """(moduli list, kappa) for this moduli count and inner dimension."""
+    mods = (ctypes.c_int * num_moduli)()
+    kap = ctypes.c_int(0)
+    _check(lib().oz2_get_moduli(num_moduli, mods, ctypes.byref(kap), k), "oz2_get_moduli")
+    return list(mods), kap.value
+
+
+def workspace_bytes(m, n, k, num_moduli):
+    return int(lib().oz2_workspace_bytes(m, n, k, num_moduli))
+
+
+def workspace_layout(m, n, k, num_moduli):
+    """dict of byte offsets and padded dims (see include/oz2.h)."""
+    offs = (ctypes.c_size_t * 7)()
+    dims = (ctypes.c_int64 * 3)()
+    _check(lib().oz2_workspace_layout(m, n, k, num_moduli, offs, dims), "oz2_workspace_layout")
+    names = ["rowmax", "colmax", "sa", "sb", "a_planes", "b_planes", "c_planes"]
+    out = {nm: int(o) for nm, o in zip(names, offs)}
+    out.update(m_pad=int(dims[0]), n_pad=int(dims[1]), k_pad=int(dims[2]))
+    return out
+
+
+def set_workspace(dev_ptr, nbytes):
+    _check(lib().oz2_set_workspace(dev_ptr, nbytes), "oz2_set_workspace")
+
+
+def oz2_set_kblock(kblock):
+    _check(lib().oz2_set_kblock(kblock), "oz2_set_kblock")
+
+
+def _stream_ptr(stream):
+    if stream is None:
+        import torch
+        stream = torch.cuda.current_stream()
+    return getattr(stream, "cuda_stream", stream)
+
+
+def oz2_dgemm(m, n, k, A_ptr, lda, B_ptr, ldb, C_ptr, ldc, num_moduli, stream=None):
+    _check(lib().oz2_dgemm(m, n, k, A_ptr, lda, B_ptr, ldb, C_ptr, ldc, num_moduli, _stream_ptr(stream)), "oz2_dgemm")
+
+
+def oz2_stage1_convert(m, n, k, A_ptr, lda, B_ptr, ldb, num_moduli, stream=None):
+    _check(lib().oz2_stage1_convert(m, n, k, A_ptr, lda, B_ptr, ldb, num_moduli, _stream_ptr(stream)),
+           "oz2_stage1_convert")
+
+
+def oz2_stage2_gemm(m, n, k, num_moduli, stream=None):
+    _check(lib().oz2_stage2_gemm(m, n, k, num_moduli, _stream_ptr(stream)), "oz2_stage2_gemm")
+
+
+def oz2_stage3_crt(m, n, k, C_ptr, ldc, num_moduli, stream=None):
+    _check(lib().oz2_stage3_crt(m, n, k, C_ptr, ldc, num_moduli, _stream_ptr(stream)), "oz2_stage3_crt")
+
+
+def host_crt_element(num_moduli, cprod):
+    arr = (ctypes.c_int32 * num_moduli)(*[int(c) for c in cprod])
+    out = ctypes.c_double(0.0)
+    _check(lib().oz2_host_crt_element(num_moduli, arr, ctypes.byref(out)), "oz2_host_crt_element")
+    return out.value
+
+
+def host_residues(num_moduli, kappa, a, shift):
+    out = (ctypes.c_int8 * num_moduli)()
+    _check(lib().oz2_host_residues(num_moduli, kappa, float(a), int(shift), out), "oz2_host_residues")
+    return list(out)
+
+
+class Workspace:
+    """A torch-owned device buffer registered with the library (device memory only; no arithmetic)."""
+
+    def __init__(self, m, n, k, num_moduli, device="cuda:0"):
+        import torch
+        self.nbytes = workspace_bytes(m, n, k, num_moduli)
+        if self.nbytes == 0:
+            raise Oz2Error("invalid problem for a workspace")
+        self.buf = torch.empty(self.nbytes + 256, dtype=torch.uint8, device=device)
+        base = self.buf.data_ptr()
+        self.offset = (-base) % 256
+        self.ptr = base + self.offset
+        set_workspace(self.ptr, self.nbytes)
+
+    def view(self, off, count, dtype):
+        """1-D torch view of `count` elements of `dtype` starting `off` bytes into the workspace."""
+        import torch
+        esz = torch.empty((), dtype=dtype).element_size()
+        return self.buf[self.offset + off: self.offset + off + count * esz].view(dtype)
+
+
+def dgemm(A, B, num_moduli, C=None, workspace=None):
+    """C = A @ B for column-major float64 torch tensors on the GPU (A: m x k, B: k x n given as the
+    transposes of contiguous tensors, i.e. A.t().is_contiguous()).  Thin convenience wrapper."""
+    import torch
+    m, k = A.shape
+    k2, n = B.shape
+    assert k == k2 and A.dtype == torch.float64 and B.dtype == torch.float64
+    assert A.t().is_contiguous() and B.t().is_contiguous(), "pass column-major matrices"
+    if C is None:
+        C = torch.empty((n, m), dtype=torch.float64, device=A.device).t()
+    if workspace is None:
+        workspace = Workspace(m, n, k, num_moduli, device=A.device)
+    oz2_dgemm(m, n, k, A.data_ptr(), max(1, m), B.data_ptr(), max(1, k), C.data_ptr(), max(1, m), num_moduli)
+    return C

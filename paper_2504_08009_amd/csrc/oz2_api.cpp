@@ -1,0 +1,237 @@
+// C ABI of liboz2 (see include/oz2.h): argument checks, workspace bookkeeping, stage sequencing.
+#include <mutex>
+
+#include "../../include/oz2.h"
+#include "oz2_internal.h"
+
+namespace {
+
+struct State {
+  std::mutex mu;
+  char* ws = nullptr;
+  size_t ws_bytes = 0;
+  int64_t kblock = 65536;
+  Oz2Plan plan;
+  int plan_N = 0;
+  int64_t plan_k = -1;
+  int plan_rc = 0;
+};
+
+State& state() {
+  static State s;
+  return s;
+}
+
+// cached plan for (N, k); caller holds the mutex
+int get_plan(State& s, int N, int64_t k, const Oz2Plan** out) {
+  if (s.plan_N != N || s.plan_k != k) {
+    s.plan_rc = oz2_build_plan(N, k, &s.plan);
+    s.plan_N = N;
+    s.plan_k = k;
+  }
+  *out = &s.plan;
+  return s.plan_rc;
+}
+
+bool n_ok(int N) { return N >= OZ2_MIN_N && N <= OZ2_MAX_N; }
+
+// grid dimension limits of the kernels
+bool dims_ok(int64_t m, int64_t n, int64_t k) {
+  const int64_t lim = (int64_t)1 << 31;
+  if (m >= lim - 512 || n >= lim - 512 || k >= lim - 512) return false;
+  if ((k + 127) / 128 > 65535) return false;  // second grid dimension of the row-wise kernels
+  if ((m + 511) / 512 > 65535) return false;
+  return true;
+}
+
+int prepare(State& s, int64_t m, int64_t n, int64_t k, int N, const Oz2Plan** plan, Oz2Layout* lay) {
+  int rc = get_plan(s, N, k, plan);
+  if (rc == 2) return OZ2_ERR_BUDGET;
+  if (rc != 0) return -10;
+  oz2_make_layout(m, n, k, N, lay);
+  if (!s.ws || s.ws_bytes < lay->total) return OZ2_ERR_WORKSPACE;
+  return OZ2_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int oz2_min_moduli(void) { return OZ2_MIN_N; }
+int oz2_max_moduli(void) { return OZ2_MAX_N; }
+
+int oz2_get_moduli(int num_moduli, int* moduli_out, int* kappa_out, int64_t k) {
+  if (!n_ok(num_moduli)) return -1;
+  if (k < 1) return -4;
+  if (moduli_out) oz2_table_moduli(num_moduli, moduli_out);
+  if (kappa_out) *kappa_out = oz2_table_kappa(num_moduli, k);
+  return OZ2_OK;
+}
+
+size_t oz2_workspace_bytes(int64_t m, int64_t n, int64_t k, int num_moduli) {
+  if (m < 0 || n < 0 || k < 0 || !n_ok(num_moduli) || !dims_ok(m, n, k)) return 0;
+  Oz2Layout lay;
+  oz2_make_layout(m, n, k, num_moduli, &lay);
+  return lay.total;
+}
+
+int oz2_set_workspace(void* dev_ptr, size_t bytes) {
+  State& s = state();
+  std::lock_guard<std::mutex> lock(s.mu);
+  if ((!dev_ptr && bytes) || (reinterpret_cast<uintptr_t>(dev_ptr) & 255u)) return -1;
+  s.ws = static_cast<char*>(dev_ptr);
+  s.ws_bytes = dev_ptr ? bytes : 0;
+  return OZ2_OK;
+}
+
+int oz2_workspace_layout(int64_t m, int64_t n, int64_t k, int num_moduli, size_t offsets[7], int64_t dims[3]) {
+  if (m < 0) return -1;
+  if (n < 0) return -2;
+  if (k < 0) return -3;
+  if (!n_ok(num_moduli)) return -4;
+  if (!dims_ok(m, n, k)) return -1;
+  if (!offsets) return -5;
+  if (!dims) return -6;
+  Oz2Layout lay;
+  oz2_make_layout(m, n, k, num_moduli, &lay);
+  offsets[0] = lay.off_rowmax;
+  offsets[1] = lay.off_colmax;
+  offsets[2] = lay.off_sa;
+  offsets[3] = lay.off_sb;
+  offsets[4] = lay.off_a;
+  offsets[5] = lay.off_b;
+  offsets[6] = lay.off_c;
+  dims[0] = lay.m_pad;
+  dims[1] = lay.n_pad;
+  dims[2] = lay.k_pad;
+  return OZ2_OK;
+}
+
+int oz2_set_kblock(int64_t kblock) {
+  if (kblock < OZ2_TILE_K || kblock > 65536 || kblock % OZ2_TILE_K) return -1;
+  State& s = state();
+  std::lock_guard<std::mutex> lock(s.mu);
+  s.kblock = kblock;
+  return OZ2_OK;
+}
+
+int oz2_stage1_convert(int64_t m, int64_t n, int64_t k, const double* A, int64_t lda, const double* B, int64_t ldb,
+                       int num_moduli, void* stream) {
+  if (m < 0) return -1;
+  if (n < 0) return -2;
+  if (k < 0) return -3;
+  if (!dims_ok(m, n, k)) return -1;
+  if (lda < (m > 1 ? m : 1)) return -5;
+  if (ldb < (k > 1 ? k : 1)) return -7;
+  if (!n_ok(num_moduli)) return -8;
+  if (m == 0 || n == 0 || k == 0) return OZ2_OK;
+  if (!A) return -4;
+  if (!B) return -6;
+  State& s = state();
+  std::lock_guard<std::mutex> lock(s.mu);
+  const Oz2Plan* plan;
+  Oz2Layout lay;
+  int rc = prepare(s, m, n, k, num_moduli, &plan, &lay);
+  if (rc) return rc;
+  hipError_t e = oz2_launch_stage1(m, n, k, A, lda, B, ldb, *plan, lay, s.ws, static_cast<hipStream_t>(stream));
+  return e == hipSuccess ? OZ2_OK : OZ2_ERR_HIP;
+}
+
+int oz2_stage2_gemm(int64_t m, int64_t n, int64_t k, int num_moduli, void* stream) {
+  if (m < 0) return -1;
+  if (n < 0) return -2;
+  if (k < 0) return -3;
+  if (!dims_ok(m, n, k)) return -1;
+  if (!n_ok(num_moduli)) return -4;
+  if (m == 0 || n == 0 || k == 0) return OZ2_OK;
+  State& s = state();
+  std::lock_guard<std::mutex> lock(s.mu);
+  const Oz2Plan* plan;
+  Oz2Layout lay;
+  int rc = prepare(s, m, n, k, num_moduli, &plan, &lay);
+  if (rc) return rc;
+  hipError_t e = oz2_launch_stage2(*plan, lay, s.ws, s.kblock, static_cast<hipStream_t>(stream));
+  return e == hipSuccess ? OZ2_OK : OZ2_ERR_HIP;
+}
+
+int oz2_stage3_crt(int64_t m, int64_t n, int64_t k, double* C, int64_t ldc, int num_moduli, void* stream) {
+  if (m < 0) return -1;
+  if (n < 0) return -2;
+  if (k < 0) return -3;
+  if (!dims_ok(m, n, k)) return -1;
+  if (ldc < (m > 1 ? m : 1)) return -5;
+  if (!n_ok(num_moduli)) return -6;
+  if (m == 0 || n == 0) return OZ2_OK;
+  if (!C) return -4;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  if (k == 0) return oz2_launch_zero_c(m, n, C, ldc, st) == hipSuccess ? OZ2_OK : OZ2_ERR_HIP;
+  State& s = state();
+  std::lock_guard<std::mutex> lock(s.mu);
+  const Oz2Plan* plan;
+  Oz2Layout lay;
+  int rc = prepare(s, m, n, k, num_moduli, &plan, &lay);
+  if (rc) return rc;
+  hipError_t e = oz2_launch_stage3(m, n, C, ldc, *plan, lay, s.ws, st);
+  return e == hipSuccess ? OZ2_OK : OZ2_ERR_HIP;
+}
+
+int oz2_dgemm(int64_t m, int64_t n, int64_t k, const double* A, int64_t lda, const double* B, int64_t ldb, double* C,
+              int64_t ldc, int num_moduli, void* stream) {
+  if (m < 0) return -1;
+  if (n < 0) return -2;
+  if (k < 0) return -3;
+  if (!dims_ok(m, n, k)) return -1;
+  if (lda < (m > 1 ? m : 1)) return -5;
+  if (ldb < (k > 1 ? k : 1)) return -7;
+  if (ldc < (m > 1 ? m : 1)) return -9;
+  if (!n_ok(num_moduli)) return -10;
+  if (m == 0 || n == 0) return OZ2_OK;
+  if (!C) return -8;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  if (k == 0) return oz2_launch_zero_c(m, n, C, ldc, st) == hipSuccess ? OZ2_OK : OZ2_ERR_HIP;
+  if (!A) return -4;
+  if (!B) return -6;
+  State& s = state();
+  std::lock_guard<std::mutex> lock(s.mu);
+  const Oz2Plan* plan;
+  Oz2Layout lay;
+  int rc = prepare(s, m, n, k, num_moduli, &plan, &lay);
+  if (rc) return rc;
+  if (oz2_launch_stage1(m, n, k, A, lda, B, ldb, *plan, lay, s.ws, st) != hipSuccess) return OZ2_ERR_HIP;
+  if (oz2_launch_stage2(*plan, lay, s.ws, s.kblock, st) != hipSuccess) return OZ2_ERR_HIP;
+  if (oz2_launch_stage3(m, n, C, ldc, *plan, lay, s.ws, st) != hipSuccess) return OZ2_ERR_HIP;
+  return OZ2_OK;
+}
+
+int oz2_host_crt_element(int num_moduli, const int32_t* cprod, double* x_out) {
+  if (!n_ok(num_moduli)) return -1;
+  if (!cprod) return -2;
+  if (!x_out) return -3;
+  Oz2Plan plan;
+  if (oz2_build_plan(num_moduli, 1, &plan) < 0) return -1;  // the CRT tables do not depend on k
+  *x_out = oz2_host_crt_impl(plan.crt, cprod);
+  return OZ2_OK;
+}
+
+int oz2_host_residues(int num_moduli, int kappa, double a, int shift, int8_t* res_out) {
+  if (!n_ok(num_moduli)) return -1;
+  if (kappa < 1 || kappa > 110) return -2;
+  if (!res_out) return -5;
+  Oz2Plan plan;
+  if (oz2_build_plan(num_moduli, 1, &plan) < 0) return -1;
+  plan.conv.two_level = kappa > 75;
+  oz2_host_residues_impl(plan.conv, a, shift, res_out);
+  return OZ2_OK;
+}
+
+const char* oz2_status_string(int status) {
+  switch (status) {
+    case OZ2_OK: return "success";
+    case OZ2_ERR_WORKSPACE: return "workspace not registered or too small";
+    case OZ2_ERR_BUDGET: return "moduli product too small for this inner dimension (kappa < 1)";
+    case OZ2_ERR_HIP: return "HIP call failed";
+    default: return status < 0 ? "invalid argument" : "unknown status";
+  }
+}
+
+}  // extern "C"

@@ -1,0 +1,73 @@
+// Internal declarations shared by the translation units of liboz2 (host side + kernel launchers).
+#ifndef OZ2_INTERNAL_H
+#define OZ2_INTERNAL_H
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#define OZ2_MIN_N 2
+#define OZ2_MAX_N 26   // greedy table 256 ... 139; M < 2^200
+#define OZ2_MAX_L 5    // 40-bit limbs of M
+#define OZ2_LIMB_BITS 40
+
+// GEMM tiling (stage 2): workgroup tile TILE_M x TILE_N, k-tile TILE_K bytes.
+#define OZ2_TILE_M 256
+#define OZ2_TILE_N 256
+#define OZ2_TILE_K 128
+
+// Constants of the conversion kernels (Algorithm 1 lines 2-5), passed by value as a kernel argument.
+struct Oz2ConvConsts {
+  int N;
+  int two_level;             // 1 when kappa is too large for the one-level 2^32 split
+  double p[OZ2_MAX_N];       // moduli as doubles
+  double inv_p[OZ2_MAX_N];   // RN(1/p)
+  double c32[OZ2_MAX_N];     // 2^32 reduced to the symmetric range modulo p
+  double c64[OZ2_MAX_N];     // 2^64 likewise
+};
+
+// Constants of the CRT kernel (Algorithm 1 lines 7-10).
+struct Oz2CrtConsts {
+  int N;
+  int L;                               // number of 40-bit limbs: 40*L >= bit length of M
+  double p[OZ2_MAX_N];
+  double inv_p[OZ2_MAX_N];             // RN(1/p)
+  double half_inv_p[OZ2_MAX_N];        // 0.5 * inv_p
+  double w[OZ2_MAX_N][OZ2_MAX_L];      // limbs of W_t = (M/p_t) * ((M/p_t)^-1 mod p_t), each < 2^40
+  double mlimb[OZ2_MAX_L];             // limbs of M
+  double mhalf[OZ2_MAX_L];             // limbs of M/2
+  double rinv[OZ2_MAX_L];              // RN(2^(40 l) / M)
+};
+
+struct Oz2Plan {
+  int N;
+  int kappa;
+  int moduli[OZ2_MAX_N];
+  Oz2ConvConsts conv;
+  Oz2CrtConsts crt;
+};
+
+// Host constants (oz2_host.cpp).  Returns 0, or -1 for an unsupported N, or 2 when kappa < 1.
+int oz2_build_plan(int N, int64_t k, Oz2Plan* plan);
+int oz2_table_moduli(int N, int* out);
+int oz2_table_kappa(int N, int64_t k);
+
+struct Oz2Layout {
+  int64_t m_pad, n_pad, k_pad;
+  size_t off_rowmax, off_colmax, off_sa, off_sb, off_a, off_b, off_c, total;
+};
+void oz2_make_layout(int64_t m, int64_t n, int64_t k, int N, Oz2Layout* lay);
+
+// Kernel launchers.  Each returns hipSuccess or the launch error.
+hipError_t oz2_launch_stage1(int64_t m, int64_t n, int64_t k, const double* A, int64_t lda, const double* B,
+                             int64_t ldb, const Oz2Plan& plan, const Oz2Layout& lay, char* ws, hipStream_t st);
+hipError_t oz2_launch_stage2(const Oz2Plan& plan, const Oz2Layout& lay, char* ws, int64_t kblock, hipStream_t st);
+hipError_t oz2_launch_stage3(int64_t m, int64_t n, double* C, int64_t ldc, const Oz2Plan& plan,
+                             const Oz2Layout& lay, char* ws, hipStream_t st);
+hipError_t oz2_launch_zero_c(int64_t m, int64_t n, double* C, int64_t ldc, hipStream_t st);
+
+// Host instantiations of the device math (oz2_stage1.hip / oz2_stage3.hip), for unit tests.
+void oz2_host_residues_impl(const Oz2ConvConsts& c, double a, int shift, int8_t* out);
+double oz2_host_crt_impl(const Oz2CrtConsts& c, const int32_t* cprod);
+
+#endif

@@ -1,0 +1,230 @@
+// Stage 1 of Ozaki scheme II on gfx950: Algorithm 1 lines 1-5.
+//   1a  per-row maximum of |A| and per-column maximum of |B| (bit patterns, 64-bit atomic max)
+//   1a' shifts  sa_i = kappa - 1 - floor(log2 max_l |a_il|),  sb_j likewise  (Section 3, D and E)
+//   1b  a' = trunc(a * 2^sa_i) and its symmetric residues modulo every p_t, written as INT8 planes with
+//       the inner dimension contiguous (A'_t row-major, B'_t column-major) and zero padding up to the
+//       GEMM tile sizes.
+// All three are bound by HBM traffic: 8 bytes read per element in 1a, 8 read + N written in 1b.
+#include "oz2_math.h"
+
+namespace {
+
+constexpr int kThreads = 256;
+
+__global__ void __launch_bounds__(kThreads) fill_u64_kernel(unsigned long long* p, int64_t count) {
+  int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+  if (i < count) p[i] = 0ull;
+}
+
+__device__ __forceinline__ unsigned long long abs_bits(double v) {
+  return (unsigned long long)__double_as_longlong(v) & 0x7fffffffffffffffull;
+}
+
+// A is m x k column-major: lanes run along rows (coalesced), each block covers 256 rows x KC columns.
+constexpr int kRowMaxKC = 128;
+__global__ void __launch_bounds__(kThreads) rowmax_kernel(const double* __restrict__ A, int64_t lda, int64_t m,
+                                                          int64_t k, unsigned long long* __restrict__ rowmax) {
+  int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+  if (i >= m) return;
+  int64_t l0 = (int64_t)blockIdx.y * kRowMaxKC;
+  int64_t l1 = l0 + kRowMaxKC < k ? l0 + kRowMaxKC : k;
+  const double* p = A + i + l0 * lda;
+  unsigned long long mx = 0ull;
+  int64_t l = l0;
+  for (; l + 8 <= l1; l += 8) {
+    unsigned long long v[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) v[u] = abs_bits(p[(int64_t)u * lda]);
+#pragma unroll
+    for (int u = 0; u < 8; ++u) mx = v[u] > mx ? v[u] : mx;
+    p += 8 * lda;
+  }
+  for (; l < l1; ++l) {
+    unsigned long long v = abs_bits(*p);
+    mx = v > mx ? v : mx;
+    p += lda;
+  }
+  if (mx) atomicMax(rowmax + i, mx);
+}
+
+// B is k x n column-major: one block per (column, chunk of KC rows); lanes run down the column.
+constexpr int kColMaxKC = 4096;
+__global__ void __launch_bounds__(kThreads) colmax_kernel(const double* __restrict__ B, int64_t ldb, int64_t k,
+                                                          unsigned long long* __restrict__ colmax) {
+  int64_t j = blockIdx.x;
+  int64_t l0 = (int64_t)blockIdx.y * kColMaxKC;
+  const double* p = B + j * ldb;
+  unsigned long long mx = 0ull;
+#pragma unroll 4
+  for (int u = 0; u < kColMaxKC / kThreads; ++u) {
+    int64_t l = l0 + (int64_t)u * kThreads + threadIdx.x;
+    if (l < k) {
+      unsigned long long v = abs_bits(p[l]);
+      mx = v > mx ? v : mx;
+    }
+  }
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) {
+    unsigned long long o = __shfl_xor(mx, off, 64);
+    mx = o > mx ? o : mx;
+  }
+  __shared__ unsigned long long part[kThreads / 64];
+  if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = mx;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+#pragma unroll
+    for (int w = 1; w < kThreads / 64; ++w) mx = part[w] > mx ? part[w] : mx;
+    if (mx) atomicMax(colmax + j, mx);
+  }
+}
+
+// shift = kappa - 1 - floor(log2 max); 0 for an all-zero vector
+__global__ void __launch_bounds__(kThreads) shifts_kernel(const unsigned long long* __restrict__ mx, int* __restrict__ s,
+                                                          int64_t count, int kappa) {
+  int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+  if (i >= count) return;
+  unsigned long long b = mx[i];
+  int out = 0;
+  if (b) {
+    int be = (int)(b >> 52);
+    int e = be ? be - 1023 : (63 - __clzll((long long)b)) - 1074;
+    out = kappa - 1 - e;
+  }
+  s[i] = out;
+}
+
+__device__ __forceinline__ unsigned pack4(int r0, int r1, int r2, int r3) {
+  return (unsigned)(r0 & 0xff) | ((unsigned)(r1 & 0xff) << 8) | ((unsigned)(r2 & 0xff) << 16) | ((unsigned)r3 << 24);
+}
+
+// A (m x k column-major) -> planes [t][i][l], pitch k_pad.  Block: 256 rows x 128 columns; each thread
+// owns one row and walks 16 columns at a time, so every plane gets one 16-byte store per step.
+constexpr int kConvAKC = 128;
+template <bool TWO_LEVEL>
+__global__ void __launch_bounds__(kThreads) convert_a_kernel(const double* __restrict__ A, int64_t lda, int64_t m,
+                                                             int64_t k, int64_t m_pad, int64_t k_pad,
+                                                             const int* __restrict__ sa, int8_t* __restrict__ planes,
+                                                             const Oz2ConvConsts cc) {
+  int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;  // < m_pad by construction of the grid
+  int64_t lbase = (int64_t)blockIdx.y * kConvAKC;
+  const bool row_ok = i < m;
+  const int shift = row_ok ? sa[i] : 0;
+  const size_t plane_stride = (size_t)m_pad * k_pad;
+  for (int step = 0; step < kConvAKC / 16; ++step) {
+    int64_t l0 = lbase + step * 16;
+    Oz2Split xs[16];
+#pragma unroll
+    for (int u = 0; u < 16; ++u) {
+      double a = (row_ok && l0 + u < k) ? A[i + (l0 + u) * lda] : 0.0;
+      xs[u] = oz2_scale_trunc_split<TWO_LEVEL>(a, shift);
+    }
+    int8_t* dst = planes + (size_t)i * k_pad + l0;
+    for (int t = 0; t < cc.N; ++t) {
+      const double p = cc.p[t], ip = cc.inv_p[t], c32 = cc.c32[t], c64 = cc.c64[t];
+      int r[16];
+#pragma unroll
+      for (int u = 0; u < 16; ++u) r[u] = oz2_sym_residue<TWO_LEVEL>(xs[u], p, ip, c32, c64);
+      uint4 v;
+      v.x = pack4(r[0], r[1], r[2], r[3]);
+      v.y = pack4(r[4], r[5], r[6], r[7]);
+      v.z = pack4(r[8], r[9], r[10], r[11]);
+      v.w = pack4(r[12], r[13], r[14], r[15]);
+      *reinterpret_cast<uint4*>(dst + (size_t)t * plane_stride) = v;
+    }
+  }
+}
+
+// B (k x n column-major) -> planes [t][j][l], pitch k_pad.  Block: one column x 4096 rows.  The column
+// segment is read coalesced (one double per lane per load), transposed through LDS so that each thread
+// holds 16 consecutive rows, and every plane gets coalesced 16-byte stores.
+constexpr int kConvBKC = 4096;
+constexpr int kConvBPitch = 18;  // doubles per 16-element group in LDS (144 bytes: conflict-free b128 reads)
+template <bool TWO_LEVEL>
+__global__ void __launch_bounds__(kThreads) convert_b_kernel(const double* __restrict__ B, int64_t ldb, int64_t k,
+                                                             int64_t n, int64_t n_pad, int64_t k_pad,
+                                                             const int* __restrict__ sb, int8_t* __restrict__ planes,
+                                                             const Oz2ConvConsts cc) {
+  __shared__ __attribute__((aligned(16))) double tile[kThreads * kConvBPitch];
+  const int64_t j = blockIdx.x;  // < n_pad
+  const int64_t lbase = (int64_t)blockIdx.y * kConvBKC;
+  const bool col_ok = j < n;
+  const int shift = col_ok ? sb[j] : 0;
+  const double* src = B + j * ldb;
+#pragma unroll 4
+  for (int u = 0; u < kConvBKC / kThreads; ++u) {
+    int e = u * kThreads + threadIdx.x;
+    int64_t l = lbase + e;
+    double v = (col_ok && l < k) ? src[l] : 0.0;
+    tile[(e >> 4) * kConvBPitch + (e & 15)] = v;
+  }
+  __syncthreads();
+  int64_t l0 = lbase + (int64_t)threadIdx.x * 16;
+  if (l0 >= k_pad) return;
+  Oz2Split xs[16];
+  const double* mine = tile + threadIdx.x * kConvBPitch;
+#pragma unroll
+  for (int u = 0; u < 16; ++u) xs[u] = oz2_scale_trunc_split<TWO_LEVEL>(mine[u], shift);
+  const size_t plane_stride = (size_t)n_pad * k_pad;
+  int8_t* dst = planes + (size_t)j * k_pad + l0;
+  for (int t = 0; t < cc.N; ++t) {
+    const double p = cc.p[t], ip = cc.inv_p[t], c32 = cc.c32[t], c64 = cc.c64[t];
+    int r[16];
+#pragma unroll
+    for (int u = 0; u < 16; ++u) r[u] = oz2_sym_residue<TWO_LEVEL>(xs[u], p, ip, c32, c64);
+    uint4 v;
+    v.x = pack4(r[0], r[1], r[2], r[3]);
+    v.y = pack4(r[4], r[5], r[6], r[7]);
+    v.z = pack4(r[8], r[9], r[10], r[11]);
+    v.w = pack4(r[12], r[13], r[14], r[15]);
+    *reinterpret_cast<uint4*>(dst + (size_t)t * plane_stride) = v;
+  }
+}
+
+}  // namespace
+
+hipError_t oz2_launch_stage1(int64_t m, int64_t n, int64_t k, const double* A, int64_t lda, const double* B,
+                             int64_t ldb, const Oz2Plan& plan, const Oz2Layout& lay, char* ws, hipStream_t st) {
+  unsigned long long* rowmax = reinterpret_cast<unsigned long long*>(ws + lay.off_rowmax);
+  unsigned long long* colmax = reinterpret_cast<unsigned long long*>(ws + lay.off_colmax);
+  int* sa = reinterpret_cast<int*>(ws + lay.off_sa);
+  int* sb = reinterpret_cast<int*>(ws + lay.off_sb);
+  int8_t* pa = reinterpret_cast<int8_t*>(ws + lay.off_a);
+  int8_t* pb = reinterpret_cast<int8_t*>(ws + lay.off_b);
+  auto blocks = [](int64_t v, int64_t per) { return (unsigned)((v + per - 1) / per); };
+
+  // rowmax and colmax are adjacent in the workspace only up to alignment: clear them separately
+  hipLaunchKernelGGL(fill_u64_kernel, dim3(blocks(lay.m_pad, kThreads)), dim3(kThreads), 0, st, rowmax, lay.m_pad);
+  hipLaunchKernelGGL(fill_u64_kernel, dim3(blocks(lay.n_pad, kThreads)), dim3(kThreads), 0, st, colmax, lay.n_pad);
+  hipLaunchKernelGGL(rowmax_kernel, dim3(blocks(m, kThreads), blocks(k, kRowMaxKC)), dim3(kThreads), 0, st, A, lda,
+                     m, k, rowmax);
+  hipLaunchKernelGGL(colmax_kernel, dim3((unsigned)n, blocks(k, kColMaxKC)), dim3(kThreads), 0, st, B, ldb, k,
+                     colmax);
+  hipLaunchKernelGGL(shifts_kernel, dim3(blocks(lay.m_pad, kThreads)), dim3(kThreads), 0, st, rowmax, sa, lay.m_pad,
+                     plan.kappa);
+  hipLaunchKernelGGL(shifts_kernel, dim3(blocks(lay.n_pad, kThreads)), dim3(kThreads), 0, st, colmax, sb, lay.n_pad,
+                     plan.kappa);
+  dim3 ga(blocks(lay.m_pad, kThreads), blocks(lay.k_pad, kConvAKC));
+  dim3 gb((unsigned)lay.n_pad, blocks(lay.k_pad, kConvBKC));
+  if (plan.conv.two_level) {
+    hipLaunchKernelGGL(convert_a_kernel<true>, ga, dim3(kThreads), 0, st, A, lda, m, k, lay.m_pad, lay.k_pad, sa, pa,
+                       plan.conv);
+    hipLaunchKernelGGL(convert_b_kernel<true>, gb, dim3(kThreads), 0, st, B, ldb, k, n, lay.n_pad, lay.k_pad, sb, pb,
+                       plan.conv);
+  } else {
+    hipLaunchKernelGGL(convert_a_kernel<false>, ga, dim3(kThreads), 0, st, A, lda, m, k, lay.m_pad, lay.k_pad, sa,
+                       pa, plan.conv);
+    hipLaunchKernelGGL(convert_b_kernel<false>, gb, dim3(kThreads), 0, st, B, ldb, k, n, lay.n_pad, lay.k_pad, sb,
+                       pb, plan.conv);
+  }
+  return hipGetLastError();
+}
+
+void oz2_host_residues_impl(const Oz2ConvConsts& c, double a, int shift, int8_t* out) {
+  if (c.two_level) {
+    Oz2Split s = oz2_scale_trunc_split<true>(a, shift);
+    for (int t = 0; t < c.N; ++t) out[t] = (int8_t)(oz2_sym_residue<true>(s, c.p[t], c.inv_p[t], c.c32[t], c.c64[t]) & 0xff);
+  } else {
+    Oz2Split s = oz2_scale_trunc_split<false>(a, shift);
+    for (int t = 0; t < c.N; ++t) out[t] = (int8_t)(oz2_sym_residue<false>(s, c.p[t], c.inv_p[t], c.c32[t], c.c64[t]) & 0xff);
+  }
+}

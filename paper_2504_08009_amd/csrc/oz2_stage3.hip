@@ -1,0 +1,113 @@
+// Stages 3 and 4 of Ozaki scheme II on gfx950: Algorithm 1 lines 7-11 fused in one pass.
+//   per output element: c''_t = c'_t mod p_t (line 7), Y = sum_t c''_t W_t on 40-bit FP64 limbs (line 9),
+//   X = Y mod M in the symmetric range (line 10), one rounding to FP64 and the exact power-of-two
+//   scaling by 2^-(sa_i + sb_j) (line 11).
+// Bound by HBM traffic: 4N bytes read and 8 written per element.
+#include "oz2_math.h"
+
+namespace {
+
+constexpr int kThreads = 256;
+constexpr int kRowsPerThread = 2;
+
+template <int L>
+__global__ void __launch_bounds__(kThreads) crt_kernel(const int* __restrict__ cplanes, int64_t m_pad, int64_t n_pad,
+                                                       const int* __restrict__ sa, const int* __restrict__ sb,
+                                                       double* __restrict__ C, int64_t ldc, int64_t m, int64_t n,
+                                                       const Oz2CrtConsts cc) {
+  const int64_t j = blockIdx.x;
+  const int64_t i0 = ((int64_t)blockIdx.y * kThreads + threadIdx.x) * kRowsPerThread;
+  if (i0 >= m) return;
+  const size_t plane_stride = (size_t)n_pad * m_pad;
+  const int* src = cplanes + (size_t)j * m_pad + i0;
+
+  double S[kRowsPerThread][L];
+#pragma unroll
+  for (int r = 0; r < kRowsPerThread; ++r)
+#pragma unroll
+    for (int l = 0; l < L; ++l) S[r][l] = 0.0;
+
+  for (int t = 0; t < cc.N; ++t) {
+    int2 c = *reinterpret_cast<const int2*>(src + (size_t)t * plane_stride);
+    const double p = cc.p[t], ip = cc.inv_p[t], hip_ = cc.half_inv_p[t];
+    double r0 = oz2_floor_mod(c.x, p, ip, hip_);
+    double r1 = oz2_floor_mod(c.y, p, ip, hip_);
+#pragma unroll
+    for (int l = 0; l < L; ++l) {
+      const double w = cc.w[t][l];
+      S[0][l] = fma(r0, w, S[0][l]);
+      S[1][l] = fma(r1, w, S[1][l]);
+    }
+  }
+  const int sbj = sb[j];
+#pragma unroll
+  for (int r = 0; r < kRowsPerThread; ++r) {
+    int64_t i = i0 + r;
+    if (i < m) {
+      int e2;
+      double x = oz2_crt_reduce<L>(S[r], cc, &e2);
+      C[i + j * ldc] = ldexp(x, e2 - sa[i] - sbj);
+    }
+  }
+}
+
+__global__ void __launch_bounds__(kThreads) zero_c_kernel(double* __restrict__ C, int64_t ldc, int64_t m) {
+  int64_t i = (int64_t)blockIdx.y * kThreads + threadIdx.x;
+  if (i < m) C[i + (int64_t)blockIdx.x * ldc] = 0.0;
+}
+
+template <int L>
+double host_crt(const Oz2CrtConsts& cc, const int32_t* cprod) {
+  double S[L];
+  for (int l = 0; l < L; ++l) S[l] = 0.0;
+  for (int t = 0; t < cc.N; ++t) {
+    double r = oz2_floor_mod(cprod[t], cc.p[t], cc.inv_p[t], cc.half_inv_p[t]);
+    for (int l = 0; l < L; ++l) S[l] = fma(r, cc.w[t][l], S[l]);
+  }
+  int e2;
+  double x = oz2_crt_reduce<L>(S, cc, &e2);
+  return ldexp(x, e2);
+}
+
+}  // namespace
+
+hipError_t oz2_launch_stage3(int64_t m, int64_t n, double* C, int64_t ldc, const Oz2Plan& plan,
+                             const Oz2Layout& lay, char* ws, hipStream_t st) {
+  const int* cplanes = reinterpret_cast<const int*>(ws + lay.off_c);
+  const int* sa = reinterpret_cast<const int*>(ws + lay.off_sa);
+  const int* sb = reinterpret_cast<const int*>(ws + lay.off_sb);
+  const int64_t per_block = (int64_t)kThreads * kRowsPerThread;
+  dim3 grid((unsigned)n, (unsigned)((m + per_block - 1) / per_block));
+  switch (plan.crt.L) {
+#define OZ2_CASE(LL)                                                                                          \
+  case LL:                                                                                                    \
+    hipLaunchKernelGGL(crt_kernel<LL>, grid, dim3(kThreads), 0, st, cplanes, lay.m_pad, lay.n_pad, sa, sb, C, \
+                       ldc, m, n, plan.crt);                                                                  \
+    break;
+    OZ2_CASE(1)
+    OZ2_CASE(2)
+    OZ2_CASE(3)
+    OZ2_CASE(4)
+    OZ2_CASE(5)
+#undef OZ2_CASE
+    default:
+      return hipErrorInvalidValue;
+  }
+  return hipGetLastError();
+}
+
+hipError_t oz2_launch_zero_c(int64_t m, int64_t n, double* C, int64_t ldc, hipStream_t st) {
+  dim3 grid((unsigned)n, (unsigned)((m + kThreads - 1) / kThreads));
+  hipLaunchKernelGGL(zero_c_kernel, grid, dim3(kThreads), 0, st, C, ldc, m);
+  return hipGetLastError();
+}
+
+double oz2_host_crt_impl(const Oz2CrtConsts& cc, const int32_t* cprod) {
+  switch (cc.L) {
+    case 1: return host_crt<1>(cc, cprod);
+    case 2: return host_crt<2>(cc, cprod);
+    case 3: return host_crt<3>(cc, cprod);
+    case 4: return host_crt<4>(cc, cprod);
+    default: return host_crt<5>(cc, cprod);
+  }
+}

@@ -1,0 +1,217 @@
+"""GPU parity: every stage of the HIP path against the CPU oracle, element by element, through the C ABI.
+
+Bars: shifts, INT8 residue planes and INT32 products bit-exact; final C within 1e-15 * (|A||B|)_ij of the
+oracle (the design aims at bit equality and the tests report it)."""
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+import paper_2504_08009_amd as oz
+from oracle import oracle as orc
+from paper_2504_08009_amd import inputs
+
+
+def _dev(x):
+    """numpy (rows x cols, any order) -> column-major device tensor of the same logical shape"""
+    return torch.from_numpy(np.ascontiguousarray(x.T)).cuda().t()
+
+
+def run_stages(A, B, N, kblock=None):
+    m, k = A.shape
+    _, n = B.shape
+    ws = oz.Workspace(m, n, k, N)
+    lay = oz.workspace_layout(m, n, k, N)
+    dA, dB = _dev(A), _dev(B)
+    dC = torch.full((n, m), float("nan"), dtype=torch.float64, device="cuda").t()
+    if kblock is not None:
+        oz.oz2_set_kblock(kblock)
+    try:
+        print("stage1 m=%d n=%d k=%d N=%d" % (m, n, k, N), flush=True)
+        oz.oz2_stage1_convert(m, n, k, dA.data_ptr(), m, dB.data_ptr(), k, N)
+        torch.cuda.synchronize()
+        print("stage2", flush=True)
+        oz.oz2_stage2_gemm(m, n, k, N)
+        torch.cuda.synchronize()
+        print("stage3", flush=True)
+        oz.oz2_stage3_crt(m, n, k, dC.data_ptr(), m, N)
+        torch.cuda.synchronize()
+    finally:
+        if kblock is not None:
+            oz.oz2_set_kblock(65536)
+    mp, np_, kp = lay["m_pad"], lay["n_pad"], lay["k_pad"]
+    out = dict(
+        sa=ws.view(lay["sa"], mp, torch.int32).cpu().numpy(),
+        sb=ws.view(lay["sb"], np_, torch.int32).cpu().numpy(),
+        Ap=ws.view(lay["a_planes"], N * mp * kp, torch.int8).view(N, mp, kp).cpu().numpy(),
+        Bp=ws.view(lay["b_planes"], N * np_ * kp, torch.int8).view(N, np_, kp).cpu().numpy(),
+        Cp=ws.view(lay["c_planes"], N * np_ * mp, torch.int32).view(N, np_, mp).cpu().numpy(),
+        C=dC.cpu().numpy(),
+    )
+    return out
+
+
+def check_against_oracle(A, B, N, kblock=None, products_exact=True):
+    m, k = A.shape
+    _, n = B.shape
+    got = run_stages(A, B, N, kblock)
+    ref = orc.dgemm(A, B, N, want=("C", "shifts", "Ares", "Bres", "Cprod", "Cres"))
+    assert np.array_equal(got["sa"][:m], ref.sa), "row shifts"
+    assert np.array_equal(got["sb"][:n], ref.sb), "column shifts"
+    assert np.array_equal(got["Ap"][:, :m, :k], ref.Ares), "A residue planes"
+    assert np.array_equal(got["Bp"][:, :n, :k], ref.Bres), "B residue planes"
+    # padding must be zero: the GEMM reads it
+    assert not got["Ap"][:, m:, :].any() and not got["Ap"][:, :, k:].any()
+    assert not got["Bp"][:, n:, :].any() and not got["Bp"][:, :, k:].any()
+    prod = got["Cp"][:, :n, :m].transpose(0, 2, 1).astype(np.int64)
+    if products_exact:
+        assert np.array_equal(prod, ref.Cprod), "INT32 products"
+    else:
+        mods = np.array(orc.moduli(N), dtype=np.int64)[:, None, None]
+        assert np.array_equal(np.mod(prod, mods), ref.Cres.astype(np.int64)), "products modulo p_t"
+    _, S = orc.exact(A, B)
+    err = np.abs(got["C"] - ref.C)
+    assert np.all(err <= 1e-15 * S), "final C tolerance"
+    nbad = int(np.count_nonzero(got["C"] != ref.C))
+    print("C elements differing from the oracle in the last bit or more: %d of %d" % (nbad, m * n), flush=True)
+    assert nbad == 0, "final C not bit-identical"
+    return got, ref
+
+
+def test_c1_all_stages():
+    cfg = inputs.CONFIGS["c1"]
+    A, B = inputs.gemm_inputs(cfg["seed"], cfg["m"], cfg["n"], cfg["k"], cfg["phi"])
+    check_against_oracle(A, B, 14)
+
+
+@pytest.mark.parametrize("m,n,k,N,phi", [
+    (300, 200, 333, 5, 0.5),      # ragged in every dimension, two row tiles
+    (257, 513, 129, 14, 1.0),     # one past the tile in each dimension
+    (64, 40, 1000, 20, 4.0),      # wide exponent range, 4 limbs at the limit
+    (33, 17, 50, 23, 4.0),        # kappa > 75: two-level split, 5 limbs
+    (5, 3, 1, 26, 0.5),           # k = 1, largest moduli count
+    (1, 1, 7, 2, 0.5),            # smallest everything
+])
+def test_ragged_shapes(m, n, k, N, phi):
+    rng = np.random.default_rng(m * 1000 + n)
+    A = (rng.random((m, k)) - 0.5) * np.exp(phi * rng.standard_normal((m, k)))
+    B = (rng.random((k, n)) - 0.5) * np.exp(phi * rng.standard_normal((k, n)))
+    check_against_oracle(A, B, N)
+
+
+def test_zero_rows_columns_and_extreme_exponents():
+    rng = np.random.default_rng(77)
+    m, n, k, N = 70, 90, 200, 16
+    A = rng.standard_normal((m, k))
+    B = rng.standard_normal((k, n))
+    A[3, :] = 0.0
+    B[:, 5] = 0.0
+    A[10, :] *= 2.0**300      # rows and columns of very different scale
+    A[11, :] *= 2.0**-300
+    B[:, 7] *= 2.0**200
+    B[:, 8] *= 2.0**-250
+    A[12, 1:] = 0.0           # a single nonzero in the row
+    A[20, :] = np.ldexp(np.round(rng.standard_normal(k) * 1000), 0)  # integers
+    got, _ = check_against_oracle(A, B, N)
+    assert np.all(got["C"][3, :] == 0.0) and np.all(got["C"][:, 5] == 0.0)
+
+
+def test_dgemm_single_call_equals_stages_and_handles_ld():
+    rng = np.random.default_rng(5)
+    m, n, k, N = 120, 75, 260, 15
+    lda, ldb, ldc = m + 8, k + 3, m + 5
+    Af = np.zeros((lda, k), order="F")
+    Bf = np.zeros((ldb, n), order="F")
+    Af[:m, :] = rng.standard_normal((m, k))
+    Bf[:k, :] = rng.standard_normal((k, n))
+    Af[m:, :] = 1e300   # must never be read as data
+    Bf[k:, :] = 1e300
+    dA = torch.from_numpy(np.ascontiguousarray(Af.T)).cuda()   # (k, lda) contiguous == column-major lda x k
+    dB = torch.from_numpy(np.ascontiguousarray(Bf.T)).cuda()
+    dC = torch.full((n, ldc), -7.0, dtype=torch.float64, device="cuda")
+    ws = oz.Workspace(m, n, k, N)
+    oz.oz2_dgemm(m, n, k, dA.data_ptr(), lda, dB.data_ptr(), ldb, dC.data_ptr(), ldc, N)
+    torch.cuda.synchronize()
+    C = dC.cpu().numpy().T
+    ref = orc.dgemm(Af[:m, :], Bf[:k, :], N).C
+    assert np.array_equal(C[:m, :], ref)
+    assert np.all(C[m:, :] == -7.0)   # rows beyond m of the ldc-padded output untouched
+    del ws
+
+
+def test_quick_returns_and_errors():
+    ws = oz.Workspace(8, 8, 8, 4)
+    dC = torch.full((4, 6), 3.0, dtype=torch.float64, device="cuda")
+    L = oz.lib()
+    st = torch.cuda.current_stream().cuda_stream
+    # k == 0: C := 0
+    assert L.oz2_dgemm(6, 4, 0, None, 6, None, 1, dC.data_ptr(), 6, 4, st) == 0
+    torch.cuda.synchronize()
+    assert torch.all(dC == 0.0)
+    # m == 0 or n == 0: nothing happens
+    assert L.oz2_dgemm(0, 4, 5, None, 1, None, 5, None, 1, 4, st) == 0
+    assert L.oz2_dgemm(3, 0, 5, None, 3, None, 5, None, 3, 4, st) == 0
+    # bad arguments
+    assert L.oz2_dgemm(-1, 4, 4, None, 1, None, 4, None, 1, 4, st) == -1
+    assert L.oz2_dgemm(4, 4, 4, dC.data_ptr(), 3, dC.data_ptr(), 4, dC.data_ptr(), 4, 4, st) == -5
+    assert L.oz2_dgemm(4, 4, 4, dC.data_ptr(), 4, dC.data_ptr(), 3, dC.data_ptr(), 4, 4, st) == -7
+    assert L.oz2_dgemm(4, 4, 4, dC.data_ptr(), 4, dC.data_ptr(), 4, dC.data_ptr(), 3, 4, st) == -9
+    assert L.oz2_dgemm(4, 4, 4, dC.data_ptr(), 4, dC.data_ptr(), 4, dC.data_ptr(), 4, 1, st) == -10
+    assert L.oz2_dgemm(4, 4, 4, dC.data_ptr(), 4, dC.data_ptr(), 4, dC.data_ptr(), 4, 27, st) == -10
+    # workspace too small for a bigger problem
+    assert L.oz2_dgemm(600, 600, 600, dC.data_ptr(), 600, dC.data_ptr(), 600, dC.data_ptr(), 600, 8, st) == 1
+    # two moduli cannot carry k = 2^15 (kappa < 1)
+    big = oz.Workspace(4, 4, 1 << 15, 2)
+    assert L.oz2_dgemm(4, 4, 1 << 15, dC.data_ptr(), 4, dC.data_ptr(), 1 << 15, dC.data_ptr(), 4, 2, st) == 2
+    del big, ws
+
+
+def test_k_blocking_matches_unblocked():
+    # the block length is a parameter; blocked accumulation must give the same residues and the same C
+    rng = np.random.default_rng(9)
+    m, n, k, N = 40, 50, 1500, 12
+    A = rng.standard_normal((m, k))
+    B = rng.standard_normal((k, n))
+    base, ref = check_against_oracle(A, B, N)
+    blocked, _ = check_against_oracle(A, B, N, kblock=256, products_exact=False)
+    assert np.array_equal(blocked["C"], base["C"])
+    assert not np.array_equal(blocked["Cp"], base["Cp"])  # the reduction between blocks really ran
+
+
+def test_determinism_two_runs():
+    cfg = inputs.CONFIGS["c1"]
+    A, B = inputs.gemm_inputs(cfg["seed"] + 100, 384, 320, 512, 1.0)
+    r1 = run_stages(A, B, 16)
+    r2 = run_stages(A, B, 16)
+    for key in ("sa", "sb", "Ap", "Bp", "Cp"):
+        assert np.array_equal(r1[key], r2[key])
+    assert np.array_equal(r1["C"].view(np.uint64), r2["C"].view(np.uint64))
+
+
+def test_c2_sampled_rows_and_error_decay():
+    # config 2 at full size on the GPU; the oracle checks a sampled block of outputs for several N
+    cfg = inputs.CONFIGS["c2"]
+    m, n, k = cfg["m"], cfg["n"], cfg["k"]
+    A, B = inputs.gemm_inputs(cfg["seed"], m, n, k, cfg["phi"])
+    rows = np.unique(np.concatenate([np.arange(0, m, 37), [m - 1]]))
+    cols = np.unique(np.concatenate([np.arange(5, n, 41), [0, n - 1]]))
+    Cx, S = orc.exact(A, B, rows=rows, cols=cols)
+    dA, dB = _dev(A), _dev(B)
+    errs = {}
+    for N in (8, 12, 14, 16, 20):
+        ws = oz.Workspace(m, n, k, N)
+        dC = torch.empty((n, m), dtype=torch.float64, device="cuda").t()
+        oz.oz2_dgemm(m, n, k, dA.data_ptr(), m, dB.data_ptr(), k, dC.data_ptr(), m, N)
+        torch.cuda.synchronize()
+        C = dC.cpu().numpy()[np.ix_(rows, cols)]
+        ref = orc.dgemm(A, B, N, rows=rows, cols=cols).C
+        assert np.all(np.abs(C - ref) <= 1e-15 * S)
+        assert np.array_equal(C, ref), "N=%d not bit-identical with the oracle" % N
+        errs[N] = float(np.max(np.abs(C - Cx) / S))
+        del ws
+    native = float(np.max(np.abs((dA @ dB).cpu().numpy()[np.ix_(rows, cols)] - Cx) / S))
+    print("componentwise error vs exact:", errs, "native FP64:", native, flush=True)
+    assert errs[8] > errs[12] > errs[14] > errs[16]
+    assert errs[16] < native
