@@ -1,0 +1,168 @@
+#!/usr/bin/env python3
+"""Benchmark of the Ozaki scheme II FP64 GEMM path on one MI355X.
+
+One "step" = one oz2_dgemm call (all stages of Algorithm 1) on the headline workload
+m = n = k = 16384, phi = 0.5, 16 moduli, inputs resident in HBM.  Prints ONE JSON line.
+
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c4|c3|c2|c1|c5a|c5b] [--moduli N]
+                  [--no-cpu-baseline] [--no-context]
+"""
+import argparse
+import ctypes
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+INT8_MFMA_PEAK_TOPS = 5000.0   # MI355X dense INT8 matrix peak, TOP/s
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="c4")
+    ap.add_argument("--moduli", type=int, default=0)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-context", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (the path needs no exchange between GPUs; "
+              "see DESIGN.md on sharding). Use --gpus 1.", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    import paper_2504_08009_amd as oz
+    from paper_2504_08009_amd import inputs
+
+    cfg = inputs.CONFIGS[args.workload]
+    m, n, k, phi = cfg["m"], cfg["n"], cfg["k"], cfg["phi"]
+    N = args.moduli or (16 if args.workload == "c4" else cfg["N"][len(cfg["N"]) // 2])
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+
+    t0 = time.time()
+    A = inputs.block(cfg["seed"], 0, m, k, phi)
+    B = inputs.block(cfg["seed"], 1, k, n, phi)
+    gen_s = time.time() - t0
+    dA = torch.from_numpy(A.T).to(dev).t()   # A is column-major: A.T is a C-contiguous view
+    dB = torch.from_numpy(B.T).to(dev).t()
+    dC = torch.empty((n, m), dtype=torch.float64, device=dev).t()
+    ws = oz.Workspace(m, n, k, N, device=dev)
+    stream = torch.cuda.current_stream()
+
+    hip = ctypes.CDLL("libamdhip64.so")
+    def new_event():
+        ev = ctypes.c_void_p()
+        rc = hip.hipEventCreate(ctypes.byref(ev))
+        assert rc == 0, "hipEventCreate failed"
+        return ev
+    def elapsed(a, b):
+        ms = ctypes.c_float()
+        rc = hip.hipEventElapsedTime(ctypes.byref(ms), a, b)
+        assert rc == 0, "hipEventElapsedTime failed"
+        return ms.value
+
+    def step(events=None):
+        oz.oz2_set_stage_events(events)
+        oz.oz2_dgemm(m, n, k, dA.data_ptr(), m, dB.data_ptr(), k, dC.data_ptr(), m, N, stream)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    evs = [[new_event() for _ in range(4)] for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for s in range(args.steps):
+        step([e.value for e in evs[s]])
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    oz.oz2_set_stage_events(None)
+
+    stage_ms = np.array([[elapsed(e[i], e[i + 1]) for i in range(3)] for e in evs])
+    avg = stage_ms.mean(axis=0)
+    ms_per_step = wall * 1e3 / args.steps
+    tflops = 2.0 * m * n * k / (ms_per_step * 1e-3) / 1e12
+
+    # dominant kernel: the INT8 GEMM of stage 2 (one launch per step)
+    gemm_ms = float(avg[1])
+    gemm_tops = 2.0 * m * n * k * N / (gemm_ms * 1e-3) / 1e12
+    s1_bytes = (16 + N) * (m * k + k * n) + 4 * (m + n)
+    s3_bytes = (4 * N + 8) * m * n + 4 * (m + n)
+    roofline = {"bound": "mfma", "kernel": "gemm_i8_kernel", "achieved": round(gemm_tops, 2),
+                "peak": INT8_MFMA_PEAK_TOPS, "unit": "TOP/s", "frac": round(gemm_tops / INT8_MFMA_PEAK_TOPS, 4),
+                "traffic": None, "avg_launch_ms": round(gemm_ms, 4)}
+    stages = {
+        "stage1_convert_ms": round(float(avg[0]), 4),
+        "stage2_gemm_ms": round(gemm_ms, 4),
+        "stage3_crt_ms": round(float(avg[2]), 4),
+        "stage1_algorithmic_GBps": round(s1_bytes / (avg[0] * 1e-3) / 1e9, 1),
+        "stage3_algorithmic_GBps": round(s3_bytes / (avg[2] * 1e-3) / 1e9, 1),
+        "hbm_peak_GBps": 8000.0,
+    }
+
+    out = {
+        "metric": "emulated FP64 TFLOPS (2mnk/t) at m=n=k=16384 per #moduli; max rel err",
+        "value": round(tflops, 3), "unit": "TFLOPS", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "int8", "data": "synthetic",
+        "config": {"workload": "%s: m=%d n=%d k=%d phi=%g, %d moduli, seed %d" % (args.workload, m, n, k, phi, N, cfg["seed"]),
+                   "num_moduli": N, "entry_point": "oz2_dgemm", "host_input_generation_s": round(gen_s, 1)},
+        "roofline": roofline, "stages": stages,
+    }
+
+    # accuracy + CPU baseline: the oracle on a bounded sample of the same workload
+    if not args.no_cpu_baseline:
+        from oracle import oracle as orc
+        nr, nc = (1024, 2048) if k >= 8192 else (min(m, 1024), min(n, 1024))
+        rng = np.random.default_rng(1)
+        rows = np.sort(rng.choice(m, size=min(nr, m), replace=False))
+        cols = np.sort(rng.choice(n, size=min(nc, n), replace=False))
+        Asub = np.asfortranarray(A[rows, :])
+        Bsub = np.asfortranarray(B[:, cols])
+        t0 = time.perf_counter()
+        ref = orc.dgemm(Asub, Bsub, N).C
+        cpu_s = time.perf_counter() - t0
+        Cx, S = orc.exact(Asub, Bsub)
+        got = dC[torch.from_numpy(rows).to(dev)][:, torch.from_numpy(cols).to(dev)].cpu().numpy()
+        out["cpu_baseline"] = {
+            "value": round(2.0 * len(rows) * len(cols) * k / cpu_s / 1e12, 6), "unit": "TFLOPS",
+            "cores": min(os.cpu_count() or 1, int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))),
+            "kind": "oracle",
+            "sample": "%d random rows x %d random columns of C, full k=%d, %d moduli: %.1f s" % (len(rows), len(cols), k, N, cpu_s),
+        }
+        out["accuracy"] = {
+            "max_abs_diff_vs_oracle_over_absAabsB": float(np.max(np.abs(got - ref) / S)),
+            "bit_identical_with_oracle": bool(np.array_equal(got, ref)),
+            "max_componentwise_err_vs_exact": float(np.max(np.abs(got - Cx) / S)),
+            "max_rel_err_vs_exact": float(np.max(np.abs(got - Cx) / np.maximum(np.abs(Cx), 1e-300))),
+        }
+
+    if not args.no_context:
+        # context only: native FP64 GEMM of the same shape on the same GPU
+        torch.matmul(dA, dB)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(3):
+            Cn = torch.matmul(dA, dB)
+        e1.record()
+        torch.cuda.synchronize()
+        nat_ms = e0.elapsed_time(e1) / 3
+        out["context"] = {"native_fp64_gemm_TFLOPS_same_gpu": round(2.0 * m * n * k / (nat_ms * 1e-3) / 1e12, 2),
+                          "paper_GH200_OSII_fast_16_n16384_TFLOPS": 70.4, "paper_GH200_DGEMM_n16384_TFLOPS": 60.9}
+        if not args.no_cpu_baseline:
+            gotn = Cn[torch.from_numpy(rows).to(dev)][:, torch.from_numpy(cols).to(dev)].cpu().numpy()
+            out["context"]["native_fp64_max_componentwise_err_vs_exact"] = float(np.max(np.abs(gotn - Cx) / S))
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -81,6 +81,11 @@ int oz2_stage1_convert(int64_t m, int64_t n, int64_t k, const double* A, int64_t
 int oz2_stage2_gemm(int64_t m, int64_t n, int64_t k, int num_moduli, void* stream);
 int oz2_stage3_crt(int64_t m, int64_t n, int64_t k, double* C, int64_t ldc, int num_moduli, void* stream);
 
+/* Optional timing hooks for oz2_dgemm: four caller-owned hipEvent_t handles (as void*), recorded on the
+ * call's stream before stage 1 and after stages 1, 2 and 3 of every later oz2_dgemm call.  The kernels and
+ * their order do not change.  events == NULL switches the hooks off.  Returns 0. */
+int oz2_set_stage_events(void* const events[4]);
+
 /* Inner-dimension block length for line 6.  INT32 accumulation is exact for fewer than 2^17 terms
  * (Section 3.1); longer inner dimensions are processed in blocks and the accumulators are reduced
  * modulo p_t between blocks.  kblock must be a positive multiple of 128 and at most 65536 (the default).

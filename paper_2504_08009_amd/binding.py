@@ -9,7 +9,7 @@ _lib = None
 SYMBOLS = [
     "oz2_min_moduli", "oz2_max_moduli", "oz2_get_moduli", "oz2_workspace_bytes", "oz2_set_workspace",
     "oz2_workspace_layout", "oz2_dgemm", "oz2_stage1_convert", "oz2_stage2_gemm", "oz2_stage3_crt",
-    "oz2_set_kblock", "oz2_host_crt_element", "oz2_host_residues", "oz2_status_string",
+    "oz2_set_kblock", "oz2_set_stage_events", "oz2_host_crt_element", "oz2_host_residues", "oz2_status_string",
 ]
 
 
@@ -35,6 +35,7 @@ def lib():
         L.oz2_stage2_gemm.argtypes = [i64, i64, i64, ci, vp]
         L.oz2_stage3_crt.argtypes = [i64, i64, i64, vp, i64, ci, vp]
         L.oz2_set_kblock.argtypes = [i64]
+        L.oz2_set_stage_events.argtypes = [vp]
         L.oz2_host_crt_element.argtypes = [ci, vp, vp]
         L.oz2_host_residues.argtypes = [ci, ci, ctypes.c_double, ci, vp]
         L.oz2_status_string.restype = ctypes.c_char_p
@@ -85,6 +86,15 @@ def set_workspace(dev_ptr, nbytes):
 
 def oz2_set_kblock(kblock):
     _check(lib().oz2_set_kblock(kblock), "oz2_set_kblock")
+
+
+def oz2_set_stage_events(events):
+    """events: four hipEvent_t handles (ints) or None."""
+    if events is None:
+        _check(lib().oz2_set_stage_events(None), "oz2_set_stage_events")
+    else:
+        arr = (ctypes.c_void_p * 4)(*events)
+        _check(lib().oz2_set_stage_events(arr), "oz2_set_stage_events")
 
 
 def _stream_ptr(stream):

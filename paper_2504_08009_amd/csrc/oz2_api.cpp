@@ -11,6 +11,8 @@ struct State {
   char* ws = nullptr;
   size_t ws_bytes = 0;
   int64_t kblock = 65536;
+  hipEvent_t ev[4] = {nullptr, nullptr, nullptr, nullptr};
+  bool ev_on = false;
   Oz2Plan plan;
   int plan_N = 0;
   int64_t plan_k = -1;
@@ -107,6 +109,14 @@ int oz2_workspace_layout(int64_t m, int64_t n, int64_t k, int num_moduli, size_t
   return OZ2_OK;
 }
 
+int oz2_set_stage_events(void* const events[4]) {
+  State& s = state();
+  std::lock_guard<std::mutex> lock(s.mu);
+  s.ev_on = events != nullptr;
+  for (int i = 0; i < 4; ++i) s.ev[i] = events ? static_cast<hipEvent_t>(events[i]) : nullptr;
+  return OZ2_OK;
+}
+
 int oz2_set_kblock(int64_t kblock) {
   if (kblock < OZ2_TILE_K || kblock > 65536 || kblock % OZ2_TILE_K) return -1;
   State& s = state();
@@ -197,9 +207,11 @@ int oz2_dgemm(int64_t m, int64_t n, int64_t k, const double* A, int64_t lda, con
   Oz2Layout lay;
   int rc = prepare(s, m, n, k, num_moduli, &plan, &lay);
   if (rc) return rc;
-  if (oz2_launch_stage1(m, n, k, A, lda, B, ldb, *plan, lay, s.ws, st) != hipSuccess) return OZ2_ERR_HIP;
-  if (oz2_launch_stage2(*plan, lay, s.ws, s.kblock, st) != hipSuccess) return OZ2_ERR_HIP;
-  if (oz2_launch_stage3(m, n, C, ldc, *plan, lay, s.ws, st) != hipSuccess) return OZ2_ERR_HIP;
+  auto mark = [&](int i) { return !s.ev_on || hipEventRecord(s.ev[i], st) == hipSuccess; };
+  if (!mark(0)) return OZ2_ERR_HIP;
+  if (oz2_launch_stage1(m, n, k, A, lda, B, ldb, *plan, lay, s.ws, st) != hipSuccess || !mark(1)) return OZ2_ERR_HIP;
+  if (oz2_launch_stage2(*plan, lay, s.ws, s.kblock, st) != hipSuccess || !mark(2)) return OZ2_ERR_HIP;
+  if (oz2_launch_stage3(m, n, C, ldc, *plan, lay, s.ws, st) != hipSuccess || !mark(3)) return OZ2_ERR_HIP;
   return OZ2_OK;
 }
 
