@@ -57,11 +57,14 @@ int oz2_set_workspace(void* dev_ptr, size_t bytes);
  *   1 colmax  : n_pad uint64, same per column of B
  *   2 sa      : m_pad int32 shifts of A's rows      (Algorithm 1 line 1)
  *   3 sb      : n_pad int32 shifts of B's columns
- *   4 A planes: num_moduli x m_pad x k_pad int8, plane t row i at ((t*m_pad)+i)*k_pad, k contiguous
- *   5 B planes: num_moduli x n_pad x k_pad int8, plane t column j at ((t*n_pad)+j)*k_pad, k contiguous
+ *   4 A planes: num_moduli x m_pad x k_pad int8 residues of A' (Algorithm 1 line 4), stored in contiguous
+ *               blocks of 256 rows x 64 inner-dimension bytes: element (i, l) of plane t at byte
+ *               ((t*m_pad + 256*(i/256)) * k_pad) + (l/64)*16384 + (i%256)*64 + (l%64)
+ *   5 B planes: num_moduli x n_pad x k_pad int8 residues of B' (line 5), same blocking with the column
+ *               index j of B in the place of i and n_pad in the place of m_pad
  *   6 C planes: num_moduli x n_pad x m_pad int32, plane t element (i,j) at ((t*n_pad)+j)*m_pad + i
- * dims[0..2] = m_pad, n_pad, k_pad (m, n rounded up to the GEMM tile, k to the k-tile; padding holds
- * zeros).  Returns 0 or a negative argument code. */
+ * dims[0..2] = m_pad, n_pad, k_pad (m, n rounded up to 256, k to 64; padding holds zeros).
+ * Returns 0 or a negative argument code. */
 int oz2_workspace_layout(int64_t m, int64_t n, int64_t k, int num_moduli, size_t offsets[7], int64_t dims[3]);
 
 /* The whole of Algorithm 1:  C := A*B  with num_moduli INT8 products.
@@ -88,7 +91,7 @@ int oz2_set_stage_events(void* const events[4]);
 
 /* Inner-dimension block length for line 6.  INT32 accumulation is exact for fewer than 2^17 terms
  * (Section 3.1); longer inner dimensions are processed in blocks and the accumulators are reduced
- * modulo p_t between blocks.  kblock must be a positive multiple of 128 and at most 65536 (the default).
+ * modulo p_t between blocks.  kblock must be a positive multiple of 64 and at most 65536 (the default).
  * With blocking active the INT32 planes hold a value congruent to the exact product modulo p_t.
  * Returns 0 or -1. */
 int oz2_set_kblock(int64_t kblock);

@@ -41,7 +41,7 @@ bool n_ok(int N) { return N >= OZ2_MIN_N && N <= OZ2_MAX_N; }
 bool dims_ok(int64_t m, int64_t n, int64_t k) {
   const int64_t lim = (int64_t)1 << 31;
   if (m >= lim - 512 || n >= lim - 512 || k >= lim - 512) return false;
-  if ((k + 127) / 128 > 65535) return false;  // second grid dimension of the row-wise kernels
+  if ((k + 63) / 64 > 65535) return false;  // second grid dimension of the row-wise kernels
   if ((m + 511) / 512 > 65535) return false;
   return true;
 }

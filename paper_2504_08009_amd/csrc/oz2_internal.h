@@ -14,7 +14,7 @@
 // GEMM tiling (stage 2): workgroup tile TILE_M x TILE_N, k-tile TILE_K bytes.
 #define OZ2_TILE_M 256
 #define OZ2_TILE_N 256
-#define OZ2_TILE_K 128
+#define OZ2_TILE_K 64
 
 // Constants of the conversion kernels (Algorithm 1 lines 2-5), passed by value as a kernel argument.
 struct Oz2ConvConsts {

@@ -1,9 +1,9 @@
 // Stage 1 of Ozaki scheme II on gfx950: Algorithm 1 lines 1-5.
 //   1a  per-row maximum of |A| and per-column maximum of |B| (bit patterns, 64-bit atomic max)
 //   1a' shifts  sa_i = kappa - 1 - floor(log2 max_l |a_il|),  sb_j likewise  (Section 3, D and E)
-//   1b  a' = trunc(a * 2^sa_i) and its symmetric residues modulo every p_t, written as INT8 planes with
-//       the inner dimension contiguous (A'_t row-major, B'_t column-major) and zero padding up to the
-//       GEMM tile sizes.
+//   1b  a' = trunc(a * 2^sa_i) and its symmetric residues modulo every p_t, written as INT8 planes in the
+//       blocked layout the GEMM reads (256 rows x 64 inner-dimension bytes per contiguous block), zero
+//       padded up to the GEMM tile sizes.
 // All three are bound by HBM traffic: 8 bytes read per element in 1a, 8 read + N written in 1b.
 #include "oz2_math.h"
 
@@ -97,28 +97,37 @@ __device__ __forceinline__ unsigned pack4(int r0, int r1, int r2, int r3) {
   return (unsigned)(r0 & 0xff) | ((unsigned)(r1 & 0xff) << 8) | ((unsigned)(r2 & 0xff) << 16) | ((unsigned)r3 << 24);
 }
 
-// A (m x k column-major) -> planes [t][i][l], pitch k_pad.  Block: 256 rows x 128 columns; each thread
-// owns one row and walks 16 columns at a time, so every plane gets one 16-byte store per step.
-constexpr int kConvAKC = 128;
+// Plane layout (shared with the GEMM kernel): blocks of 256 rows x 64 bytes of the inner dimension, each
+// block contiguous; element (row, l) of plane t at
+//   ((t*rows_pad + 256*(row/256)) * k_pad) + (l/64)*16384 + (row%256)*64 + (l%64).
+constexpr int kBlkRows = OZ2_TILE_M;   // 256
+constexpr int kBlkK = OZ2_TILE_K;      // 64
+static_assert(OZ2_TILE_M == 256 && OZ2_TILE_N == 256 && OZ2_TILE_K == 64, "plane layout is 256 x 64 blocks");
+
+// A (m x k column-major) -> planes.  Block: 256 rows x 64 columns = one output block per plane; each
+// thread owns one row and walks 16 columns at a time, so every plane gets one 16-byte store per step and
+// the block's 16 KiB are filled by the same workgroup.
 template <bool TWO_LEVEL>
 __global__ void __launch_bounds__(kThreads) convert_a_kernel(const double* __restrict__ A, int64_t lda, int64_t m,
                                                              int64_t k, int64_t m_pad, int64_t k_pad,
                                                              const int* __restrict__ sa, int8_t* __restrict__ planes,
                                                              const Oz2ConvConsts cc) {
-  int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;  // < m_pad by construction of the grid
-  int64_t lbase = (int64_t)blockIdx.y * kConvAKC;
+  const int64_t rb = blockIdx.x;
+  const int64_t i = rb * kBlkRows + threadIdx.x;  // < m_pad by construction of the grid
+  const int64_t kb = blockIdx.y;
   const bool row_ok = i < m;
   const int shift = row_ok ? sa[i] : 0;
   const size_t plane_stride = (size_t)m_pad * k_pad;
-  for (int step = 0; step < kConvAKC / 16; ++step) {
-    int64_t l0 = lbase + step * 16;
+  int8_t* blk = planes + (size_t)rb * kBlkRows * k_pad + (size_t)kb * (kBlkRows * kBlkK) + threadIdx.x * kBlkK;
+  for (int step = 0; step < kBlkK / 16; ++step) {
+    const int64_t l0 = kb * kBlkK + step * 16;
     Oz2Split xs[16];
 #pragma unroll
     for (int u = 0; u < 16; ++u) {
       double a = (row_ok && l0 + u < k) ? A[i + (l0 + u) * lda] : 0.0;
       xs[u] = oz2_scale_trunc_split<TWO_LEVEL>(a, shift);
     }
-    int8_t* dst = planes + (size_t)i * k_pad + l0;
+    int8_t* dst = blk + step * 16;
     for (int t = 0; t < cc.N; ++t) {
       const double p = cc.p[t], ip = cc.inv_p[t], c32 = cc.c32[t], c64 = cc.c64[t];
       int r[16];
@@ -134,38 +143,46 @@ __global__ void __launch_bounds__(kThreads) convert_a_kernel(const double* __res
   }
 }
 
-// B (k x n column-major) -> planes [t][j][l], pitch k_pad.  Block: one column x 4096 rows.  The column
-// segment is read coalesced (one double per lane per load), transposed through LDS so that each thread
-// holds 16 consecutive rows, and every plane gets coalesced 16-byte stores.
-constexpr int kConvBKC = 4096;
-constexpr int kConvBPitch = 18;  // doubles per 16-element group in LDS (144 bytes: conflict-free b128 reads)
+// B (k x n column-major) -> planes (row index of a plane = column j of B).  Block: 16 columns x 256 rows
+// of B.  Each column segment is read coalesced (one double per lane), transposed through LDS so that a
+// thread holds 16 consecutive inner-dimension values of one column, and wave w writes, for every plane,
+// the 1 KiB that 16 columns x 64 bytes occupy contiguously in the output block of k-tile w.
+constexpr int kConvBCols = 16;
+constexpr int kConvBKC = 256;
+constexpr int kConvBGroup = 18;     // doubles per 16-element group in LDS (144 bytes)
+constexpr int kConvBColPitch = 296; // doubles per column in LDS: 16 groups + 8 (2368 bytes = 64 mod 256)
 template <bool TWO_LEVEL>
 __global__ void __launch_bounds__(kThreads) convert_b_kernel(const double* __restrict__ B, int64_t ldb, int64_t k,
                                                              int64_t n, int64_t n_pad, int64_t k_pad,
                                                              const int* __restrict__ sb, int8_t* __restrict__ planes,
                                                              const Oz2ConvConsts cc) {
-  __shared__ __attribute__((aligned(16))) double tile[kThreads * kConvBPitch];
-  const int64_t j = blockIdx.x;  // < n_pad
+  __shared__ __attribute__((aligned(16))) double tile[kConvBCols * kConvBColPitch];
+  const int64_t j0 = (int64_t)blockIdx.x * kConvBCols;  // < n_pad, multiple of 16
   const int64_t lbase = (int64_t)blockIdx.y * kConvBKC;
-  const bool col_ok = j < n;
-  const int shift = col_ok ? sb[j] : 0;
-  const double* src = B + j * ldb;
+  {
+    const int64_t l = lbase + threadIdx.x;
+    const int slot = (threadIdx.x >> 4) * kConvBGroup + (threadIdx.x & 15);
 #pragma unroll 4
-  for (int u = 0; u < kConvBKC / kThreads; ++u) {
-    int e = u * kThreads + threadIdx.x;
-    int64_t l = lbase + e;
-    double v = (col_ok && l < k) ? src[l] : 0.0;
-    tile[(e >> 4) * kConvBPitch + (e & 15)] = v;
+    for (int c = 0; c < kConvBCols; ++c) {
+      const int64_t j = j0 + c;
+      double v = (j < n && l < k) ? B[l + j * ldb] : 0.0;
+      tile[c * kConvBColPitch + slot] = v;
+    }
   }
   __syncthreads();
-  int64_t l0 = lbase + (int64_t)threadIdx.x * 16;
-  if (l0 >= k_pad) return;
+  const int wv = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int64_t l0 = lbase + wv * kBlkK + (lane & 3) * 16;
+  if (lbase + wv * kBlkK >= k_pad) return;
+  const int c = lane >> 2;
+  const int64_t j = j0 + c;
+  const int shift = j < n ? sb[j] : 0;
   Oz2Split xs[16];
-  const double* mine = tile + threadIdx.x * kConvBPitch;
+  const double* mine = tile + c * kConvBColPitch + (wv * 4 + (lane & 3)) * kConvBGroup;
 #pragma unroll
   for (int u = 0; u < 16; ++u) xs[u] = oz2_scale_trunc_split<TWO_LEVEL>(mine[u], shift);
   const size_t plane_stride = (size_t)n_pad * k_pad;
-  int8_t* dst = planes + (size_t)j * k_pad + l0;
+  int8_t* dst = planes + (size_t)(j / kBlkRows) * kBlkRows * k_pad + (size_t)(l0 / kBlkK) * (kBlkRows * kBlkK) +
+                (j % kBlkRows) * kBlkK + (l0 % kBlkK);
   for (int t = 0; t < cc.N; ++t) {
     const double p = cc.p[t], ip = cc.inv_p[t], c32 = cc.c32[t], c64 = cc.c64[t];
     int r[16];
@@ -203,8 +220,8 @@ hipError_t oz2_launch_stage1(int64_t m, int64_t n, int64_t k, const double* A, i
                      plan.kappa);
   hipLaunchKernelGGL(shifts_kernel, dim3(blocks(lay.n_pad, kThreads)), dim3(kThreads), 0, st, colmax, sb, lay.n_pad,
                      plan.kappa);
-  dim3 ga(blocks(lay.m_pad, kThreads), blocks(lay.k_pad, kConvAKC));
-  dim3 gb((unsigned)lay.n_pad, blocks(lay.k_pad, kConvBKC));
+  dim3 ga((unsigned)(lay.m_pad / kBlkRows), (unsigned)(lay.k_pad / kBlkK));
+  dim3 gb((unsigned)(lay.n_pad / kConvBCols), blocks(lay.k_pad, kConvBKC));
   if (plan.conv.two_level) {
     hipLaunchKernelGGL(convert_a_kernel<true>, ga, dim3(kThreads), 0, st, A, lda, m, k, lay.m_pad, lay.k_pad, sa, pa,
                        plan.conv);

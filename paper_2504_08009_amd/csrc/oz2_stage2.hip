@@ -1,16 +1,26 @@
 // Stage 2 of Ozaki scheme II on gfx950: Algorithm 1 line 6, C'_t = A'_t B'_t for every modulus t with
 // INT8 operands and INT32 accumulation on the matrix cores (v_mfma_i32_32x32x32_i8).
 //
-// Operand layout (written by stage 1): A'_t is m_pad x k_pad with k contiguous, B'_t is n_pad x k_pad with
-// k contiguous, both zero padded to the tile sizes, so the kernel has no edge cases.  Output plane t holds
-// element (i,j) at (j*m_pad + i), i contiguous.
+// Operand layout (written by stage 1): each residue plane is stored in blocks of 256 rows x 64 bytes of
+// the inner dimension, every block contiguous (16 KiB): element (row, l) of plane t lives at
+//   ((t*rows_pad + 256*(row/256)) * k_pad) + (l/64)*16384 + (row%256)*64 + (l%64).
+// Rows and the inner dimension are zero padded to the tile sizes, so the kernel has no edge cases, and
+// every global -> LDS copy of a k-tile reads contiguous kilobytes (a row-major plane with a power-of-two
+// pitch would hit the same L2 channels with all 256 rows of a tile).  Output plane t holds element (i,j)
+// at (j*m_pad + i), i contiguous.
 //
 // One workgroup (4 waves, one per SIMD) computes a 256 x 256 tile of one modulus.  Each wave owns a
 // 128 x 128 sub-tile = 4 x 4 MFMA tiles of 32 x 32 (256 accumulator registers).  The inner dimension is
-// walked in k-tiles of 128 bytes; both operands of a k-tile are copied global -> LDS with 16-byte direct
-// loads (no VGPR staging), double buffered, one barrier per k-tile.  LDS rows are 128 bytes; the 16-byte
-// chunk index is XOR-swizzled with bits 1..3 of the row so that the 16 rows read together by a
-// ds_read_b128 fall on 16 different bank groups.
+// walked in k-tiles of 64 bytes through a ring of four LDS stages (32 KiB each).  Both operands of a
+// k-tile are copied global -> LDS with 16-byte direct loads (no VGPR staging).  LDS rows are 64 bytes; the
+// 16-byte chunk index is XOR-swizzled with bits 2..3 of the row so that the 16 rows read together by a
+// ds_read_b128 fall on 16 different bank groups (measured: no bank conflicts).
+//
+// Schedule of one k-tile (two MFMA k-steps of 16 MFMAs): during step 0 the fragments of step 1 are read
+// from LDS; then one vmcnt wait + barrier makes the NEXT k-tile visible to all waves; during step 1 the
+// first fragments of that next tile are read and the 8 direct loads that refill the stage freed by the
+// barrier are issued, one LDS read per two MFMAs and one global load per two MFMAs, so that no queue
+// fills up and stalls MFMA issue.
 //
 // INT32 accumulation is exact for fewer than 2^17 terms (Section 3.1).  For longer inner dimensions the
 // accumulators are reduced modulo p_t every `kblock` bytes of k (kblock <= 65536), which keeps them below
@@ -19,6 +29,8 @@
 // The 1-D grid is remapped so that each XCD (workgroup id mod 8) walks a contiguous range of tiles, and
 // consecutive tiles of that range form 8-tile-tall column groups: the 32 workgroups resident on an XCD
 // then share A' and B' panels in that XCD's L2.
+#include <type_traits>
+
 #include "oz2_internal.h"
 
 namespace {
@@ -27,9 +39,12 @@ typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v16i __attribute__((ext_vector_type(16)));
 
 constexpr int BM = OZ2_TILE_M, BN = OZ2_TILE_N, BK = OZ2_TILE_K;
+static_assert(BM == 256 && BN == 256 && BK == 64, "the kernel below is written for 256 x 256 x 64 tiles");
 constexpr int kThreads = 256;
-constexpr int kStageBytes = (BM + BN) * BK;      // 64 KiB: A tile then B tile
-constexpr int kLdsBytes = 2 * kStageBytes;       // double buffered
+constexpr int NS = 4;                            // LDS stages
+constexpr int kStageBytes = (BM + BN) * BK;      // 32 KiB: A tile then B tile
+constexpr int kLdsBytes = NS * kStageBytes;
+constexpr int kLoads = 8;                        // direct loads per wave per k-tile
 constexpr int kGroupM = 8;
 
 struct GemmArgs {
@@ -58,6 +73,12 @@ __device__ __forceinline__ void load_to_lds_16(const int8_t* base, unsigned voff
       : "memory");
 }
 
+// s_waitcnt vmcnt(N) only (gfx9 encoding: vmcnt in bits 3:0 and 15:14, expcnt 6:4, lgkmcnt 11:8)
+template <int N>
+__device__ __forceinline__ void wait_vmcnt() {
+  __builtin_amdgcn_s_waitcnt((N & 15) | (7 << 4) | (15 << 8) | ((N >> 4) << 14));
+}
+
 // Any representative of c modulo p with |result| <= 3p is enough between k-blocks: the final residue is
 // taken in stage 3.  The quotient is estimated in FP32 (error below two units).
 __device__ __forceinline__ int reduce_mod(int c, int p, float inv_p) {
@@ -65,13 +86,16 @@ __device__ __forceinline__ int reduce_mod(int c, int p, float inv_p) {
   return c - q * p;
 }
 
+struct Frag {
+  v4i a[4], b[4];
+};
+
 __global__ void __launch_bounds__(kThreads) gemm_i8_kernel(const GemmArgs g) {
   extern __shared__ __attribute__((aligned(1024))) char lds[];
 
   // ---- which tile
   const int wg = blockIdx.x;
-  const int idx = wg >> 3;
-  const int item = (wg & 7) * g.chunk + idx;
+  const int item = (wg & 7) * g.chunk + (wg >> 3);
   if (item >= g.total) return;
   const int per_t = g.tiles_m * g.tiles_n;
   const int t = item / per_t;
@@ -88,41 +112,37 @@ __global__ void __launch_bounds__(kThreads) gemm_i8_kernel(const GemmArgs g) {
   const int wv = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int wm = wv >> 1, wn = wv & 1;
 
-  // ---- global -> LDS copy: wave wv fills rows [64 wv, 64 wv + 64) of both tiles, 8 rows per load.
-  // Lane l of a load covers row (l >> 3) of its 8-row group and the 16-byte chunk that the swizzle
-  // places at physical position (l & 7).
+  // ---- global -> LDS copy: wave wv fills rows [64 wv, 64 wv + 64) of both tiles, 16 rows (1 KiB) per
+  // load.  Lane l covers row (l >> 2) of the group and the chunk that the swizzle puts at position (l & 3).
   const size_t kp = (size_t)g.k_pad;
-  const int8_t* a_wave = g.a + ((size_t)t * g.m_pad + (size_t)tm * BM + wv * 64) * kp;
-  const int8_t* b_wave = g.b + ((size_t)t * g.n_pad + (size_t)tn * BN + wv * 64) * kp;
-  const unsigned voff_even = (unsigned)((lane >> 3) * kp) + (((lane & 7) ^ (lane >> 4)) << 4);
-  const unsigned voff_odd = (unsigned)(((lane >> 3) + 8) * kp) + (((lane & 7) ^ (4 + (lane >> 4))) << 4);
-  const size_t row16 = 16 * kp;
-
+  const int8_t* a_wave = g.a + ((size_t)t * g.m_pad + (size_t)tm * BM) * kp + wv * 64 * BK;
+  const int8_t* b_wave = g.b + ((size_t)t * g.n_pad + (size_t)tn * BN) * kp + wv * 64 * BK;
+  const unsigned voff = (unsigned)((lane >> 2) * BK) + (((lane & 3) ^ (lane >> 4)) << 4);
   const unsigned lds_base = (unsigned)(size_t)(__attribute__((address_space(3))) char*)lds;
-  const unsigned lds_wave = __builtin_amdgcn_readfirstlane(lds_base + wv * 8192);
+  const unsigned lds_wave = __builtin_amdgcn_readfirstlane(lds_base + wv * (64 * BK));
 
-  auto issue = [&](int stage, int kt) {
+  auto gl = [&](int stage, int kt, int q) {  // direct load q in 0..7 of k-tile kt into `stage`
     const unsigned sa = lds_wave + stage * kStageBytes;
-    const unsigned sb = sa + BM * BK;
-    const int8_t* ga = a_wave + (size_t)kt * BK;
-    const int8_t* gb = b_wave + (size_t)kt * BK;
-#pragma unroll
-    for (int q = 0; q < 4; ++q) {
-      load_to_lds_16(ga + q * row16, voff_even, sa + (2 * q) * 1024);
-      load_to_lds_16(ga + q * row16, voff_odd, sa + (2 * q + 1) * 1024);
-    }
-#pragma unroll
-    for (int q = 0; q < 4; ++q) {
-      load_to_lds_16(gb + q * row16, voff_even, sb + (2 * q) * 1024);
-      load_to_lds_16(gb + q * row16, voff_odd, sb + (2 * q + 1) * 1024);
-    }
+    if (q < 4)
+      load_to_lds_16(a_wave + (size_t)kt * (BM * BK) + q * 1024, voff, sa + q * 1024);
+    else
+      load_to_lds_16(b_wave + (size_t)kt * (BN * BK) + (q - 4) * 1024, voff, sa + BM * BK + (q - 4) * 1024);
   };
 
-  // ---- LDS -> fragment addresses
-  const int swz = (lane >> 1) & 7;
+  // ---- LDS -> fragments: lane reads row (lane & 31) of a 32-row group, k-chunk (2 s + lane/32)
+  const int swz = (lane >> 2) & 3;
   const int half = lane >> 5;
-  const int a_row_off = (wm * 128 + (lane & 31)) * BK;             // + ti*32*BK
-  const int b_row_off = BM * BK + (wn * 128 + (lane & 31)) * BK;   // + tj*32*BK
+  const int a_row_off = (wm * 128 + (lane & 31)) * BK;
+  const int b_row_off = BM * BK + (wn * 128 + (lane & 31)) * BK;
+  const int off_s0 = ((0 + half) ^ swz) << 4, off_s1 = ((2 + half) ^ swz) << 4;
+  auto rd = [&](Frag& F, const char* base, int coff, int q) {  // read q in 0..7, ordered by first use
+    if (q == 0)
+      F.b[0] = *reinterpret_cast<const v4i*>(base + b_row_off + coff);
+    else if (q <= 4)
+      F.a[q - 1] = *reinterpret_cast<const v4i*>(base + a_row_off + (q - 1) * 32 * BK + coff);
+    else
+      F.b[q - 4] = *reinterpret_cast<const v4i*>(base + b_row_off + (q - 4) * 32 * BK + coff);
+  };
 
   v16i acc[4][4];
 #pragma unroll
@@ -132,41 +152,65 @@ __global__ void __launch_bounds__(kThreads) gemm_i8_kernel(const GemmArgs g) {
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc[x][y][e] = 0;
 
-  const int p_int = (int)g.p[t];
-  const float inv_pf = 1.0f / g.p[t];
+#define OZ2_MFMA(F, q)                                                                                       \
+  acc[(q) >> 2][(q)&3] = __builtin_amdgcn_mfma_i32_32x32x32_i8(F.b[(q) >> 2], F.a[(q)&3], acc[(q) >> 2][(q)&3], 0, 0, 0)
 
-  auto load_frags = [&](const char* base, int s, v4i* af, v4i* bf) {
-    const int coff = (((2 * s + half) ^ swz) << 4);
+  // ---- prologue: k-tiles 0 .. NS-2 in flight, tile 0 visible, its first fragments in registers
 #pragma unroll
-    for (int x = 0; x < 4; ++x) {
-      af[x] = *reinterpret_cast<const v4i*>(base + a_row_off + x * 32 * BK + coff);
-      bf[x] = *reinterpret_cast<const v4i*>(base + b_row_off + x * 32 * BK + coff);
+  for (int pth = 0; pth < NS - 1; ++pth)
+    if (pth < g.ktiles) {
+#pragma unroll
+      for (int q = 0; q < kLoads; ++q) gl(pth, pth, q);
     }
-  };
+  if (g.ktiles >= NS - 1)
+    wait_vmcnt<(NS - 2) * kLoads>();
+  else
+    wait_vmcnt<0>();
+  __syncthreads();
+  Frag F0, F1;
+#pragma unroll
+  for (int q = 0; q < 8; ++q) rd(F0, lds, off_s0, q);
 
-  issue(0, 0);
-  for (int kt0 = 0; kt0 < g.ktiles; kt0 += g.ktiles_per_block) {
-    const int kt1 = kt0 + g.ktiles_per_block < g.ktiles ? kt0 + g.ktiles_per_block : g.ktiles;
-    for (int kt = kt0; kt < kt1; ++kt) {
-      const int stage = kt & 1;
-      __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): this wave's direct loads have landed in LDS
-      __syncthreads();
-      if (kt + 1 < g.ktiles) issue(stage ^ 1, kt + 1);
-      const char* base = lds + stage * kStageBytes;
-      v4i af[2][4], bf[2][4];
-      load_frags(base, 0, af[0], bf[0]);
+  int stage = 0;
+  auto body = [&](int kt, auto more_tag) {
+    constexpr bool more = decltype(more_tag)::value;  // k-tile kt + NS - 1 exists
+    const char* base = lds + stage * kStageBytes;
+    const int nstage = stage + 1 == NS ? 0 : stage + 1;
+    const char* nbase = lds + nstage * kStageBytes;
+    const int lstage = stage == 0 ? NS - 1 : stage - 1;  // stage of tile kt-1 == stage of tile kt+NS-1
+    // step 0: MFMAs on F0, fetch F1 = (tile kt, step 1)
 #pragma unroll
-      for (int s = 0; s < 4; ++s) {
-        __builtin_amdgcn_sched_barrier(0);
-        if (s + 1 < 4) load_frags(base, s + 1, af[(s + 1) & 1], bf[(s + 1) & 1]);
-#pragma unroll
-        for (int tj = 0; tj < 4; ++tj)
-#pragma unroll
-          for (int ti = 0; ti < 4; ++ti)
-            acc[tj][ti] = __builtin_amdgcn_mfma_i32_32x32x32_i8(bf[s & 1][tj], af[s & 1][ti], acc[tj][ti], 0, 0, 0);
-      }
+    for (int q = 0; q < 16; ++q) {
+      OZ2_MFMA(F0, q);
+      if ((q & 1) == 0) rd(F1, base, off_s1, q >> 1);
       __builtin_amdgcn_sched_barrier(0);
     }
+    // k-tile kt+1 must be complete in LDS for every wave before anyone reads it; passing this barrier
+    // also means every wave has finished reading k-tile kt-1, whose stage is refilled below
+    if (more || kt + 2 < g.ktiles)
+      wait_vmcnt<(NS - 3) * kLoads>();
+    else
+      wait_vmcnt<0>();
+    __syncthreads();
+    // step 1: MFMAs on F1, fetch F0 = (tile kt+1, step 0), issue the loads of tile kt+NS-1
+#pragma unroll
+    for (int q = 0; q < 16; ++q) {
+      OZ2_MFMA(F1, q);
+      if ((q & 1) == 0) rd(F0, nbase, off_s0, q >> 1);
+      if ((q & 1) == 1 && more) gl(lstage, kt + NS - 1, q >> 1);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    stage = nstage;
+  };
+
+  const int p_int = (int)g.p[t];
+  const float inv_pf = 1.0f / g.p[t];
+  const int last_full = g.ktiles - (NS - 1);  // k-tiles below this index still have a tile to prefetch
+  for (int kt0 = 0; kt0 < g.ktiles; kt0 += g.ktiles_per_block) {
+    const int kt1 = kt0 + g.ktiles_per_block < g.ktiles ? kt0 + g.ktiles_per_block : g.ktiles;
+    int kt = kt0;
+    for (; kt < kt1 && kt < last_full; ++kt) body(kt, std::true_type{});
+    for (; kt < kt1; ++kt) body(kt, std::false_type{});
     if (kt1 < g.ktiles) {  // between k-blocks: bring the accumulators back near zero
 #pragma unroll
       for (int x = 0; x < 4; ++x)
@@ -176,6 +220,7 @@ __global__ void __launch_bounds__(kThreads) gemm_i8_kernel(const GemmArgs g) {
           for (int e = 0; e < 16; ++e) acc[x][y][e] = reduce_mod(acc[x][y][e], p_int, inv_pf);
     }
   }
+#undef OZ2_MFMA
 
   // ---- epilogue: lane holds i = lane%32 (second operand), registers run over j
   int* c_tile = g.c + ((size_t)t * g.n_pad + (size_t)tn * BN + wn * 128) * g.m_pad + (size_t)tm * BM + wm * 128;

@@ -42,11 +42,17 @@ def run_stages(A, B, N, kblock=None):
         if kblock is not None:
             oz.oz2_set_kblock(65536)
     mp, np_, kp = lay["m_pad"], lay["n_pad"], lay["k_pad"]
+
+    def planes(off, rows_pad):
+        # blocked layout of include/oz2.h: [t][row block][k tile][256 rows][64 bytes] -> [t][row][l]
+        raw = ws.view(off, N * rows_pad * kp, torch.int8).view(N, rows_pad // 256, kp // 64, 256, 64)
+        return raw.permute(0, 1, 3, 2, 4).reshape(N, rows_pad, kp).cpu().numpy()
+
     out = dict(
         sa=ws.view(lay["sa"], mp, torch.int32).cpu().numpy(),
         sb=ws.view(lay["sb"], np_, torch.int32).cpu().numpy(),
-        Ap=ws.view(lay["a_planes"], N * mp * kp, torch.int8).view(N, mp, kp).cpu().numpy(),
-        Bp=ws.view(lay["b_planes"], N * np_ * kp, torch.int8).view(N, np_, kp).cpu().numpy(),
+        Ap=planes(lay["a_planes"], mp),
+        Bp=planes(lay["b_planes"], np_),
         Cp=ws.view(lay["c_planes"], N * np_ * mp, torch.int32).view(N, np_, mp).cpu().numpy(),
         C=dC.cpu().numpy(),
     )
