@@ -104,42 +104,55 @@ constexpr int kBlkRows = OZ2_TILE_M;   // 256
 constexpr int kBlkK = OZ2_TILE_K;      // 64
 static_assert(OZ2_TILE_M == 256 && OZ2_TILE_N == 256 && OZ2_TILE_K == 64, "plane layout is 256 x 64 blocks");
 
-// A (m x k column-major) -> planes.  Block: 256 rows x 64 columns = one output block per plane; each
-// thread owns one row and walks 16 columns at a time, so every plane gets one 16-byte store per step and
-// the block's 16 KiB are filled by the same workgroup.
+// A (m x k column-major) -> planes.  Block: 64 rows x 64 columns.  Every column segment (64 rows, 512
+// bytes) is read coalesced with lanes along the rows, transposed through LDS so that a thread holds 16
+// consecutive inner-dimension values of one row, and wave w writes, for every plane, the 1 KiB that its 16
+// rows x 64 bytes occupy contiguously in the output block.
+constexpr int kConvARows = 64;
+constexpr int kConvAPitch = 65;  // doubles per row in LDS
 template <bool TWO_LEVEL>
 __global__ void __launch_bounds__(kThreads) convert_a_kernel(const double* __restrict__ A, int64_t lda, int64_t m,
                                                              int64_t k, int64_t m_pad, int64_t k_pad,
                                                              const int* __restrict__ sa, int8_t* __restrict__ planes,
                                                              const Oz2ConvConsts cc) {
-  const int64_t rb = blockIdx.x;
-  const int64_t i = rb * kBlkRows + threadIdx.x;  // < m_pad by construction of the grid
+  __shared__ double tile[kConvARows * kConvAPitch];
+  const int64_t r0 = (int64_t)blockIdx.x * kConvARows;  // < m_pad
   const int64_t kb = blockIdx.y;
-  const bool row_ok = i < m;
-  const int shift = row_ok ? sa[i] : 0;
+  const int wv = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  {
+    const int64_t i = r0 + lane;
+    const double* src = A + i;
+#pragma unroll 4
+    for (int c = 0; c < kBlkK / 4; ++c) {
+      const int lc = c * 4 + wv;
+      const int64_t l = kb * kBlkK + lc;
+      double v = (i < m && l < k) ? src[l * lda] : 0.0;
+      tile[lane * kConvAPitch + lc] = v;
+    }
+  }
+  __syncthreads();
+  const int row = wv * 16 + (lane >> 2);
+  const int chunk = lane & 3;
+  const int64_t i = r0 + row;
+  const int shift = i < m ? sa[i] : 0;
+  Oz2Split xs[16];
+  const double* mine = tile + row * kConvAPitch + chunk * 16;
+#pragma unroll
+  for (int u = 0; u < 16; ++u) xs[u] = oz2_scale_trunc_split<TWO_LEVEL>(mine[u], shift);
   const size_t plane_stride = (size_t)m_pad * k_pad;
-  int8_t* blk = planes + (size_t)rb * kBlkRows * k_pad + (size_t)kb * (kBlkRows * kBlkK) + threadIdx.x * kBlkK;
-  for (int step = 0; step < kBlkK / 16; ++step) {
-    const int64_t l0 = kb * kBlkK + step * 16;
-    Oz2Split xs[16];
+  int8_t* dst = planes + (size_t)(i / kBlkRows) * kBlkRows * k_pad + (size_t)kb * (kBlkRows * kBlkK) +
+                (i % kBlkRows) * kBlkK + chunk * 16;
+  for (int t = 0; t < cc.N; ++t) {
+    const double p = cc.p[t], ip = cc.inv_p[t], c32 = cc.c32[t], c64 = cc.c64[t];
+    int r[16];
 #pragma unroll
-    for (int u = 0; u < 16; ++u) {
-      double a = (row_ok && l0 + u < k) ? A[i + (l0 + u) * lda] : 0.0;
-      xs[u] = oz2_scale_trunc_split<TWO_LEVEL>(a, shift);
-    }
-    int8_t* dst = blk + step * 16;
-    for (int t = 0; t < cc.N; ++t) {
-      const double p = cc.p[t], ip = cc.inv_p[t], c32 = cc.c32[t], c64 = cc.c64[t];
-      int r[16];
-#pragma unroll
-      for (int u = 0; u < 16; ++u) r[u] = oz2_sym_residue<TWO_LEVEL>(xs[u], p, ip, c32, c64);
-      uint4 v;
-      v.x = pack4(r[0], r[1], r[2], r[3]);
-      v.y = pack4(r[4], r[5], r[6], r[7]);
-      v.z = pack4(r[8], r[9], r[10], r[11]);
-      v.w = pack4(r[12], r[13], r[14], r[15]);
-      *reinterpret_cast<uint4*>(dst + (size_t)t * plane_stride) = v;
-    }
+    for (int u = 0; u < 16; ++u) r[u] = oz2_sym_residue<TWO_LEVEL>(xs[u], p, ip, c32, c64);
+    uint4 v;
+    v.x = pack4(r[0], r[1], r[2], r[3]);
+    v.y = pack4(r[4], r[5], r[6], r[7]);
+    v.z = pack4(r[8], r[9], r[10], r[11]);
+    v.w = pack4(r[12], r[13], r[14], r[15]);
+    *reinterpret_cast<uint4*>(dst + (size_t)t * plane_stride) = v;
   }
 }
 
@@ -220,7 +233,7 @@ hipError_t oz2_launch_stage1(int64_t m, int64_t n, int64_t k, const double* A, i
                      plan.kappa);
   hipLaunchKernelGGL(shifts_kernel, dim3(blocks(lay.n_pad, kThreads)), dim3(kThreads), 0, st, colmax, sb, lay.n_pad,
                      plan.kappa);
-  dim3 ga((unsigned)(lay.m_pad / kBlkRows), (unsigned)(lay.k_pad / kBlkK));
+  dim3 ga((unsigned)(lay.m_pad / kConvARows), (unsigned)(lay.k_pad / kBlkK));
   dim3 gb((unsigned)(lay.n_pad / kConvBCols), blocks(lay.k_pad, kConvBKC));
   if (plan.conv.two_level) {
     hipLaunchKernelGGL(convert_a_kernel<true>, ga, dim3(kThreads), 0, st, A, lda, m, k, lay.m_pad, lay.k_pad, sa, pa,
