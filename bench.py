@@ -30,6 +30,8 @@ def main():
     ap.add_argument("--moduli", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-context", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one plain device copy of A (known size) so that rocprofv3 byte counters can be scaled")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (the path needs no exchange between GPUs; "
@@ -144,6 +146,12 @@ def main():
             "max_componentwise_err_vs_exact": float(np.max(np.abs(got - Cx) / S)),
             "max_rel_err_vs_exact": float(np.max(np.abs(got - Cx) / np.maximum(np.abs(Cx), 1e-300))),
         }
+
+    if args.calibrate_copy:
+        tmp = torch.empty_like(dA)
+        tmp.copy_(dA)   # 8*m*k bytes read, 8*m*k bytes written
+        torch.cuda.synchronize()
+        del tmp
 
     if not args.no_context:
         # context only: native FP64 GEMM of the same shape on the same GPU

@@ -221,3 +221,42 @@ def test_c2_sampled_rows_and_error_decay():
     print("componentwise error vs exact:", errs, "native FP64:", native, flush=True)
     assert errs[8] > errs[12] > errs[14] > errs[16]
     assert errs[16] < native
+
+
+@pytest.mark.parametrize("name,kblock", [("c3", None), ("c5a", None), ("c4", None), ("c5b", 32768)])
+def test_full_size_configs_on_sampled_outputs(name, kblock):
+    """The benchmark configurations at full size through oz2_dgemm (the call bench.py times); the oracle
+    recomputes a sample of output rows and columns (first, last and random ones) with the full inner
+    dimension.  c5b runs with a k-block of 32768 so that the reduction between k-blocks is exercised at
+    k = 65536; the result must still be bit-identical."""
+    cfg = inputs.CONFIGS[name]
+    m, n, k, phi = cfg["m"], cfg["n"], cfg["k"], cfg["phi"]
+    N = 16 if name == "c4" else cfg["N"][-1]
+    print("generating %s: m=%d n=%d k=%d N=%d" % (name, m, n, k, N), flush=True)
+    A = inputs.block(cfg["seed"], 0, m, k, phi)
+    B = inputs.block(cfg["seed"], 1, k, n, phi)
+    rng = np.random.default_rng(3)
+    rows = np.unique(np.concatenate([[0, 255, 256, m - 1], rng.choice(m, 44, replace=False)]))
+    cols = np.unique(np.concatenate([[0, 255, 256, n - 1], rng.choice(n, 44, replace=False)]))
+    dA = torch.from_numpy(A.T).cuda().t()
+    dB = torch.from_numpy(B.T).cuda().t()
+    dC = torch.full((n, m), float("nan"), dtype=torch.float64, device="cuda").t()
+    ws = oz.Workspace(m, n, k, N)
+    if kblock:
+        oz.oz2_set_kblock(kblock)
+    try:
+        print("oz2_dgemm", flush=True)
+        oz.oz2_dgemm(m, n, k, dA.data_ptr(), m, dB.data_ptr(), k, dC.data_ptr(), m, N)
+        torch.cuda.synchronize()
+    finally:
+        oz.oz2_set_kblock(65536)
+    assert not bool(torch.isnan(dC).any())
+    got = dC[torch.from_numpy(rows).cuda()][:, torch.from_numpy(cols).cuda()].cpu().numpy()
+    Asub = np.asfortranarray(A[rows, :])
+    Bsub = np.asfortranarray(B[:, cols])
+    print("oracle on %d x %d outputs" % (len(rows), len(cols)), flush=True)
+    ref = orc.dgemm(Asub, Bsub, N).C
+    _, S = orc.exact(Asub, Bsub)
+    assert np.all(np.abs(got - ref) <= 1e-15 * S)
+    assert np.array_equal(got, ref), "%s: not bit-identical with the oracle" % name
+    del ws

@@ -1,0 +1,189 @@
+"""CPU-only tests of the product library: it loads, exports every symbol that include/oz2.h declares,
+validates arguments, computes the same host constants as the oracle, and its exact-arithmetic element
+routines (the same source the kernels use, compiled for the host) agree with Python big integers on
+random and adversarial inputs.  No GPU call is made here."""
+import ctypes
+import math
+import os
+import random
+import re
+
+import numpy as np
+import pytest
+
+import paper_2504_08009_amd as oz
+from oracle import oracle as orc
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "oz2.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    declared = set(re.findall(r"\b(oz2_[a-z0-9_]+)\s*\(", header))
+    assert len(declared) >= 14
+    lib = oz.lib()
+    for name in sorted(declared):
+        assert hasattr(lib, name), name
+    assert declared == set(oz.binding.SYMBOLS)
+
+
+def test_moduli_and_kappa_match_the_oracle():
+    assert oz.min_moduli() == 2 and oz.max_moduli() == 26
+    for N in range(2, 27):
+        for k in (1, 7, 256, 1024, 4096, 16384, 65536, 1 << 20):
+            mods, kap = oz.get_moduli(N, k)
+            assert mods == orc.moduli(N)
+            assert kap == orc.kappa(N, k)
+
+
+def test_argument_validation_without_gpu():
+    L = oz.lib()
+    assert L.oz2_get_moduli(1, None, None, 5) == -1
+    assert L.oz2_get_moduli(27, None, None, 5) == -1
+    assert L.oz2_get_moduli(5, None, None, 0) == -4
+    assert oz.workspace_bytes(-1, 4, 4, 4) == 0
+    assert oz.workspace_bytes(4, 4, 4, 1) == 0
+    assert oz.workspace_bytes(4, 4, 4, 27) == 0
+    assert L.oz2_set_workspace(None, 16) == -1
+    assert L.oz2_set_workspace(ctypes.c_void_p(0x1001), 4096) == -1   # not 256-byte aligned
+    assert L.oz2_set_workspace(None, 0) == 0
+    assert L.oz2_set_kblock(0) == -1 and L.oz2_set_kblock(100) == -1 and L.oz2_set_kblock(1 << 17) == -1
+    assert L.oz2_set_kblock(65536) == 0
+    # calls that fail before anything is launched
+    assert L.oz2_dgemm(-1, 1, 1, None, 1, None, 1, None, 1, 4, None) == -1
+    assert L.oz2_dgemm(1, -1, 1, None, 1, None, 1, None, 1, 4, None) == -2
+    assert L.oz2_dgemm(1, 1, -1, None, 1, None, 1, None, 1, 4, None) == -3
+    assert L.oz2_dgemm(4, 4, 4, None, 3, None, 4, None, 4, 4, None) == -5
+    assert L.oz2_dgemm(4, 4, 4, None, 4, None, 4, None, 4, 4, None) == -8     # C is NULL
+    assert L.oz2_dgemm(0, 0, 0, None, 1, None, 1, None, 1, 4, None) == 0      # empty: nothing to do
+    assert L.oz2_stage2_gemm(4, 4, 4, 4, None) == 1                          # no workspace registered
+    assert oz.lib().oz2_status_string(1).decode().startswith("workspace")
+    assert oz.lib().oz2_status_string(-3).decode() == "invalid argument"
+
+
+def test_workspace_layout_is_consistent():
+    for (m, n, k, N) in [(1, 1, 1, 2), (300, 200, 100, 3), (256, 256, 64, 14), (16384, 16384, 16384, 16)]:
+        lay = oz.workspace_layout(m, n, k, N)
+        mp, npad, kp = lay["m_pad"], lay["n_pad"], lay["k_pad"]
+        assert mp % 256 == 0 and npad % 256 == 0 and kp % 64 == 0
+        assert mp >= m and npad >= n and kp >= k and mp - m < 256 and kp - k < 64
+        order = ["rowmax", "colmax", "sa", "sb", "a_planes", "b_planes", "c_planes"]
+        sizes = [8 * mp, 8 * npad, 4 * mp, 4 * npad, N * mp * kp, N * npad * kp, 4 * N * npad * mp]
+        for a, b, sz in zip(order, order[1:], sizes):
+            assert lay[a] % 256 == 0 and lay[a] + sz <= lay[b]
+        assert lay["c_planes"] + sizes[-1] <= oz.workspace_bytes(m, n, k, N)
+    assert oz.workspace_bytes(16384, 16384, 16384, 16) < 25 * 2**30
+
+
+# ----------------------------------------------------------------------------------------------
+# Algorithm 1 lines 2-5 on one element: the FP64 split-and-reduce routine against exact integers
+# ----------------------------------------------------------------------------------------------
+def _exact_residues(a, shift, mods):
+    from fractions import Fraction
+    ap = math.trunc(Fraction(a) * Fraction(2) ** shift)
+    return [orc.sym_mod(ap, p) if abs(ap) < 2**62 else _sym_big(ap, p) for p in mods]
+
+
+def _sym_big(x, p):
+    r = x % p
+    if 2 * r >= p:
+        r -= p
+    return r
+
+
+@pytest.mark.parametrize("N,kappa", [(8, 26), (14, 50), (16, 55), (20, 72), (20, 75), (22, 80), (26, 99)])
+def test_host_residues_match_exact_integers(N, kappa):
+    mods = orc.moduli(N)
+    rng = random.Random(1000 * N + kappa)
+    cases = []
+    for _ in range(3000):
+        e = rng.randint(-40, 40)
+        a = math.ldexp(rng.random() + 1.0, e) * rng.choice((-1, 1))       # |a| in [2^e, 2^(e+1))
+        emax = e + rng.randint(0, 60)                                      # row maximum exponent
+        cases.append((a, kappa - 1 - emax))
+    # adversarial: full 53-bit mantissas at the top of the range, values that land on multiples of p,
+    # on p/2 boundaries and on +-128 modulo 256
+    top = (2**53 - 1) / 2**52
+    cases += [(top, kappa - 1), (-top, kappa - 1), (1.0, kappa - 1), (1.0, 0), (0.0, 5), (-0.0, 5)]
+    for p in mods:
+        for mult in (1, 2, 3, 1000003):
+            for delta in (0, 1, -1, p // 2, -(p // 2), p // 2 + 1):
+                v = p * mult + delta
+                if abs(v) < 2**min(kappa, 52):
+                    cases.append((float(v), 0))
+    for v in (128.0, -128.0, 384.0, -384.0, 127.0, -129.0, 2.0**40 + 128, -(2.0**40) - 128):
+        cases.append((v, 0))
+    for a, shift in cases:
+        got = oz.host_residues(N, kappa, a, shift)
+        want = _exact_residues(a, shift, mods)
+        want8 = [((w + 128) % 256) - 128 for w in want]   # INT8 wrap-around of +128 for p = 256
+        assert got == want8, (a, shift, got, want8)
+        for g, p in zip(got, mods):
+            assert -128 <= g <= 127 and (p == 256 or abs(g) <= (p - 1) // 2)
+
+
+# ----------------------------------------------------------------------------------------------
+# Algorithm 1 lines 7-11 on one element: residues of INT32 products -> double nearest to X
+# ----------------------------------------------------------------------------------------------
+def _crt_cases(N, rng):
+    mods = orc.moduli(N)
+    M = math.prod(mods)
+    half = M // 2
+    xs = []
+    for _ in range(4000):
+        xs.append(rng.randrange(-half, half))
+        b = rng.randrange(1, M.bit_length())
+        xs.append(rng.randrange(-(2**b), 2**b) % M - (M if rng.random() < 0.5 else 0))
+    # range boundaries (Section 3: X in [-M/2, M/2)), zero, small values, powers of two
+    xs += [0, 1, -1, half - 1, -half, -half + 1, half - 2, 2, -2]
+    for b in range(0, M.bit_length() - 1):
+        for d in (-1, 0, 1):
+            xs += [2**b + d, -(2**b) + d]
+    # rounding ties and near-ties: 54-bit patterns times a power of two, plus or minus one
+    for _ in range(3000):
+        mant = (rng.getrandbits(52) | (1 << 52)) * 2 + 1          # odd 54-bit integer: an exact tie
+        sh = rng.randrange(0, max(1, M.bit_length() - 56))
+        for d in (0, 1, -1, 2**max(sh - 1, 0), -(2**max(sh - 1, 0))):
+            xs.append(mant * 2**sh + d)
+            xs.append(-(mant * 2**sh) + d)
+    # digit boundaries of the 40-bit limb representation
+    for l in range(1, (M.bit_length() + 39) // 40):
+        for d in (-2, -1, 0, 1, 2):
+            for mul in (1, 3, 2**39, 2**39 + 1, 2**39 - 1):
+                xs.append(mul * 2**(40 * l) + d)
+                xs.append(-mul * 2**(40 * l) + d)
+    out = []
+    for x in xs:
+        x = (x + half) % M - half
+        out.append(x)
+    return mods, M, out
+
+
+@pytest.mark.parametrize("N", [2, 3, 5, 8, 11, 14, 16, 18, 20, 21, 24, 26])
+def test_host_crt_element_is_correctly_rounded(N):
+    rng = random.Random(77 + N)
+    mods, M, xs = _crt_cases(N, rng)
+    for x in xs:
+        # any INT32 representative of the residue must give the same result (line 7 takes floor-mod)
+        c = []
+        for p in mods:
+            r = x % p
+            span = (2**31 - 1 - r) // p
+            c.append(r + p * rng.randrange(-span, span + 1) if rng.random() < 0.7 else r)
+        assert all(-2**31 <= v < 2**31 for v in c)
+        got = oz.host_crt_element(N, c)
+        assert got == float(x), (N, x, got, float(x))
+
+
+def test_host_crt_extreme_int32_products():
+    # products at the INT32 limits and negative values: floor-mod must stay in [0, p)
+    N = 16
+    mods = orc.moduli(N)
+    M, W = orc.crt_constants(N)
+    for c0 in (-2**31, 2**31 - 1, -1, 0, -255, -256, -257, 2**30 + 1):
+        c = [c0] * N
+        y = sum((c0 % p) * w for p, w in zip(mods, W)) % M
+        if y >= M - M // 2:
+            y -= M
+        assert oz.host_crt_element(N, c) == float(y)
