@@ -166,6 +166,21 @@ def main():
         nat_ms = e0.elapsed_time(e1) / 3
         out["context"] = {"native_fp64_gemm_TFLOPS_same_gpu": round(2.0 * m * n * k / (nat_ms * 1e-3) / 1e12, 2),
                           "paper_GH200_OSII_fast_16_n16384_TFLOPS": 70.4, "paper_GH200_DGEMM_n16384_TFLOPS": 60.9}
+        # context only: the same MFMA instruction with no memory traffic, constant vs random INT8 operands
+        sink = torch.empty(512 * 256, dtype=torch.int32, device=dev)
+        clocks = torch.zeros(2, dtype=torch.int64, device=dev)
+        for label, rnd in (("constant", 0), ("random", 1)):
+            iters = 200000
+            oz.oz2_calibrate_mfma(512, 2000, rnd, sink.data_ptr(), clocks.data_ptr(), stream)
+            torch.cuda.synchronize()
+            e0.record()
+            oz.oz2_calibrate_mfma(512, iters, rnd, sink.data_ptr(), clocks.data_ptr(), stream)
+            e1.record()
+            torch.cuda.synchronize()
+            ms = e0.elapsed_time(e1)
+            cyc, ref = [int(v) for v in clocks.cpu()]
+            out["context"]["mfma_only_%s_operands_TOPs" % label] = round(512 * 4 * iters * 8 * 65536.0 / (ms * 1e-3) / 1e12, 1)
+            out["context"]["mfma_only_%s_operands_GHz" % label] = round(cyc / max(ref, 1) * 0.1, 3)
         if not args.no_cpu_baseline:
             gotn = Cn[torch.from_numpy(rows).to(dev)][:, torch.from_numpy(cols).to(dev)].cpu().numpy()
             out["context"]["native_fp64_max_componentwise_err_vs_exact"] = float(np.max(np.abs(gotn - Cx) / S))

@@ -89,6 +89,14 @@ int oz2_stage3_crt(int64_t m, int64_t n, int64_t k, double* C, int64_t ldc, int 
  * their order do not change.  events == NULL switches the hooks off.  Returns 0. */
 int oz2_set_stage_events(void* const events[4]);
 
+/* Measurement support: an MFMA-only kernel (v_mfma_i32_32x32x32_i8, no memory traffic) that shows what
+ * the matrix cores of the card sustain under its power cap.  `workgroups` x 256 threads each issue
+ * iters x 8 MFMAs (65536 INT8 operations per wave and MFMA); random_operands != 0 fills the operand
+ * registers with random bytes, 0 with a constant.  sink: device buffer of workgroups*256 ints (written).
+ * clocks: device buffer of two int64: shader-clock cycles and 100 MHz reference ticks spent in the loop by
+ * workgroup 0.  The caller times the launch itself.  Returns 0, a negative argument code, or OZ2_ERR_HIP. */
+int oz2_calibrate_mfma(int workgroups, int iters, int random_operands, int* sink, long long* clocks, void* stream);
+
 /* Inner-dimension block length for line 6.  INT32 accumulation is exact for fewer than 2^17 terms
  * (Section 3.1); longer inner dimensions are processed in blocks and the accumulators are reduced
  * modulo p_t between blocks.  kblock must be a positive multiple of 64 and at most 65536 (the default).

@@ -9,7 +9,7 @@ _lib = None
 SYMBOLS = [
     "oz2_min_moduli", "oz2_max_moduli", "oz2_get_moduli", "oz2_workspace_bytes", "oz2_set_workspace",
     "oz2_workspace_layout", "oz2_dgemm", "oz2_stage1_convert", "oz2_stage2_gemm", "oz2_stage3_crt",
-    "oz2_set_kblock", "oz2_set_stage_events", "oz2_host_crt_element", "oz2_host_residues", "oz2_status_string",
+    "oz2_set_kblock", "oz2_set_stage_events", "oz2_calibrate_mfma", "oz2_host_crt_element", "oz2_host_residues", "oz2_status_string",
 ]
 
 
@@ -36,6 +36,7 @@ def lib():
         L.oz2_stage3_crt.argtypes = [i64, i64, i64, vp, i64, ci, vp]
         L.oz2_set_kblock.argtypes = [i64]
         L.oz2_set_stage_events.argtypes = [vp]
+        L.oz2_calibrate_mfma.argtypes = [ci, ci, ci, vp, vp, vp]
         L.oz2_host_crt_element.argtypes = [ci, vp, vp]
         L.oz2_host_residues.argtypes = [ci, ci, ctypes.c_double, ci, vp]
         L.oz2_status_string.restype = ctypes.c_char_p
@@ -119,6 +120,11 @@ def oz2_stage2_gemm(m, n, k, num_moduli, stream=None):
 
 def oz2_stage3_crt(m, n, k, C_ptr, ldc, num_moduli, stream=None):
     _check(lib().oz2_stage3_crt(m, n, k, C_ptr, ldc, num_moduli, _stream_ptr(stream)), "oz2_stage3_crt")
+
+
+def oz2_calibrate_mfma(workgroups, iters, random_operands, sink_ptr, clocks_ptr, stream=None):
+    _check(lib().oz2_calibrate_mfma(workgroups, iters, int(random_operands), sink_ptr, clocks_ptr,
+                                    _stream_ptr(stream)), "oz2_calibrate_mfma")
 
 
 def host_crt_element(num_moduli, cprod):

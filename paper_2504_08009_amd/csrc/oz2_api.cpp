@@ -215,6 +215,16 @@ int oz2_dgemm(int64_t m, int64_t n, int64_t k, const double* A, int64_t lda, con
   return OZ2_OK;
 }
 
+int oz2_calibrate_mfma(int workgroups, int iters, int random_operands, int* sink, long long* clocks, void* stream) {
+  if (workgroups < 1 || workgroups > 65536) return -1;
+  if (iters < 1) return -2;
+  if (!sink) return -4;
+  if (!clocks) return -5;
+  hipError_t e = oz2_launch_mfma_calibration(workgroups, iters, random_operands, sink, clocks,
+                                             static_cast<hipStream_t>(stream));
+  return e == hipSuccess ? OZ2_OK : OZ2_ERR_HIP;
+}
+
 int oz2_host_crt_element(int num_moduli, const int32_t* cprod, double* x_out) {
   if (!n_ok(num_moduli)) return -1;
   if (!cprod) return -2;

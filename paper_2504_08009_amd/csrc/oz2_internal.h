@@ -66,6 +66,9 @@ hipError_t oz2_launch_stage3(int64_t m, int64_t n, double* C, int64_t ldc, const
                              const Oz2Layout& lay, char* ws, hipStream_t st);
 hipError_t oz2_launch_zero_c(int64_t m, int64_t n, double* C, int64_t ldc, hipStream_t st);
 
+hipError_t oz2_launch_mfma_calibration(int workgroups, int iters, int random_operands, int* sink, long long* clocks,
+                                       hipStream_t st);
+
 // Host instantiations of the device math (oz2_stage1.hip / oz2_stage3.hip), for unit tests.
 void oz2_host_residues_impl(const Oz2ConvConsts& c, double a, int shift, int8_t* out);
 double oz2_host_crt_impl(const Oz2CrtConsts& c, const int32_t* cprod);
