@@ -8,8 +8,10 @@
 namespace {
 
 constexpr int kThreads = 256;
-constexpr int kRowsPerThread = 2;
+constexpr int kRowsPerThread = 4;
 
+// One thread: four consecutive rows i of one column j.  The INT32 planes are read with 16-byte loads, one
+// plane ahead of the arithmetic, so that each wave keeps two kilobytes in flight.
 template <int L>
 __global__ void __launch_bounds__(kThreads) crt_kernel(const int* __restrict__ cplanes, int64_t m_pad, int64_t n_pad,
                                                        const int* __restrict__ sa, const int* __restrict__ sb,
@@ -19,7 +21,8 @@ __global__ void __launch_bounds__(kThreads) crt_kernel(const int* __restrict__ c
   const int64_t i0 = ((int64_t)blockIdx.y * kThreads + threadIdx.x) * kRowsPerThread;
   if (i0 >= m) return;
   const size_t plane_stride = (size_t)n_pad * m_pad;
-  const int* src = cplanes + (size_t)j * m_pad + i0;
+  const int4* src = reinterpret_cast<const int4*>(cplanes + (size_t)j * m_pad + i0);
+  const size_t stride4 = plane_stride / 4;
 
   double S[kRowsPerThread][L];
 #pragma unroll
@@ -27,28 +30,35 @@ __global__ void __launch_bounds__(kThreads) crt_kernel(const int* __restrict__ c
 #pragma unroll
     for (int l = 0; l < L; ++l) S[r][l] = 0.0;
 
+  int4 cur = src[0];
   for (int t = 0; t < cc.N; ++t) {
-    int2 c = *reinterpret_cast<const int2*>(src + (size_t)t * plane_stride);
+    const int4 c = cur;
+    if (t + 1 < cc.N) cur = src[(size_t)(t + 1) * stride4];
     const double p = cc.p[t], ip = cc.inv_p[t], hip_ = cc.half_inv_p[t];
-    double r0 = oz2_floor_mod(c.x, p, ip, hip_);
-    double r1 = oz2_floor_mod(c.y, p, ip, hip_);
+    double res[kRowsPerThread];
+    res[0] = oz2_floor_mod(c.x, p, ip, hip_);
+    res[1] = oz2_floor_mod(c.y, p, ip, hip_);
+    res[2] = oz2_floor_mod(c.z, p, ip, hip_);
+    res[3] = oz2_floor_mod(c.w, p, ip, hip_);
 #pragma unroll
     for (int l = 0; l < L; ++l) {
       const double w = cc.w[t][l];
-      S[0][l] = fma(r0, w, S[0][l]);
-      S[1][l] = fma(r1, w, S[1][l]);
+#pragma unroll
+      for (int r = 0; r < kRowsPerThread; ++r) S[r][l] = fma(res[r], w, S[r][l]);
     }
   }
   const int sbj = sb[j];
+  double out[kRowsPerThread];
 #pragma unroll
   for (int r = 0; r < kRowsPerThread; ++r) {
-    int64_t i = i0 + r;
-    if (i < m) {
-      int e2;
-      double x = oz2_crt_reduce<L>(S[r], cc, &e2);
-      C[i + j * ldc] = ldexp(x, e2 - sa[i] - sbj);
-    }
+    int e2;
+    double x = oz2_crt_reduce<L>(S[r], cc, &e2);
+    out[r] = ldexp(x, e2 - sa[i0 + r] - sbj);   // sa is padded to m_pad (a multiple of 256): always readable
   }
+  double* dst = C + i0 + j * ldc;
+#pragma unroll
+  for (int r = 0; r < kRowsPerThread; ++r)
+    if (i0 + r < m) dst[r] = out[r];
 }
 
 __global__ void __launch_bounds__(kThreads) zero_c_kernel(double* __restrict__ C, int64_t ldc, int64_t m) {
