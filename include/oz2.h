@@ -32,6 +32,9 @@ extern "C" {
 #define OZ2_ERR_BUDGET 2
 #define OZ2_ERR_HIP 3
 
+#define OZ2_SHIFT_MAX 0            /* shifts from row/column maxima: the simple bound of Section 3 */
+#define OZ2_SHIFT_CAUCHY_SCHWARZ 1 /* shifts from row/column 2-norms: Section 4.1, the "fast" variant */
+
 /* Smallest and largest supported number of moduli (Section 3.1: the table starts at s = 2). */
 int oz2_min_moduli(void);
 int oz2_max_moduli(void);
@@ -52,7 +55,7 @@ size_t oz2_workspace_bytes(int64_t m, int64_t n, int64_t k, int num_moduli);
 int oz2_set_workspace(void* dev_ptr, size_t bytes);
 
 /* Where each intermediate lives inside the workspace, so that a test can read every stage's output.
- * offsets[0..6] (bytes from the workspace start):
+ * offsets[0..8] (bytes from the workspace start):
  *   0 rowmax  : m_pad uint64, bit pattern of max_l |a_il| per row of A
  *   1 colmax  : n_pad uint64, same per column of B
  *   2 sa      : m_pad int32 shifts of A's rows      (Algorithm 1 line 1)
@@ -63,9 +66,11 @@ int oz2_set_workspace(void* dev_ptr, size_t bytes);
  *   5 B planes: num_moduli x n_pad x k_pad int8 residues of B' (line 5), same blocking with the column
  *               index j of B in the place of i and n_pad in the place of m_pad
  *   6 C planes: num_moduli x n_pad x m_pad int32, plane t element (i,j) at ((t*n_pad)+j)*m_pad + i
+ *   7 rownorm : m_pad uint64, integer norm bound S_i of A's rows (Cauchy-Schwarz shift mode only)
+ *   8 colnorm : n_pad uint64, same per column of B
  * dims[0..2] = m_pad, n_pad, k_pad (m, n rounded up to 256, k to 64; padding holds zeros).
  * Returns 0 or a negative argument code. */
-int oz2_workspace_layout(int64_t m, int64_t n, int64_t k, int num_moduli, size_t offsets[7], int64_t dims[3]);
+int oz2_workspace_layout(int64_t m, int64_t n, int64_t k, int num_moduli, size_t offsets[9], int64_t dims[3]);
 
 /* The whole of Algorithm 1:  C := A*B  with num_moduli INT8 products.
  *   A: m x k, lda >= max(1,m);  B: k x n, ldb >= max(1,k);  C: m x n, ldc >= max(1,m).
@@ -83,6 +88,15 @@ int oz2_stage1_convert(int64_t m, int64_t n, int64_t k, const double* A, int64_t
                        int64_t ldb, int num_moduli, void* stream);
 int oz2_stage2_gemm(int64_t m, int64_t n, int64_t k, int num_moduli, void* stream);
 int oz2_stage3_crt(int64_t m, int64_t n, int64_t k, double* C, int64_t ldc, int num_moduli, void* stream);
+
+/* How Algorithm 1 line 1 picks the shifts, for all later calls (default OZ2_SHIFT_MAX).
+ *   OZ2_SHIFT_MAX: sa_i = kappa - 1 - floor(log2 max_l |a_il|) with the bit budget kappa of Section 3.
+ *   OZ2_SHIFT_CAUCHY_SCHWARZ (Section 4.1): (|A||B|)_ij <= ||A(i,:)||_2 ||B(:,j)||_2, and the shifts are the
+ *     largest with 2^sa_i nu_i <= 2^beta, 2^sb_j nu_j <= 2^beta, 4^beta <= M/2 - 1, where nu is an integer
+ *     upper bound of the 2-norm: e = floor(log2 max |a|), q_l = ceil(|a_l| 2^(19-e)), S = sum q_l^2,
+ *     h = min{h : 4^h >= S}, nu = 2^(e-19+h), sa = beta - (e - 19 + h).  One more pass over A and B.
+ * Returns 0 or -1. */
+int oz2_set_shift_mode(int mode);
 
 /* Optional timing hooks for oz2_dgemm: four caller-owned hipEvent_t handles (as void*), recorded on the
  * call's stream before stage 1 and after stages 1, 2 and 3 of every later oz2_dgemm call.  The kernels and

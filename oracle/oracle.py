@@ -33,10 +33,11 @@ def lib():
         _lib.oz2o_sym_mod.restype = ctypes.c_int64
         _lib.oz2o_sym_mod.argtypes = [ctypes.c_int64, ctypes.c_int]
         _lib.oz2o_kappa.argtypes = [ctypes.c_int, ctypes.c_void_p, ctypes.c_int64]
+        _lib.oz2o_beta.argtypes = [ctypes.c_int, ctypes.c_void_p]
         _lib.oz2o_shifts.argtypes = [ctypes.c_int, ctypes.c_int64, ctypes.c_int64, ctypes.c_void_p,
                                      ctypes.c_int64, ctypes.c_int, ctypes.c_void_p]
         _lib.oz2o_dgemm_sub.argtypes = ([ctypes.c_int64] * 3 + [ctypes.c_void_p, ctypes.c_int64, ctypes.c_void_p,
-                                        ctypes.c_int64, ctypes.c_int, ctypes.c_void_p, ctypes.c_int64,
+                                        ctypes.c_int64, ctypes.c_int, ctypes.c_int, ctypes.c_void_p, ctypes.c_int64,
                                         ctypes.c_void_p, ctypes.c_int64, ctypes.c_void_p] + [ctypes.c_void_p] * 13)
         _lib.oz2o_exact_sub.argtypes = ([ctypes.c_int64] * 3 + [ctypes.c_void_p, ctypes.c_int64, ctypes.c_void_p,
                                         ctypes.c_int64, ctypes.c_int64, ctypes.c_void_p, ctypes.c_int64,
@@ -75,6 +76,11 @@ def kappa(N, k, mods=None):
     return int(lib().oz2o_kappa(int(N), _ptr(mods), int(k)))
 
 
+def beta(N, mods=None):
+    mods = np.asarray(moduli(N) if mods is None else mods, dtype=np.int32)
+    return int(lib().oz2o_beta(int(N), _ptr(mods)))
+
+
 def crt_constants(N, mods=None):
     """Return (M, [W_1..W_N]) as Python ints."""
     mods = np.asarray(moduli(N) if mods is None else mods, dtype=np.int32)
@@ -98,8 +104,9 @@ class Result(dict):
     __getattr__ = dict.__getitem__
 
 
-def dgemm(A, B, N, mods=None, rows=None, cols=None, want=("C",)):
-    """Run Algorithm 1 on the CPU.  A (m x k), B (k x n): numpy float64, any layout (copied to
+def dgemm(A, B, N, mods=None, rows=None, cols=None, want=("C",), mode=0):
+    """Run Algorithm 1 on the CPU.  mode 0: shifts from the row/column maxima (Section 3); mode 1: shifts
+    from the Cauchy-Schwarz bound (Section 4.1, "fast").  A (m x k), B (k x n): numpy float64, any layout (copied to
     column-major).  rows / cols: optional index lists selecting the outputs to compute.
     want: any of "C", "shifts", "Ap", "Bp", "Ares", "Bres", "Cprod", "Cres", "X".
     Ap/Bp/X come back as nested Python-int lists (tiny inputs only)."""
@@ -127,7 +134,7 @@ def dgemm(A, B, N, mods=None, rows=None, cols=None, want=("C",)):
     cres = np.zeros((N, nJ, nI), dtype=np.uint8) if "Cres" in w else None
     xs = np.zeros((nJ, nI), dtype=np.uint8) if "X" in w else None
     xm = np.zeros((nJ, nI, WORDS), dtype=np.uint32) if "X" in w else None
-    rc = lib().oz2o_dgemm_sub(m, n, k, _ptr(A), max(1, m), _ptr(B), max(1, k), int(N), _ptr(mods_a),
+    rc = lib().oz2o_dgemm_sub(m, n, k, _ptr(A), max(1, m), _ptr(B), max(1, k), int(N), int(mode), _ptr(mods_a),
                               nI, _ptr(I), nJ, _ptr(J), _ptr(C), _ptr(sa), _ptr(sb), _ptr(aps), _ptr(apm),
                               _ptr(bps), _ptr(bpm), _ptr(ares), _ptr(bres), _ptr(cprod), _ptr(cres),
                               _ptr(xs), _ptr(xm))

@@ -18,6 +18,13 @@
 //              power-of-two scaling.
 // kappa = k_A = k_B follows the second bit-budget equation of Section 3 evaluated with integers:
 //   the largest kappa with k * 4^kappa <= M/2 - 1.
+// Shift selection has two modes.  Mode 0 is the simple bound of Section 3 described above.  Mode 1 is the
+// Cauchy-Schwarz bound of Section 4.1 (the paper's "OS II-fast"): (|A||B|)_ij <= ||A(i,:)||_2 ||B(:,j)||_2, and
+// the shifts are chosen so that 2^sa_i ||A(i,:)||_2 <= 2^beta and 2^sb_j ||B(:,j)||_2 <= 2^beta with
+// 4^beta <= M/2 - 1, hence (|A'||B'|)_ij < M/2.  To make the choice reproducible bit for bit the norm is
+// replaced by an integer upper bound: with e_i = floor(log2 max_l |a_il|), q_il = ceil(|a_il| 2^(19-e_i)) (an
+// integer below 2^20), S_i = sum_l q_il^2 and h_i the smallest integer with 4^h_i >= S_i, one has
+// ||A(i,:)||_2 <= 2^(e_i-19+h_i) and sa_i = beta - (e_i - 19 + h_i).
 // The moduli are the greedy descending pairwise-coprime sequence starting at 256 (Section 3.1 asks for
 // the largest possible pairwise-coprime values not above 256); a caller may pass any other list, e.g. the
 // sixteen values the paper prints.
@@ -301,6 +308,57 @@ void round_to_53(const BigU& mag, uint64_t* m53, int* e2) {
   *e2 = drop;
 }
 
+// Section 4.1 (Cauchy-Schwarz variant): largest beta with 4^beta <= M/2 - 1
+int beta_of(const BigU& M) {
+  BigU half = shr1(M);
+  if (is_zero(half)) return -1;
+  BigU lim = sub(half, BigU(1));
+  if (is_zero(lim)) return -1;
+  BigU v(1);
+  int beta = 0;
+  for (;;) {
+    BigU nxt = shl1(shl1(v));
+    if (cmp(nxt, lim) > 0) break;
+    v = nxt;
+    ++beta;
+  }
+  return beta;
+}
+
+// ceil(|x| * 2^(19 - e)) for |x| < 2^(e+1): an integer in [0, 2^20]
+uint64_t scaled_ceil(double x, int e) {
+  int neg, ex;
+  uint64_t mant;
+  decompose(x, &neg, &mant, &ex);
+  if (mant == 0) return 0;
+  int sh = ex + 19 - e;  // always negative here: mant has up to 53 bits, the result at most 21
+  if (sh >= 0) return mant << sh;
+  if (-sh >= 64) return 1;
+  uint64_t q = mant >> (-sh);
+  if ((q << (-sh)) != mant) q += 1;
+  return q;
+}
+
+// shift of one vector under the Cauchy-Schwarz bound; x[l*stride], l < k
+int fast_shift(const double* x, int64_t k, int64_t stride, int beta) {
+  double mx = 0.0;
+  for (int64_t l = 0; l < k; ++l) mx = std::fmax(mx, std::fabs(x[l * stride]));
+  if (mx == 0.0) return 0;
+  int e = ilog2_abs(mx);
+  u128 S = 0;
+  for (int64_t l = 0; l < k; ++l) {
+    u128 q = scaled_ceil(x[l * stride], e);
+    S += q * q;
+  }
+  int h = 0;
+  u128 pw = 1;
+  while (pw < S) {
+    pw <<= 2;
+    ++h;
+  }
+  return beta - (e - 19 + h);
+}
+
 int validate(int64_t m, int64_t n, int64_t k, int64_t lda, int64_t ldb, int N) {
   if (m < 0 || n < 0 || k < 0) return -1;
   if (lda < (m > 1 ? m : 1) || ldb < (k > 1 ? k : 1)) return -2;
@@ -318,6 +376,12 @@ int oz2o_words(void) { return WORDS; }
 int oz2o_moduli(int N, int* out) {
   if (N < 1 || N > 28) return -1;
   return greedy_moduli(N, out);
+}
+
+// beta of the Cauchy-Schwarz variant for a moduli list: largest beta with 4^beta <= M/2 - 1.
+int oz2o_beta(int N, const int* moduli) {
+  if (N < 1 || N > 28) return -1;
+  return beta_of(product(N, moduli));
 }
 
 // kappa for a moduli list and inner dimension k.  -1 when even kappa = 0 violates the bound.
@@ -374,12 +438,13 @@ int oz2o_shifts(int which, int64_t rows, int64_t cols, const double* X, int64_t 
 //   X_sign[r + c*nI], X_mag[(r + c*nI)*WORDS + w]   the integer X
 // Returns 0, or a negative code for bad arguments, or 2 when kappa < 1.
 int oz2o_dgemm_sub(int64_t m, int64_t n, int64_t k, const double* A, int64_t lda, const double* B, int64_t ldb,
-                   int N, const int* moduli_in, int64_t nI, const int64_t* I, int64_t nJ, const int64_t* J,
+                   int N, int mode, const int* moduli_in, int64_t nI, const int64_t* I, int64_t nJ, const int64_t* J,
                    double* C_out, int32_t* sa_out, int32_t* sb_out, uint8_t* Ap_sign, uint32_t* Ap_mag,
                    uint8_t* Bp_sign, uint32_t* Bp_mag, int8_t* Ares, int8_t* Bres, int64_t* Cprod, uint8_t* Cres,
                    uint8_t* X_sign, uint32_t* X_mag) {
   int rc = validate(m, n, k, lda, ldb, N);
   if (rc) return rc;
+  if (mode != 0 && mode != 1) return -4;
   if (!I) nI = m;
   if (!J) nJ = n;
   if (nI == 0 || nJ == 0) return 0;
@@ -403,12 +468,18 @@ int oz2o_dgemm_sub(int64_t m, int64_t n, int64_t k, const double* A, int64_t lda
   const int kappa = kappa_of(M, k);
   if (kappa < 1) return 2;
   if (kappa > 120) return -3;
+  const int beta = beta_of(M);
+  if (mode == 1 && (beta < 1 || beta > 120)) return 2;
 
   // line 1: shifts
   std::vector<int32_t> sa(nI), sb(nJ);
 #pragma omp parallel for schedule(static)
   for (int64_t r = 0; r < nI; ++r) {
     int64_t i = I ? I[r] : r;
+    if (mode == 1) {
+      sa[r] = fast_shift(A + i, k, lda, beta);
+      continue;
+    }
     double mx = 0.0;
     for (int64_t l = 0; l < k; ++l) mx = std::fmax(mx, std::fabs(A[i + l * lda]));
     sa[r] = mx == 0.0 ? 0 : kappa - 1 - ilog2_abs(mx);
@@ -416,6 +487,10 @@ int oz2o_dgemm_sub(int64_t m, int64_t n, int64_t k, const double* A, int64_t lda
 #pragma omp parallel for schedule(static)
   for (int64_t c = 0; c < nJ; ++c) {
     int64_t j = J ? J[c] : c;
+    if (mode == 1) {
+      sb[c] = fast_shift(B + j * ldb, k, 1, beta);
+      continue;
+    }
     double mx = 0.0;
     for (int64_t l = 0; l < k; ++l) mx = std::fmax(mx, std::fabs(B[l + j * ldb]));
     sb[c] = mx == 0.0 ? 0 : kappa - 1 - ilog2_abs(mx);

@@ -9,7 +9,7 @@ _lib = None
 SYMBOLS = [
     "oz2_min_moduli", "oz2_max_moduli", "oz2_get_moduli", "oz2_workspace_bytes", "oz2_set_workspace",
     "oz2_workspace_layout", "oz2_dgemm", "oz2_stage1_convert", "oz2_stage2_gemm", "oz2_stage3_crt",
-    "oz2_set_kblock", "oz2_set_stage_events", "oz2_calibrate_mfma", "oz2_host_crt_element", "oz2_host_residues", "oz2_status_string",
+    "oz2_set_kblock", "oz2_set_shift_mode", "oz2_set_stage_events", "oz2_calibrate_mfma", "oz2_host_crt_element", "oz2_host_residues", "oz2_status_string",
 ]
 
 
@@ -35,6 +35,7 @@ def lib():
         L.oz2_stage2_gemm.argtypes = [i64, i64, i64, ci, vp]
         L.oz2_stage3_crt.argtypes = [i64, i64, i64, vp, i64, ci, vp]
         L.oz2_set_kblock.argtypes = [i64]
+        L.oz2_set_shift_mode.argtypes = [ci]
         L.oz2_set_stage_events.argtypes = [vp]
         L.oz2_calibrate_mfma.argtypes = [ci, ci, ci, vp, vp, vp]
         L.oz2_host_crt_element.argtypes = [ci, vp, vp]
@@ -72,10 +73,10 @@ def workspace_bytes(m, n, k, num_moduli):
 
 def workspace_layout(m, n, k, num_moduli):
     """dict of byte offsets and padded dims (see include/oz2.h)."""
-    offs = (ctypes.c_size_t * 7)()
+    offs = (ctypes.c_size_t * 9)()
     dims = (ctypes.c_int64 * 3)()
     _check(lib().oz2_workspace_layout(m, n, k, num_moduli, offs, dims), "oz2_workspace_layout")
-    names = ["rowmax", "colmax", "sa", "sb", "a_planes", "b_planes", "c_planes"]
+    names = ["rowmax", "colmax", "sa", "sb", "a_planes", "b_planes", "c_planes", "rownorm", "colnorm"]
     out = {nm: int(o) for nm, o in zip(names, offs)}
     out.update(m_pad=int(dims[0]), n_pad=int(dims[1]), k_pad=int(dims[2]))
     return out
@@ -87,6 +88,11 @@ def set_workspace(dev_ptr, nbytes):
 
 def oz2_set_kblock(kblock):
     _check(lib().oz2_set_kblock(kblock), "oz2_set_kblock")
+
+
+def oz2_set_shift_mode(mode):
+    """0: shifts from maxima (Section 3); 1: Cauchy-Schwarz bound (Section 4.1)."""
+    _check(lib().oz2_set_shift_mode(int(mode)), "oz2_set_shift_mode")
 
 
 def oz2_set_stage_events(events):

@@ -11,6 +11,7 @@ struct State {
   char* ws = nullptr;
   size_t ws_bytes = 0;
   int64_t kblock = 65536;
+  int shift_mode = 0;
   hipEvent_t ev[4] = {nullptr, nullptr, nullptr, nullptr};
   bool ev_on = false;
   Oz2Plan plan;
@@ -48,7 +49,8 @@ bool dims_ok(int64_t m, int64_t n, int64_t k) {
 
 int prepare(State& s, int64_t m, int64_t n, int64_t k, int N, const Oz2Plan** plan, Oz2Layout* lay) {
   int rc = get_plan(s, N, k, plan);
-  if (rc == 2) return OZ2_ERR_BUDGET;
+  if (rc == 2 && (s.shift_mode == OZ2_SHIFT_MAX || (*plan)->beta < 1)) return OZ2_ERR_BUDGET;
+  if (rc == 2) rc = 0;
   if (rc != 0) return -10;
   oz2_make_layout(m, n, k, N, lay);
   if (!s.ws || s.ws_bytes < lay->total) return OZ2_ERR_WORKSPACE;
@@ -86,7 +88,7 @@ int oz2_set_workspace(void* dev_ptr, size_t bytes) {
   return OZ2_OK;
 }
 
-int oz2_workspace_layout(int64_t m, int64_t n, int64_t k, int num_moduli, size_t offsets[7], int64_t dims[3]) {
+int oz2_workspace_layout(int64_t m, int64_t n, int64_t k, int num_moduli, size_t offsets[9], int64_t dims[3]) {
   if (m < 0) return -1;
   if (n < 0) return -2;
   if (k < 0) return -3;
@@ -103,6 +105,8 @@ int oz2_workspace_layout(int64_t m, int64_t n, int64_t k, int num_moduli, size_t
   offsets[4] = lay.off_a;
   offsets[5] = lay.off_b;
   offsets[6] = lay.off_c;
+  offsets[7] = lay.off_rownorm;
+  offsets[8] = lay.off_colnorm;
   dims[0] = lay.m_pad;
   dims[1] = lay.n_pad;
   dims[2] = lay.k_pad;
@@ -114,6 +118,14 @@ int oz2_set_stage_events(void* const events[4]) {
   std::lock_guard<std::mutex> lock(s.mu);
   s.ev_on = events != nullptr;
   for (int i = 0; i < 4; ++i) s.ev[i] = events ? static_cast<hipEvent_t>(events[i]) : nullptr;
+  return OZ2_OK;
+}
+
+int oz2_set_shift_mode(int mode) {
+  if (mode != OZ2_SHIFT_MAX && mode != OZ2_SHIFT_CAUCHY_SCHWARZ) return -1;
+  State& s = state();
+  std::lock_guard<std::mutex> lock(s.mu);
+  s.shift_mode = mode;
   return OZ2_OK;
 }
 
@@ -143,7 +155,8 @@ int oz2_stage1_convert(int64_t m, int64_t n, int64_t k, const double* A, int64_t
   Oz2Layout lay;
   int rc = prepare(s, m, n, k, num_moduli, &plan, &lay);
   if (rc) return rc;
-  hipError_t e = oz2_launch_stage1(m, n, k, A, lda, B, ldb, *plan, lay, s.ws, static_cast<hipStream_t>(stream));
+  hipError_t e = oz2_launch_stage1(m, n, k, A, lda, B, ldb, *plan, s.shift_mode, lay, s.ws,
+                                   static_cast<hipStream_t>(stream));
   return e == hipSuccess ? OZ2_OK : OZ2_ERR_HIP;
 }
 
@@ -209,7 +222,8 @@ int oz2_dgemm(int64_t m, int64_t n, int64_t k, const double* A, int64_t lda, con
   if (rc) return rc;
   auto mark = [&](int i) { return !s.ev_on || hipEventRecord(s.ev[i], st) == hipSuccess; };
   if (!mark(0)) return OZ2_ERR_HIP;
-  if (oz2_launch_stage1(m, n, k, A, lda, B, ldb, *plan, lay, s.ws, st) != hipSuccess || !mark(1)) return OZ2_ERR_HIP;
+  if (oz2_launch_stage1(m, n, k, A, lda, B, ldb, *plan, s.shift_mode, lay, s.ws, st) != hipSuccess || !mark(1))
+    return OZ2_ERR_HIP;
   if (oz2_launch_stage2(*plan, lay, s.ws, s.kblock, st) != hipSuccess || !mark(2)) return OZ2_ERR_HIP;
   if (oz2_launch_stage3(m, n, C, ldc, *plan, lay, s.ws, st) != hipSuccess || !mark(3)) return OZ2_ERR_HIP;
   return OZ2_OK;
@@ -241,7 +255,7 @@ int oz2_host_residues(int num_moduli, int kappa, double a, int shift, int8_t* re
   if (!res_out) return -5;
   Oz2Plan plan;
   if (oz2_build_plan(num_moduli, 1, &plan) < 0) return -1;
-  plan.conv.two_level = kappa > 75;
+  plan.conv.two_level = kappa > 75;  // same rule as the launcher: |x| < 2^kappa
   oz2_host_residues_impl(plan.conv, a, shift, res_out);
   return OZ2_OK;
 }

@@ -130,13 +130,22 @@ int oz2_table_kappa(int N, int64_t k) {
   return (bits - 1) / 2;  // largest kappa with 4^kappa <= floor((M/2-1)/k)
 }
 
+// largest beta with 4^beta <= M/2 - 1
+static int table_beta(const int* moduli, int N) {
+  Wide lim = product_of(moduli, N);
+  wide_divmod(lim, 2);
+  wide_sub_one(lim);
+  int bits = wide_bits(lim);
+  return bits == 0 ? -1 : (bits - 1) / 2;
+}
+
 int oz2_build_plan(int N, int64_t k, Oz2Plan* plan) {
   if (N < OZ2_MIN_N || N > OZ2_MAX_N || k < 1) return -1;
   std::memset(plan, 0, sizeof(*plan));
   plan->N = N;
   oz2_table_moduli(N, plan->moduli);
   plan->kappa = oz2_table_kappa(N, k);
-  if (plan->kappa < 1) return 2;
+  plan->beta = table_beta(plan->moduli, N);
 
   const Wide M = product_of(plan->moduli, N);
   const int mbits = wide_bits(M);
@@ -183,7 +192,7 @@ int oz2_build_plan(int N, int64_t k, Oz2Plan* plan) {
     wide_mul_small(W, (uint32_t)y);
     for (int l = 0; l < OZ2_MAX_L; ++l) cc.w[t][l] = l < L ? wide_limb(W, OZ2_LIMB_BITS * l) : 0.0;
   }
-  return 0;
+  return plan->kappa < 1 ? 2 : 0;  // 2: the simple bound of Section 3 leaves no bits for this k
 }
 
 void oz2_make_layout(int64_t m, int64_t n, int64_t k, int N, Oz2Layout* lay) {
@@ -207,5 +216,9 @@ void oz2_make_layout(int64_t m, int64_t n, int64_t k, int N, Oz2Layout* lay) {
   off = up256(off + (size_t)N * lay->n_pad * lay->k_pad);
   lay->off_c = off;
   off = up256(off + (size_t)N * lay->n_pad * lay->m_pad * 4);
+  lay->off_rownorm = off;
+  off = up256(off + (size_t)lay->m_pad * 8);
+  lay->off_colnorm = off;
+  off = up256(off + (size_t)lay->n_pad * 8);
   lay->total = off;
 }

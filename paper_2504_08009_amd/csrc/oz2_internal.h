@@ -42,6 +42,7 @@ struct Oz2CrtConsts {
 struct Oz2Plan {
   int N;
   int kappa;
+  int beta;   // largest beta with 4^beta <= M/2 - 1 (Cauchy-Schwarz shift mode)
   int moduli[OZ2_MAX_N];
   Oz2ConvConsts conv;
   Oz2CrtConsts crt;
@@ -54,13 +55,14 @@ int oz2_table_kappa(int N, int64_t k);
 
 struct Oz2Layout {
   int64_t m_pad, n_pad, k_pad;
-  size_t off_rowmax, off_colmax, off_sa, off_sb, off_a, off_b, off_c, total;
+  size_t off_rowmax, off_colmax, off_sa, off_sb, off_a, off_b, off_c, off_rownorm, off_colnorm, total;
 };
 void oz2_make_layout(int64_t m, int64_t n, int64_t k, int N, Oz2Layout* lay);
 
 // Kernel launchers.  Each returns hipSuccess or the launch error.
 hipError_t oz2_launch_stage1(int64_t m, int64_t n, int64_t k, const double* A, int64_t lda, const double* B,
-                             int64_t ldb, const Oz2Plan& plan, const Oz2Layout& lay, char* ws, hipStream_t st);
+                             int64_t ldb, const Oz2Plan& plan, int shift_mode, const Oz2Layout& lay, char* ws,
+                             hipStream_t st);
 hipError_t oz2_launch_stage2(const Oz2Plan& plan, const Oz2Layout& lay, char* ws, int64_t kblock, hipStream_t st);
 hipError_t oz2_launch_stage3(int64_t m, int64_t n, double* C, int64_t ldc, const Oz2Plan& plan,
                              const Oz2Layout& lay, char* ws, hipStream_t st);

@@ -93,6 +93,94 @@ __global__ void __launch_bounds__(kThreads) shifts_kernel(const unsigned long lo
   s[i] = out;
 }
 
+// ---- Cauchy-Schwarz shift mode (Section 4.1): integer upper bound of the 2-norm.
+// With e = floor(log2 max |x|):  q_l = ceil(|x_l| 2^(19-e)) <= 2^20,  S = sum_l q_l^2  (exact in 64 bits for
+// fewer than 2^23 terms, and independent of the order of summation).
+__device__ __forceinline__ int exponent_of_bits(unsigned long long b) {  // floor(log2) of a positive double's bits
+  int be = (int)(b >> 52);
+  return be ? be - 1023 : (63 - __clzll((long long)b)) - 1074;
+}
+
+__device__ __forceinline__ double scaled_ceil_sq(double v, int sc) {
+  double q = ceil(ldexp(fabs(v), sc));  // exact: a power-of-two scaling, then an integer at most 2^20
+  if (v != 0.0 && q == 0.0) q = 1.0;    // the scaling underflowed: the ceiling of a positive value is 1
+  return q * q;                         // exact: at most 2^40
+}
+
+__global__ void __launch_bounds__(kThreads) rownorm_kernel(const double* __restrict__ A, int64_t lda, int64_t m,
+                                                           int64_t k, const unsigned long long* __restrict__ rowmax,
+                                                           unsigned long long* __restrict__ rownorm) {
+  int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+  if (i >= m) return;
+  const unsigned long long mb = rowmax[i];
+  if (!mb) return;
+  const int sc = 19 - exponent_of_bits(mb);
+  int64_t l0 = (int64_t)blockIdx.y * kRowMaxKC;
+  int64_t l1 = l0 + kRowMaxKC < k ? l0 + kRowMaxKC : k;
+  const double* p = A + i + l0 * lda;
+  double acc = 0.0;  // at most 128 terms of at most 2^40: exact
+  int64_t l = l0;
+  for (; l + 8 <= l1; l += 8) {
+    double v[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) v[u] = p[(int64_t)u * lda];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) acc += scaled_ceil_sq(v[u], sc);
+    p += 8 * lda;
+  }
+  for (; l < l1; ++l) {
+    acc += scaled_ceil_sq(*p, sc);
+    p += lda;
+  }
+  atomicAdd(rownorm + i, (unsigned long long)acc);
+}
+
+__global__ void __launch_bounds__(kThreads) colnorm_kernel(const double* __restrict__ B, int64_t ldb, int64_t k,
+                                                           const unsigned long long* __restrict__ colmax,
+                                                           unsigned long long* __restrict__ colnorm) {
+  int64_t j = blockIdx.x;
+  const unsigned long long mb = colmax[j];
+  if (!mb) return;  // uniform over the block
+  const int sc = 19 - exponent_of_bits(mb);
+  int64_t l0 = (int64_t)blockIdx.y * kColMaxKC;
+  const double* p = B + j * ldb;
+  double acc = 0.0;  // 16 terms
+#pragma unroll 4
+  for (int u = 0; u < kColMaxKC / kThreads; ++u) {
+    int64_t l = l0 + (int64_t)u * kThreads + threadIdx.x;
+    if (l < k) acc += scaled_ceil_sq(p[l], sc);
+  }
+  unsigned long long s = (unsigned long long)acc;
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) s += __shfl_xor(s, off, 64);
+  __shared__ unsigned long long part[kThreads / 64];
+  if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = s;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+#pragma unroll
+    for (int w = 1; w < kThreads / 64; ++w) s += part[w];
+    atomicAdd(colnorm + j, s);
+  }
+}
+
+// sa = beta - (e - 19 + h) with h the smallest integer such that 4^h >= S; 0 for an all-zero vector
+__global__ void __launch_bounds__(kThreads) shifts_cs_kernel(const unsigned long long* __restrict__ mx,
+                                                             const unsigned long long* __restrict__ norm,
+                                                             int* __restrict__ s, int64_t count, int beta) {
+  int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+  if (i >= count) return;
+  unsigned long long b = mx[i];
+  int out = 0;
+  if (b) {
+    const int e = exponent_of_bits(b);
+    const unsigned long long S = norm[i];            // >= 2^38: the maximum alone contributes that much
+    const int bits = 64 - __clzll((long long)(S - 1));  // ceil(log2 S)
+    const int h = (bits + 1) >> 1;
+    out = beta - (e - 19 + h);
+  }
+  s[i] = out;
+}
+
 __device__ __forceinline__ unsigned pack4(int r0, int r1, int r2, int r3) {
   return (unsigned)(r0 & 0xff) | ((unsigned)(r1 & 0xff) << 8) | ((unsigned)(r2 & 0xff) << 16) | ((unsigned)r3 << 24);
 }
@@ -213,7 +301,8 @@ __global__ void __launch_bounds__(kThreads) convert_b_kernel(const double* __res
 }  // namespace
 
 hipError_t oz2_launch_stage1(int64_t m, int64_t n, int64_t k, const double* A, int64_t lda, const double* B,
-                             int64_t ldb, const Oz2Plan& plan, const Oz2Layout& lay, char* ws, hipStream_t st) {
+                             int64_t ldb, const Oz2Plan& plan, int shift_mode, const Oz2Layout& lay, char* ws,
+                             hipStream_t st) {
   unsigned long long* rowmax = reinterpret_cast<unsigned long long*>(ws + lay.off_rowmax);
   unsigned long long* colmax = reinterpret_cast<unsigned long long*>(ws + lay.off_colmax);
   int* sa = reinterpret_cast<int*>(ws + lay.off_sa);
@@ -229,22 +318,42 @@ hipError_t oz2_launch_stage1(int64_t m, int64_t n, int64_t k, const double* A, i
                      m, k, rowmax);
   hipLaunchKernelGGL(colmax_kernel, dim3((unsigned)n, blocks(k, kColMaxKC)), dim3(kThreads), 0, st, B, ldb, k,
                      colmax);
-  hipLaunchKernelGGL(shifts_kernel, dim3(blocks(lay.m_pad, kThreads)), dim3(kThreads), 0, st, rowmax, sa, lay.m_pad,
-                     plan.kappa);
-  hipLaunchKernelGGL(shifts_kernel, dim3(blocks(lay.n_pad, kThreads)), dim3(kThreads), 0, st, colmax, sb, lay.n_pad,
-                     plan.kappa);
+  // |a'| < 2^xbits decides how deep the conversion kernels split an element
+  int xbits = plan.kappa;
+  if (shift_mode == 1) {
+    unsigned long long* rownorm = reinterpret_cast<unsigned long long*>(ws + lay.off_rownorm);
+    unsigned long long* colnorm = reinterpret_cast<unsigned long long*>(ws + lay.off_colnorm);
+    hipLaunchKernelGGL(fill_u64_kernel, dim3(blocks(lay.m_pad, kThreads)), dim3(kThreads), 0, st, rownorm, lay.m_pad);
+    hipLaunchKernelGGL(fill_u64_kernel, dim3(blocks(lay.n_pad, kThreads)), dim3(kThreads), 0, st, colnorm, lay.n_pad);
+    hipLaunchKernelGGL(rownorm_kernel, dim3(blocks(m, kThreads), blocks(k, kRowMaxKC)), dim3(kThreads), 0, st, A, lda,
+                       m, k, rowmax, rownorm);
+    hipLaunchKernelGGL(colnorm_kernel, dim3((unsigned)n, blocks(k, kColMaxKC)), dim3(kThreads), 0, st, B, ldb, k,
+                       colmax, colnorm);
+    hipLaunchKernelGGL(shifts_cs_kernel, dim3(blocks(lay.m_pad, kThreads)), dim3(kThreads), 0, st, rowmax, rownorm, sa,
+                       lay.m_pad, plan.beta);
+    hipLaunchKernelGGL(shifts_cs_kernel, dim3(blocks(lay.n_pad, kThreads)), dim3(kThreads), 0, st, colmax, colnorm, sb,
+                       lay.n_pad, plan.beta);
+    xbits = plan.beta + 1;
+  } else {
+    hipLaunchKernelGGL(shifts_kernel, dim3(blocks(lay.m_pad, kThreads)), dim3(kThreads), 0, st, rowmax, sa, lay.m_pad,
+                       plan.kappa);
+    hipLaunchKernelGGL(shifts_kernel, dim3(blocks(lay.n_pad, kThreads)), dim3(kThreads), 0, st, colmax, sb, lay.n_pad,
+                       plan.kappa);
+  }
+  Oz2ConvConsts conv = plan.conv;
+  conv.two_level = xbits > 75;
   dim3 ga((unsigned)(lay.m_pad / kConvARows), (unsigned)(lay.k_pad / kBlkK));
   dim3 gb((unsigned)(lay.n_pad / kConvBCols), blocks(lay.k_pad, kConvBKC));
-  if (plan.conv.two_level) {
+  if (conv.two_level) {
     hipLaunchKernelGGL(convert_a_kernel<true>, ga, dim3(kThreads), 0, st, A, lda, m, k, lay.m_pad, lay.k_pad, sa, pa,
-                       plan.conv);
+                       conv);
     hipLaunchKernelGGL(convert_b_kernel<true>, gb, dim3(kThreads), 0, st, B, ldb, k, n, lay.n_pad, lay.k_pad, sb, pb,
-                       plan.conv);
+                       conv);
   } else {
     hipLaunchKernelGGL(convert_a_kernel<false>, ga, dim3(kThreads), 0, st, A, lda, m, k, lay.m_pad, lay.k_pad, sa,
-                       pa, plan.conv);
+                       pa, conv);
     hipLaunchKernelGGL(convert_b_kernel<false>, gb, dim3(kThreads), 0, st, B, ldb, k, n, lay.n_pad, lay.k_pad, sb,
-                       pb, plan.conv);
+                       pb, conv);
   }
   return hipGetLastError();
 }

@@ -19,7 +19,7 @@ def _dev(x):
     return torch.from_numpy(np.ascontiguousarray(x.T)).cuda().t()
 
 
-def run_stages(A, B, N, kblock=None):
+def run_stages(A, B, N, kblock=None, mode=0):
     m, k = A.shape
     _, n = B.shape
     ws = oz.Workspace(m, n, k, N)
@@ -28,8 +28,9 @@ def run_stages(A, B, N, kblock=None):
     dC = torch.full((n, m), float("nan"), dtype=torch.float64, device="cuda").t()
     if kblock is not None:
         oz.oz2_set_kblock(kblock)
+    oz.oz2_set_shift_mode(mode)
     try:
-        print("stage1 m=%d n=%d k=%d N=%d" % (m, n, k, N), flush=True)
+        print("stage1 m=%d n=%d k=%d N=%d mode=%d" % (m, n, k, N, mode), flush=True)
         oz.oz2_stage1_convert(m, n, k, dA.data_ptr(), m, dB.data_ptr(), k, N)
         torch.cuda.synchronize()
         print("stage2", flush=True)
@@ -39,6 +40,7 @@ def run_stages(A, B, N, kblock=None):
         oz.oz2_stage3_crt(m, n, k, dC.data_ptr(), m, N)
         torch.cuda.synchronize()
     finally:
+        oz.oz2_set_shift_mode(0)
         if kblock is not None:
             oz.oz2_set_kblock(65536)
     mp, np_, kp = lay["m_pad"], lay["n_pad"], lay["k_pad"]
@@ -59,11 +61,11 @@ def run_stages(A, B, N, kblock=None):
     return out
 
 
-def check_against_oracle(A, B, N, kblock=None, products_exact=True):
+def check_against_oracle(A, B, N, kblock=None, products_exact=True, mode=0):
     m, k = A.shape
     _, n = B.shape
-    got = run_stages(A, B, N, kblock)
-    ref = orc.dgemm(A, B, N, want=("C", "shifts", "Ares", "Bres", "Cprod", "Cres"))
+    got = run_stages(A, B, N, kblock, mode)
+    ref = orc.dgemm(A, B, N, want=("C", "shifts", "Ares", "Bres", "Cprod", "Cres"), mode=mode)
     assert np.array_equal(got["sa"][:m], ref.sa), "row shifts"
     assert np.array_equal(got["sb"][:n], ref.sb), "column shifts"
     assert np.array_equal(got["Ap"][:, :m, :k], ref.Ares), "A residue planes"
@@ -259,4 +261,53 @@ def test_full_size_configs_on_sampled_outputs(name, kblock):
     _, S = orc.exact(Asub, Bsub)
     assert np.all(np.abs(got - ref) <= 1e-15 * S)
     assert np.array_equal(got, ref), "%s: not bit-identical with the oracle" % name
+    del ws
+
+
+@pytest.mark.parametrize("m,n,k,N,phi", [
+    (256, 256, 256, 14, 0.5),     # config 1
+    (300, 200, 333, 5, 0.5),
+    (64, 40, 1000, 20, 4.0),      # beta + 1 = 78 bits: two-level split
+    (33, 17, 50, 26, 4.0),
+    (70, 90, 4200, 16, 1.0),      # more than one chunk of the column-norm kernel
+    (1, 1, 1, 2, 0.5),
+])
+def test_cauchy_schwarz_mode_all_stages(m, n, k, N, phi):
+    rng = np.random.default_rng(m * 7 + n)
+    A = (rng.random((m, k)) - 0.5) * np.exp(phi * rng.standard_normal((m, k)))
+    B = (rng.random((k, n)) - 0.5) * np.exp(phi * rng.standard_normal((k, n)))
+    if m > 4:
+        A[3, :] = 0.0
+        A[4, 1:] = 0.0
+        A[2, :] *= 2.0**-200
+    check_against_oracle(A, B, N, mode=1)
+
+
+def test_cauchy_schwarz_mode_full_size_c4_sampled():
+    cfg = inputs.CONFIGS["c4"]
+    m, n, k, phi, N = cfg["m"], cfg["n"], cfg["k"], cfg["phi"], 14
+    A = inputs.block(cfg["seed"], 0, m, k, phi)
+    B = inputs.block(cfg["seed"], 1, k, n, phi)
+    rng = np.random.default_rng(4)
+    rows = np.unique(np.concatenate([[0, m - 1], rng.choice(m, 30, replace=False)]))
+    cols = np.unique(np.concatenate([[0, n - 1], rng.choice(n, 30, replace=False)]))
+    dA = torch.from_numpy(A.T).cuda().t()
+    dB = torch.from_numpy(B.T).cuda().t()
+    dC = torch.full((n, m), float("nan"), dtype=torch.float64, device="cuda").t()
+    ws = oz.Workspace(m, n, k, N)
+    oz.oz2_set_shift_mode(1)
+    try:
+        oz.oz2_dgemm(m, n, k, dA.data_ptr(), m, dB.data_ptr(), k, dC.data_ptr(), m, N)
+        torch.cuda.synchronize()
+    finally:
+        oz.oz2_set_shift_mode(0)
+    got = dC[torch.from_numpy(rows).cuda()][:, torch.from_numpy(cols).cuda()].cpu().numpy()
+    Asub, Bsub = np.asfortranarray(A[rows, :]), np.asfortranarray(B[:, cols])
+    ref = orc.dgemm(Asub, Bsub, N, mode=1).C
+    Cx, S = orc.exact(Asub, Bsub)
+    assert np.array_equal(got, ref)
+    plain = orc.dgemm(Asub, Bsub, N, mode=0).C
+    e_fast, e_plain = np.max(np.abs(got - Cx) / S), np.max(np.abs(plain - Cx) / S)
+    print("N=14 at 16384^3: componentwise error Cauchy-Schwarz %.3g, simple bound %.3g" % (e_fast, e_plain), flush=True)
+    assert e_fast < e_plain
     del ws

@@ -320,3 +320,73 @@ def test_planted_mistakes_are_caught_by_the_pins():
     shifted = r.Cres.copy()
     shifted[1] = (shifted[1].astype(np.int64) + 1) % mods[1]
     assert rebuild(W, shifted) != r.X
+
+
+# ------------------------------------------------------------------ Section 4.1: Cauchy-Schwarz shift selection
+@pytest.mark.parametrize("N,phi", [(4, 0.5), (10, 1.0), (16, 0.5), (20, 4.0), (26, 4.0)])
+def test_cauchy_schwarz_shifts_are_rigorous_and_maximal(N, phi):
+    m, n, k = 6, 5, 9
+    A, B = _tiny(500 + N, m, n, k, phi)
+    A[1, :] = 0.0
+    A[2, 1:] = 0.0            # a single nonzero: the norm equals the maximum
+    mods = orc.moduli(N)
+    M = math.prod(mods)
+    beta = orc.beta(N)
+    assert 4**beta <= M // 2 - 1 < 4 ** (beta + 1)
+    r = orc.dgemm(A, B, N, mode=1, want=("C", "shifts", "Ap", "Bp", "X"))
+    assert r.sa[1] == 0
+
+    def check(vec, s):
+        sq = sum(Fraction(float(x)) ** 2 for x in vec)
+        if sq == 0:
+            return
+        # 2^s * ||vec||_2 <= 2^beta, compared on the squares with exact rationals
+        assert sq * Fraction(4) ** int(s) <= Fraction(4) ** beta
+        # maximal for the integer norm bound: with e, q, S, h as defined in the oracle's header
+        e = max(math.frexp(abs(float(x)))[1] - 1 for x in vec if x != 0)
+        S = sum(math.ceil(abs(Fraction(float(x))) * Fraction(2) ** (19 - e)) ** 2 for x in vec)
+        h = 0
+        while 4**h < S:
+            h += 1
+        assert s == beta - (e - 19 + h)
+        assert 4 ** (h - 1) < S                       # h is the smallest such exponent
+        assert sq <= Fraction(4) ** (e - 19) * S      # the integer norm bound is an upper bound
+
+    for i in range(m):
+        check(A[i, :], r.sa[i])
+    for j in range(n):
+        check(B[:, j], r.sb[j])
+    # uniqueness premise and exact reconstruction still hold
+    for i in range(m):
+        for j in range(n):
+            ex = sum(r.Ap[i][l] * r.Bp[l][j] for l in range(k))
+            assert sum(abs(r.Ap[i][l]) * abs(r.Bp[l][j]) for l in range(k)) < M // 2
+            assert r.X[i][j] == ex
+            assert r.C[i, j] == float(Fraction(ex) / Fraction(2) ** (int(r.sa[i]) + int(r.sb[j])))
+    # truncation toward zero with these shifts
+    for i in range(m):
+        for l in range(k):
+            assert r.Ap[i][l] == math.trunc(Fraction(float(A[i, l])) * Fraction(2) ** int(r.sa[i]))
+
+
+def test_cauchy_schwarz_reaches_native_accuracy_with_14_or_15_moduli():
+    # Section 4.1: at phi = 0.5 the variants the paper measures need 14 or 15 moduli for the accuracy of
+    # native FP64; the Cauchy-Schwarz shifts are never smaller than the simple ones by more than the
+    # norm/max ratio allows and the error is smaller at every moduli count below the rounding floor
+    cfg = inputs.CONFIGS["c2"]
+    k = cfg["k"]
+    rows = np.arange(0, 1024, 16)
+    cols = np.arange(3, 1024, 16)
+    A = inputs.block(cfg["seed"], 0, cfg["m"], k, cfg["phi"], row_idx=rows)
+    B = inputs.block(cfg["seed"], 1, k, cfg["n"], cfg["phi"], col_idx=cols)
+    Cx, S = orc.exact(A, B)
+    native = np.max(np.abs(A @ B - Cx) / S)
+    err = {}
+    for N in (10, 12, 13, 14, 15):
+        e0 = np.max(np.abs(orc.dgemm(A, B, N).C - Cx) / S)
+        e1 = np.max(np.abs(orc.dgemm(A, B, N, mode=1).C - Cx) / S)
+        assert e1 < e0
+        err[N] = e1
+    assert err[13] > native
+    assert err[15] < native
+    assert err[14] < 4 * native
