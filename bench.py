@@ -52,6 +52,7 @@ def main():
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
 
+    print("bench: generating inputs on the host ...", file=sys.stderr, flush=True)
     t0 = time.time()
     A = inputs.block(cfg["seed"], 0, m, k, phi)
     B = inputs.block(cfg["seed"], 1, k, n, phi)
@@ -79,6 +80,7 @@ def main():
         oz.oz2_set_stage_events(events)
         oz.oz2_dgemm(m, n, k, dA.data_ptr(), m, dB.data_ptr(), k, dC.data_ptr(), m, N, stream)
 
+    print("bench: timing %d steps ..." % args.steps, file=sys.stderr, flush=True)
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -104,6 +106,11 @@ def main():
     roofline = {"bound": "mfma", "kernel": "gemm_i8_kernel", "achieved": round(gemm_tops, 2),
                 "peak": INT8_MFMA_PEAK_TOPS, "unit": "TOP/s", "frac": round(gemm_tops / INT8_MFMA_PEAK_TOPS, 4),
                 "traffic": None, "avg_launch_ms": round(gemm_ms, 4)}
+    if args.workload == "c4" and N == 16:
+        # HBM-side bytes per launch from the rocprofv3 counter runs summarised in
+        # profiles/c4_oz2_dgemm_counters.md: FETCH_SIZE 54.186 GiB x 2.0 (copy-kernel scale) + WRITE_SIZE 19.125 GiB
+        roofline["traffic"] = round((54.186 * 2.0 + 19.125) * 2**30)
+        roofline["traffic_unit"] = "bytes per launch (L2 misses + write-backs; algorithmic minimum 24 GiB)"
     stages = {
         "stage1_convert_ms": round(float(avg[0]), 4),
         "stage2_gemm_ms": round(gemm_ms, 4),
@@ -126,7 +133,12 @@ def main():
     # accuracy + CPU baseline: the oracle on a bounded sample of the same workload
     if not args.no_cpu_baseline:
         from oracle import oracle as orc
-        nr, nc = (1024, 2048) if k >= 8192 else (min(m, 1024), min(n, 1024))
+        # sample size: about 5e11 residue multiply-adds for the oracle (10-20 s on 16 cores)
+        nr = 1
+        while 2 * (2 * nr) ** 2 * k * N <= 5.5e11 and 2 * nr <= m:
+            nr *= 2
+        nc = min(n, 2 * nr)
+        print("bench: oracle on a %d x %d sample of C ..." % (nr, nc), file=sys.stderr, flush=True)
         rng = np.random.default_rng(1)
         rows = np.sort(rng.choice(m, size=min(nr, m), replace=False))
         cols = np.sort(rng.choice(n, size=min(nc, n), replace=False))
