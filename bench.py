@@ -28,6 +28,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="c4")
     ap.add_argument("--moduli", type=int, default=0)
+    ap.add_argument("--mnk", default="", help="override the shape of the workload: m,n,k (same phi and seed)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-context", action="store_true")
     ap.add_argument("--shift-mode", type=int, default=0,
@@ -48,6 +49,8 @@ def main():
 
     cfg = inputs.CONFIGS[args.workload]
     m, n, k, phi = cfg["m"], cfg["n"], cfg["k"], cfg["phi"]
+    if args.mnk:
+        m, n, k = [int(v) for v in args.mnk.split(",")]
     N = args.moduli or (16 if args.workload == "c4" else cfg["N"][len(cfg["N"]) // 2])
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
@@ -106,7 +109,7 @@ def main():
     roofline = {"bound": "mfma", "kernel": "gemm_i8_kernel", "achieved": round(gemm_tops, 2),
                 "peak": INT8_MFMA_PEAK_TOPS, "unit": "TOP/s", "frac": round(gemm_tops / INT8_MFMA_PEAK_TOPS, 4),
                 "traffic": None, "avg_launch_ms": round(gemm_ms, 4)}
-    if args.workload == "c4" and N == 16:
+    if args.workload == "c4" and N == 16 and not args.mnk:
         # HBM-side bytes per launch from the rocprofv3 counter runs summarised in
         # profiles/c4_oz2_dgemm_counters.md: FETCH_SIZE 54.186 GiB x 2.0 (copy-kernel scale) + WRITE_SIZE 19.125 GiB
         roofline["traffic"] = round((54.186 * 2.0 + 19.125) * 2**30)
@@ -164,7 +167,7 @@ def main():
 
     # the metric is quoted per number of moduli: same workload, N = 14 .. 18 (a few calls each, outside the
     # timed region of the headline number above)
-    if args.workload == "c4" and not args.no_context:
+    if args.workload == "c4" and not args.no_context and not args.mnk:
         per_n = {}
         for Nx in (14, 15, 17, 18):
             del ws
@@ -184,7 +187,7 @@ def main():
         torch.cuda.synchronize()
 
     # context: the paper's tables time the Cauchy-Schwarz variant; same workload with 14 moduli in that mode
-    if args.workload == "c4" and not args.no_context and args.shift_mode == 0 and not args.no_cpu_baseline:
+    if args.workload == "c4" and not args.no_context and args.shift_mode == 0 and not args.no_cpu_baseline and not args.mnk:
         del ws
         ws = oz.Workspace(m, n, k, 14, device=dev)
         oz.oz2_set_shift_mode(1)

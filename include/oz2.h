@@ -79,6 +79,16 @@ int oz2_workspace_layout(int64_t m, int64_t n, int64_t k, int num_moduli, size_t
 int oz2_dgemm(int64_t m, int64_t n, int64_t k, const double* A, int64_t lda, const double* B, int64_t ldb,
               double* C, int64_t ldc, int num_moduli, void* stream);
 
+/* BLAS-style general form:  C := alpha * op(A) * op(B) + beta * C,  op(X) = X for 'N', X^T for 'T' or 'C'.
+ *   op(A) is m x k: A is stored m x k (lda >= max(1,m)) for 'N' and k x m (lda >= max(1,k)) otherwise;
+ *   op(B) is k x n: B is stored k x n (ldb >= max(1,k)) for 'N' and n x k (ldb >= max(1,n)) otherwise.
+ * The product P = op(A) op(B) is formed by Algorithm 1 exactly as in oz2_dgemm; then each element is
+ * C_ij := fma(alpha, P_ij, beta * C_ij) (beta * C_ij rounded once; C is not read when beta == 0).  With
+ * alpha == 1 and beta == 0 the result is P itself.  alpha == 0 or k == 0: C := beta * C, A and B are not
+ * touched.  Argument codes are 1-based over this parameter list. */
+int oz2_dgemm_ex(char transa, char transb, int64_t m, int64_t n, int64_t k, double alpha, const double* A, int64_t lda,
+                 const double* B, int64_t ldb, double beta, double* C, int64_t ldc, int num_moduli, void* stream);
+
 /* The three device stages of oz2_dgemm as separate calls (same kernels, same workspace); running them
  * in order is identical to oz2_dgemm.  They exist so that each stage can be tested and timed alone.
  *   oz2_stage1_convert : Algorithm 1 lines 1-5 (shifts, truncation, INT8 residues of A and B)

@@ -34,6 +34,7 @@ def lib():
         _lib.oz2o_sym_mod.argtypes = [ctypes.c_int64, ctypes.c_int]
         _lib.oz2o_kappa.argtypes = [ctypes.c_int, ctypes.c_void_p, ctypes.c_int64]
         _lib.oz2o_beta.argtypes = [ctypes.c_int, ctypes.c_void_p]
+        _lib.oz2o_axpby.argtypes = [ctypes.c_int64, ctypes.c_double, ctypes.c_void_p, ctypes.c_double, ctypes.c_void_p]
         _lib.oz2o_shifts.argtypes = [ctypes.c_int, ctypes.c_int64, ctypes.c_int64, ctypes.c_void_p,
                                      ctypes.c_int64, ctypes.c_int, ctypes.c_void_p]
         _lib.oz2o_dgemm_sub.argtypes = ([ctypes.c_int64] * 3 + [ctypes.c_void_p, ctypes.c_int64, ctypes.c_void_p,
@@ -159,6 +160,24 @@ def dgemm(A, B, N, mods=None, rows=None, cols=None, want=("C",), mode=0):
         out["Cres"] = np.ascontiguousarray(cres.transpose(0, 2, 1))
     if xs is not None:
         out["X"] = [[(-1 if xs[c, r] else 1) * _words_to_int(xm[c, r]) for c in range(nJ)] for r in range(nI)]
+    return out
+
+
+def dgemm_ex(transa, transb, alpha, A, B, beta, C, N, mode=0):
+    """C := alpha * op(A) op(B) + beta * C with the product formed by Algorithm 1 (see oz2o_axpby for the
+    order of the floating-point operations of the update).  A, B as stored; returns the new C."""
+    opA = A.T if transa in "TtCc" else A
+    opB = B.T if transb in "TtCc" else B
+    m, k = opA.shape
+    if k == 0 or alpha == 0.0:
+        P = np.zeros((m, opB.shape[1]), order="F")
+    else:
+        P = dgemm(opA, opB, N, mode=mode).C
+    out = np.array(C, dtype=np.float64, order="F", copy=True)
+    Pf = np.asfortranarray(P)
+    rc = lib().oz2o_axpby(out.size, float(alpha), _ptr(Pf), float(beta), _ptr(out))
+    if rc:
+        raise ValueError("oz2o_axpby -> %d" % rc)
     return out
 
 

@@ -567,6 +567,18 @@ int oz2o_dgemm_sub(int64_t m, int64_t n, int64_t k, const double* A, int64_t lda
   return 0;
 }
 
+// BLAS-style update with the product P already formed by Algorithm 1:
+//   C_e := alpha * P_e + beta * C_e, evaluated as one rounding of beta * C_e (skipped, and C not read, when
+//   beta == 0) followed by one fused multiply-add.
+int oz2o_axpby(int64_t count, double alpha, const double* P, double beta, double* C) {
+  if (count < 0) return -1;
+  for (int64_t e = 0; e < count; ++e) {
+    double t = beta == 0.0 ? 0.0 : beta * C[e];
+    C[e] = std::fma(alpha, P[e], t);
+  }
+  return 0;
+}
+
 // Reference product on the same subset in binary128: every product of two doubles is exact in 113 bits,
 // the sum is accumulated in binary128 (relative error about k * 2^-113 of sum |a||b|).
 // C_ref = rounded-to-double sum, absAB = sum_l |a_il| |b_lj| rounded to double.

@@ -155,7 +155,7 @@ int oz2_stage1_convert(int64_t m, int64_t n, int64_t k, const double* A, int64_t
   Oz2Layout lay;
   int rc = prepare(s, m, n, k, num_moduli, &plan, &lay);
   if (rc) return rc;
-  hipError_t e = oz2_launch_stage1(m, n, k, A, lda, B, ldb, *plan, s.shift_mode, lay, s.ws,
+  hipError_t e = oz2_launch_stage1(0, 0, m, n, k, A, lda, B, ldb, *plan, s.shift_mode, lay, s.ws,
                                    static_cast<hipStream_t>(stream));
   return e == hipSuccess ? OZ2_OK : OZ2_ERR_HIP;
 }
@@ -187,33 +187,50 @@ int oz2_stage3_crt(int64_t m, int64_t n, int64_t k, double* C, int64_t ldc, int 
   if (m == 0 || n == 0) return OZ2_OK;
   if (!C) return -4;
   hipStream_t st = static_cast<hipStream_t>(stream);
-  if (k == 0) return oz2_launch_zero_c(m, n, C, ldc, st) == hipSuccess ? OZ2_OK : OZ2_ERR_HIP;
+  if (k == 0) return oz2_launch_scale_c(m, n, 0.0, C, ldc, st) == hipSuccess ? OZ2_OK : OZ2_ERR_HIP;
   State& s = state();
   std::lock_guard<std::mutex> lock(s.mu);
   const Oz2Plan* plan;
   Oz2Layout lay;
   int rc = prepare(s, m, n, k, num_moduli, &plan, &lay);
   if (rc) return rc;
-  hipError_t e = oz2_launch_stage3(m, n, C, ldc, *plan, lay, s.ws, st);
+  hipError_t e = oz2_launch_stage3(m, n, 1.0, 0.0, C, ldc, *plan, lay, s.ws, st);
   return e == hipSuccess ? OZ2_OK : OZ2_ERR_HIP;
 }
 
-int oz2_dgemm(int64_t m, int64_t n, int64_t k, const double* A, int64_t lda, const double* B, int64_t ldb, double* C,
-              int64_t ldc, int num_moduli, void* stream) {
-  if (m < 0) return -1;
-  if (n < 0) return -2;
-  if (k < 0) return -3;
-  if (!dims_ok(m, n, k)) return -1;
-  if (lda < (m > 1 ? m : 1)) return -5;
-  if (ldb < (k > 1 ? k : 1)) return -7;
-  if (ldc < (m > 1 ? m : 1)) return -9;
-  if (!n_ok(num_moduli)) return -10;
+namespace {
+int trans_code(char c) {
+  switch (c) {
+    case 'N': case 'n': return 0;
+    case 'T': case 't': case 'C': case 'c': return 1;
+    default: return -1;
+  }
+}
+}  // namespace
+
+int oz2_dgemm_ex(char transa, char transb, int64_t m, int64_t n, int64_t k, double alpha, const double* A, int64_t lda,
+                 const double* B, int64_t ldb, double beta, double* C, int64_t ldc, int num_moduli, void* stream) {
+  const int ta = trans_code(transa), tb = trans_code(transb);
+  if (ta < 0) return -1;
+  if (tb < 0) return -2;
+  if (m < 0) return -3;
+  if (n < 0) return -4;
+  if (k < 0) return -5;
+  if (!dims_ok(m, n, k)) return -3;
+  const int64_t rows_a = ta ? k : m, rows_b = tb ? n : k;
+  if (lda < (rows_a > 1 ? rows_a : 1)) return -8;
+  if (ldb < (rows_b > 1 ? rows_b : 1)) return -10;
+  if (ldc < (m > 1 ? m : 1)) return -13;
+  if (!n_ok(num_moduli)) return -14;
   if (m == 0 || n == 0) return OZ2_OK;
-  if (!C) return -8;
+  if (!C) return -12;
   hipStream_t st = static_cast<hipStream_t>(stream);
-  if (k == 0) return oz2_launch_zero_c(m, n, C, ldc, st) == hipSuccess ? OZ2_OK : OZ2_ERR_HIP;
-  if (!A) return -4;
-  if (!B) return -6;
+  if (k == 0 || alpha == 0.0) {
+    if (beta == 1.0) return OZ2_OK;
+    return oz2_launch_scale_c(m, n, beta, C, ldc, st) == hipSuccess ? OZ2_OK : OZ2_ERR_HIP;
+  }
+  if (!A) return -7;
+  if (!B) return -9;
   State& s = state();
   std::lock_guard<std::mutex> lock(s.mu);
   const Oz2Plan* plan;
@@ -222,11 +239,30 @@ int oz2_dgemm(int64_t m, int64_t n, int64_t k, const double* A, int64_t lda, con
   if (rc) return rc;
   auto mark = [&](int i) { return !s.ev_on || hipEventRecord(s.ev[i], st) == hipSuccess; };
   if (!mark(0)) return OZ2_ERR_HIP;
-  if (oz2_launch_stage1(m, n, k, A, lda, B, ldb, *plan, s.shift_mode, lay, s.ws, st) != hipSuccess || !mark(1))
+  if (oz2_launch_stage1(ta, tb, m, n, k, A, lda, B, ldb, *plan, s.shift_mode, lay, s.ws, st) != hipSuccess || !mark(1))
     return OZ2_ERR_HIP;
   if (oz2_launch_stage2(*plan, lay, s.ws, s.kblock, st) != hipSuccess || !mark(2)) return OZ2_ERR_HIP;
-  if (oz2_launch_stage3(m, n, C, ldc, *plan, lay, s.ws, st) != hipSuccess || !mark(3)) return OZ2_ERR_HIP;
+  if (oz2_launch_stage3(m, n, alpha, beta, C, ldc, *plan, lay, s.ws, st) != hipSuccess || !mark(3)) return OZ2_ERR_HIP;
   return OZ2_OK;
+}
+
+int oz2_dgemm(int64_t m, int64_t n, int64_t k, const double* A, int64_t lda, const double* B, int64_t ldb, double* C,
+              int64_t ldc, int num_moduli, void* stream) {
+  // same argument numbering as the declaration: map the codes of the general entry point
+  int rc = oz2_dgemm_ex('N', 'N', m, n, k, 1.0, A, lda, B, ldb, 0.0, C, ldc, num_moduli, stream);
+  switch (rc) {
+    case -3: return -1;
+    case -4: return -2;
+    case -5: return -3;
+    case -7: return -4;
+    case -8: return -5;
+    case -9: return -6;
+    case -10: return -7;
+    case -12: return -8;
+    case -13: return -9;
+    case -14: return -10;
+    default: return rc;
+  }
 }
 
 int oz2_calibrate_mfma(int workgroups, int iters, int random_operands, int* sink, long long* clocks, void* stream) {

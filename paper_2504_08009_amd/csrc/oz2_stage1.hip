@@ -300,61 +300,70 @@ __global__ void __launch_bounds__(kThreads) convert_b_kernel(const double* __res
 
 }  // namespace
 
-hipError_t oz2_launch_stage1(int64_t m, int64_t n, int64_t k, const double* A, int64_t lda, const double* B,
-                             int64_t ldb, const Oz2Plan& plan, int shift_mode, const Oz2Layout& lay, char* ws,
-                             hipStream_t st) {
-  unsigned long long* rowmax = reinterpret_cast<unsigned long long*>(ws + lay.off_rowmax);
-  unsigned long long* colmax = reinterpret_cast<unsigned long long*>(ws + lay.off_colmax);
-  int* sa = reinterpret_cast<int*>(ws + lay.off_sa);
-  int* sb = reinterpret_cast<int*>(ws + lay.off_sb);
-  int8_t* pa = reinterpret_cast<int8_t*>(ws + lay.off_a);
-  int8_t* pb = reinterpret_cast<int8_t*>(ws + lay.off_b);
-  auto blocks = [](int64_t v, int64_t per) { return (unsigned)((v + per - 1) / per); };
+namespace {
 
-  // rowmax and colmax are adjacent in the workspace only up to alignment: clear them separately
-  hipLaunchKernelGGL(fill_u64_kernel, dim3(blocks(lay.m_pad, kThreads)), dim3(kThreads), 0, st, rowmax, lay.m_pad);
-  hipLaunchKernelGGL(fill_u64_kernel, dim3(blocks(lay.n_pad, kThreads)), dim3(kThreads), 0, st, colmax, lay.n_pad);
-  hipLaunchKernelGGL(rowmax_kernel, dim3(blocks(m, kThreads), blocks(k, kRowMaxKC)), dim3(kThreads), 0, st, A, lda,
-                     m, k, rowmax);
-  hipLaunchKernelGGL(colmax_kernel, dim3((unsigned)n, blocks(k, kColMaxKC)), dim3(kThreads), 0, st, B, ldb, k,
-                     colmax);
-  // |a'| < 2^xbits decides how deep the conversion kernels split an element
+// Everything stage 1 does for one operand.  The operand is a set of `nvec` vectors of length k (rows of
+// op(A) or columns of op(B)).  strided: element (v, l) at X[v + l*ld] (vectors are rows of a column-major
+// matrix); otherwise element (v, l) at X[l + v*ld] (vectors are its columns).
+void convert_operand(const double* X, int64_t ld, bool strided, int64_t nvec, int64_t nvec_pad, int64_t k, int64_t k_pad,
+                     unsigned long long* vmax, unsigned long long* vnorm, int* shifts, int8_t* planes,
+                     const Oz2Plan& plan, int shift_mode, hipStream_t st) {
+  auto blocks = [](int64_t v, int64_t per) { return (unsigned)((v + per - 1) / per); };
+  const dim3 thr(kThreads);
+  const dim3 g_vec(blocks(nvec_pad, kThreads));
+  const dim3 g_str(blocks(nvec, kThreads), blocks(k, kRowMaxKC));
+  const dim3 g_con((unsigned)nvec, blocks(k, kColMaxKC));
+  hipLaunchKernelGGL(fill_u64_kernel, g_vec, thr, 0, st, vmax, nvec_pad);
+  if (strided)
+    hipLaunchKernelGGL(rowmax_kernel, g_str, thr, 0, st, X, ld, nvec, k, vmax);
+  else
+    hipLaunchKernelGGL(colmax_kernel, g_con, thr, 0, st, X, ld, k, vmax);
+  // |x'| < 2^xbits decides how deep the conversion kernels split an element
   int xbits = plan.kappa;
   if (shift_mode == 1) {
-    unsigned long long* rownorm = reinterpret_cast<unsigned long long*>(ws + lay.off_rownorm);
-    unsigned long long* colnorm = reinterpret_cast<unsigned long long*>(ws + lay.off_colnorm);
-    hipLaunchKernelGGL(fill_u64_kernel, dim3(blocks(lay.m_pad, kThreads)), dim3(kThreads), 0, st, rownorm, lay.m_pad);
-    hipLaunchKernelGGL(fill_u64_kernel, dim3(blocks(lay.n_pad, kThreads)), dim3(kThreads), 0, st, colnorm, lay.n_pad);
-    hipLaunchKernelGGL(rownorm_kernel, dim3(blocks(m, kThreads), blocks(k, kRowMaxKC)), dim3(kThreads), 0, st, A, lda,
-                       m, k, rowmax, rownorm);
-    hipLaunchKernelGGL(colnorm_kernel, dim3((unsigned)n, blocks(k, kColMaxKC)), dim3(kThreads), 0, st, B, ldb, k,
-                       colmax, colnorm);
-    hipLaunchKernelGGL(shifts_cs_kernel, dim3(blocks(lay.m_pad, kThreads)), dim3(kThreads), 0, st, rowmax, rownorm, sa,
-                       lay.m_pad, plan.beta);
-    hipLaunchKernelGGL(shifts_cs_kernel, dim3(blocks(lay.n_pad, kThreads)), dim3(kThreads), 0, st, colmax, colnorm, sb,
-                       lay.n_pad, plan.beta);
+    hipLaunchKernelGGL(fill_u64_kernel, g_vec, thr, 0, st, vnorm, nvec_pad);
+    if (strided)
+      hipLaunchKernelGGL(rownorm_kernel, g_str, thr, 0, st, X, ld, nvec, k, vmax, vnorm);
+    else
+      hipLaunchKernelGGL(colnorm_kernel, g_con, thr, 0, st, X, ld, k, vmax, vnorm);
+    hipLaunchKernelGGL(shifts_cs_kernel, g_vec, thr, 0, st, vmax, vnorm, shifts, nvec_pad, plan.beta);
     xbits = plan.beta + 1;
   } else {
-    hipLaunchKernelGGL(shifts_kernel, dim3(blocks(lay.m_pad, kThreads)), dim3(kThreads), 0, st, rowmax, sa, lay.m_pad,
-                       plan.kappa);
-    hipLaunchKernelGGL(shifts_kernel, dim3(blocks(lay.n_pad, kThreads)), dim3(kThreads), 0, st, colmax, sb, lay.n_pad,
-                       plan.kappa);
+    hipLaunchKernelGGL(shifts_kernel, g_vec, thr, 0, st, vmax, shifts, nvec_pad, plan.kappa);
   }
   Oz2ConvConsts conv = plan.conv;
   conv.two_level = xbits > 75;
-  dim3 ga((unsigned)(lay.m_pad / kConvARows), (unsigned)(lay.k_pad / kBlkK));
-  dim3 gb((unsigned)(lay.n_pad / kConvBCols), blocks(lay.k_pad, kConvBKC));
-  if (conv.two_level) {
-    hipLaunchKernelGGL(convert_a_kernel<true>, ga, dim3(kThreads), 0, st, A, lda, m, k, lay.m_pad, lay.k_pad, sa, pa,
-                       conv);
-    hipLaunchKernelGGL(convert_b_kernel<true>, gb, dim3(kThreads), 0, st, B, ldb, k, n, lay.n_pad, lay.k_pad, sb, pb,
-                       conv);
+  const dim3 ga((unsigned)(nvec_pad / kConvARows), (unsigned)(k_pad / kBlkK));
+  const dim3 gb((unsigned)(nvec_pad / kConvBCols), blocks(k_pad, kConvBKC));
+  if (strided) {
+    if (conv.two_level)
+      hipLaunchKernelGGL(convert_a_kernel<true>, ga, thr, 0, st, X, ld, nvec, k, nvec_pad, k_pad, shifts, planes, conv);
+    else
+      hipLaunchKernelGGL(convert_a_kernel<false>, ga, thr, 0, st, X, ld, nvec, k, nvec_pad, k_pad, shifts, planes, conv);
   } else {
-    hipLaunchKernelGGL(convert_a_kernel<false>, ga, dim3(kThreads), 0, st, A, lda, m, k, lay.m_pad, lay.k_pad, sa,
-                       pa, conv);
-    hipLaunchKernelGGL(convert_b_kernel<false>, gb, dim3(kThreads), 0, st, B, ldb, k, n, lay.n_pad, lay.k_pad, sb,
-                       pb, conv);
+    if (conv.two_level)
+      hipLaunchKernelGGL(convert_b_kernel<true>, gb, thr, 0, st, X, ld, k, nvec, nvec_pad, k_pad, shifts, planes, conv);
+    else
+      hipLaunchKernelGGL(convert_b_kernel<false>, gb, thr, 0, st, X, ld, k, nvec, nvec_pad, k_pad, shifts, planes, conv);
   }
+}
+
+}  // namespace
+
+// transa / transb: 0 = the operand is stored as op(X) (column-major), 1 = it is stored transposed.
+hipError_t oz2_launch_stage1(int transa, int transb, int64_t m, int64_t n, int64_t k, const double* A, int64_t lda,
+                             const double* B, int64_t ldb, const Oz2Plan& plan, int shift_mode, const Oz2Layout& lay,
+                             char* ws, hipStream_t st) {
+  // rows of op(A): strided in a stored m x k matrix, contiguous in a stored k x m matrix
+  convert_operand(A, lda, transa == 0, m, lay.m_pad, k, lay.k_pad,
+                  reinterpret_cast<unsigned long long*>(ws + lay.off_rowmax),
+                  reinterpret_cast<unsigned long long*>(ws + lay.off_rownorm), reinterpret_cast<int*>(ws + lay.off_sa),
+                  reinterpret_cast<int8_t*>(ws + lay.off_a), plan, shift_mode, st);
+  // columns of op(B): contiguous in a stored k x n matrix, strided in a stored n x k matrix
+  convert_operand(B, ldb, transb != 0, n, lay.n_pad, k, lay.k_pad,
+                  reinterpret_cast<unsigned long long*>(ws + lay.off_colmax),
+                  reinterpret_cast<unsigned long long*>(ws + lay.off_colnorm), reinterpret_cast<int*>(ws + lay.off_sb),
+                  reinterpret_cast<int8_t*>(ws + lay.off_b), plan, shift_mode, st);
   return hipGetLastError();
 }
 

@@ -16,7 +16,7 @@ template <int L>
 __global__ void __launch_bounds__(kThreads) crt_kernel(const int* __restrict__ cplanes, int64_t m_pad, int64_t n_pad,
                                                        const int* __restrict__ sa, const int* __restrict__ sb,
                                                        double* __restrict__ C, int64_t ldc, int64_t m, int64_t n,
-                                                       const Oz2CrtConsts cc) {
+                                                       const double alpha, const double beta, const Oz2CrtConsts cc) {
   const int64_t j = blockIdx.x;
   const int64_t i0 = ((int64_t)blockIdx.y * kThreads + threadIdx.x) * kRowsPerThread;
   if (i0 >= m) return;
@@ -56,14 +56,29 @@ __global__ void __launch_bounds__(kThreads) crt_kernel(const int* __restrict__ c
     out[r] = ldexp(x, e2 - sa[i0 + r] - sbj);   // sa is padded to m_pad (a multiple of 256): always readable
   }
   double* dst = C + i0 + j * ldc;
+  if (alpha == 1.0 && beta == 0.0) {
 #pragma unroll
-  for (int r = 0; r < kRowsPerThread; ++r)
-    if (i0 + r < m) dst[r] = out[r];
+    for (int r = 0; r < kRowsPerThread; ++r)
+      if (i0 + r < m) dst[r] = out[r];
+  } else {
+    // C := alpha * P + beta * C with one rounding of beta * C and one fused multiply-add; C is not read
+    // when beta is zero (BLAS convention)
+#pragma unroll
+    for (int r = 0; r < kRowsPerThread; ++r)
+      if (i0 + r < m) {
+        const double t = beta == 0.0 ? 0.0 : beta * dst[r];
+        dst[r] = fma(alpha, out[r], t);
+      }
+  }
 }
 
-__global__ void __launch_bounds__(kThreads) zero_c_kernel(double* __restrict__ C, int64_t ldc, int64_t m) {
+// C := beta * C (zero without reading C when beta is zero): the k == 0 and alpha == 0 cases
+__global__ void __launch_bounds__(kThreads) scale_c_kernel(double* __restrict__ C, int64_t ldc, int64_t m, double beta) {
   int64_t i = (int64_t)blockIdx.y * kThreads + threadIdx.x;
-  if (i < m) C[i + (int64_t)blockIdx.x * ldc] = 0.0;
+  if (i < m) {
+    double* p = C + i + (int64_t)blockIdx.x * ldc;
+    *p = beta == 0.0 ? 0.0 : beta * *p;
+  }
 }
 
 template <int L>
@@ -81,8 +96,8 @@ double host_crt(const Oz2CrtConsts& cc, const int32_t* cprod) {
 
 }  // namespace
 
-hipError_t oz2_launch_stage3(int64_t m, int64_t n, double* C, int64_t ldc, const Oz2Plan& plan,
-                             const Oz2Layout& lay, char* ws, hipStream_t st) {
+hipError_t oz2_launch_stage3(int64_t m, int64_t n, double alpha, double beta, double* C, int64_t ldc,
+                             const Oz2Plan& plan, const Oz2Layout& lay, char* ws, hipStream_t st) {
   const int* cplanes = reinterpret_cast<const int*>(ws + lay.off_c);
   const int* sa = reinterpret_cast<const int*>(ws + lay.off_sa);
   const int* sb = reinterpret_cast<const int*>(ws + lay.off_sb);
@@ -92,7 +107,7 @@ hipError_t oz2_launch_stage3(int64_t m, int64_t n, double* C, int64_t ldc, const
 #define OZ2_CASE(LL)                                                                                          \
   case LL:                                                                                                    \
     hipLaunchKernelGGL(crt_kernel<LL>, grid, dim3(kThreads), 0, st, cplanes, lay.m_pad, lay.n_pad, sa, sb, C, \
-                       ldc, m, n, plan.crt);                                                                  \
+                       ldc, m, n, alpha, beta, plan.crt);                                                                  \
     break;
     OZ2_CASE(1)
     OZ2_CASE(2)
@@ -106,9 +121,9 @@ hipError_t oz2_launch_stage3(int64_t m, int64_t n, double* C, int64_t ldc, const
   return hipGetLastError();
 }
 
-hipError_t oz2_launch_zero_c(int64_t m, int64_t n, double* C, int64_t ldc, hipStream_t st) {
+hipError_t oz2_launch_scale_c(int64_t m, int64_t n, double beta, double* C, int64_t ldc, hipStream_t st) {
   dim3 grid((unsigned)n, (unsigned)((m + kThreads - 1) / kThreads));
-  hipLaunchKernelGGL(zero_c_kernel, grid, dim3(kThreads), 0, st, C, ldc, m);
+  hipLaunchKernelGGL(scale_c_kernel, grid, dim3(kThreads), 0, st, C, ldc, m, beta);
   return hipGetLastError();
 }
 

@@ -311,3 +311,50 @@ def test_cauchy_schwarz_mode_full_size_c4_sampled():
     print("N=14 at 16384^3: componentwise error Cauchy-Schwarz %.3g, simple bound %.3g" % (e_fast, e_plain), flush=True)
     assert e_fast < e_plain
     del ws
+
+
+@pytest.mark.parametrize("ta,tb", [("N", "N"), ("T", "N"), ("N", "T"), ("T", "T")])
+@pytest.mark.parametrize("alpha,beta", [(1.0, 0.0), (-0.75, 1.5), (2.0, 1.0)])
+def test_dgemm_ex_transposes_and_scalars(ta, tb, alpha, beta):
+    rng = np.random.default_rng(11)
+    m, n, k, N = 300, 270, 333, 15
+    opA = (rng.random((m, k)) - 0.5) * np.exp(rng.standard_normal((m, k)))
+    opB = (rng.random((k, n)) - 0.5) * np.exp(rng.standard_normal((k, n)))
+    As = np.asfortranarray(opA.T if ta == "T" else opA)   # as stored
+    Bs = np.asfortranarray(opB.T if tb == "T" else opB)
+    C0 = np.asfortranarray(rng.standard_normal((m, n)))
+    if beta == 0.0:
+        C0[:] = np.nan      # must not be read
+    dA, dB = _dev(As), _dev(Bs)
+    dC = torch.from_numpy(np.ascontiguousarray(C0.T)).cuda().t()
+    ws = oz.Workspace(m, n, k, N)
+    oz.oz2_dgemm_ex(ta, tb, m, n, k, alpha, dA.data_ptr(), As.shape[0], dB.data_ptr(), Bs.shape[0], beta,
+                    dC.data_ptr(), m, N)
+    torch.cuda.synchronize()
+    got = dC.cpu().numpy()
+    ref = orc.dgemm_ex(ta, tb, alpha, As, Bs, beta, C0, N)
+    assert np.array_equal(got, ref)
+    del ws
+
+
+def test_dgemm_ex_degenerate_cases():
+    m, n, k, N = 40, 30, 50, 8
+    rng = np.random.default_rng(2)
+    C0 = np.asfortranarray(rng.standard_normal((m, n)))
+    dC = torch.from_numpy(np.ascontiguousarray(C0.T)).cuda().t()
+    dX = torch.full((64, 64), float("nan"), dtype=torch.float64, device="cuda")
+    ws = oz.Workspace(m, n, k, N)
+    # alpha == 0: C := beta * C, A and B untouched (NaN-filled here)
+    oz.oz2_dgemm_ex("N", "N", m, n, k, 0.0, dX.data_ptr(), 64, dX.data_ptr(), 64, 0.5, dC.data_ptr(), m, N)
+    torch.cuda.synchronize()
+    assert np.array_equal(dC.cpu().numpy(), 0.5 * C0)
+    # k == 0 and beta == 0: zeros
+    oz.oz2_dgemm_ex("T", "T", m, n, 0, 1.0, None, 1, None, n, 0.0, dC.data_ptr(), m, N)
+    torch.cuda.synchronize()
+    assert not dC.cpu().numpy().any()
+    L = oz.lib()
+    st = torch.cuda.current_stream().cuda_stream
+    assert L.oz2_dgemm_ex(b"X", b"N", 4, 4, 4, 1.0, dX.data_ptr(), 4, dX.data_ptr(), 4, 0.0, dC.data_ptr(), 4, 8, st) == -1
+    assert L.oz2_dgemm_ex(b"T", b"N", 4, 4, 9, 1.0, dX.data_ptr(), 8, dX.data_ptr(), 9, 0.0, dC.data_ptr(), 4, 8, st) == -8
+    assert L.oz2_dgemm_ex(b"N", b"T", 4, 7, 9, 1.0, dX.data_ptr(), 4, dX.data_ptr(), 6, 0.0, dC.data_ptr(), 4, 8, st) == -10
+    del ws

@@ -390,3 +390,22 @@ def test_cauchy_schwarz_reaches_native_accuracy_with_14_or_15_moduli():
     assert err[13] > native
     assert err[15] < native
     assert err[14] < 4 * native
+
+
+def test_blas_update_against_rationals():
+    # C := alpha * P + beta * C: one rounding of beta*C, then a fused multiply-add; beta == 0 ignores C
+    A, B = _tiny(61, 4, 3, 6, 0.5)
+    C0 = np.asfortranarray(np.random.default_rng(1).standard_normal((4, 3)))
+    P = orc.dgemm(A, B, 12).C
+    for alpha, beta in [(1.0, 0.0), (0.75, -1.25), (-3.0, 1.0), (1e-3, 7.0), (0.0, 0.5), (2.0, 0.0)]:
+        got = orc.dgemm_ex("N", "N", alpha, A, B, beta, C0, 12)
+        for i in range(4):
+            for j in range(3):
+                t = 0.0 if beta == 0.0 else float(Fraction(beta) * Fraction(float(C0[i, j])))
+                want = float(Fraction(alpha) * Fraction(float(P[i, j])) + Fraction(t))
+                assert got[i, j] == want
+    Cn = np.full((4, 3), np.nan, order="F")
+    assert np.array_equal(orc.dgemm_ex("N", "N", 1.0, A, B, 0.0, Cn, 12), P)
+    # transposes only change how the operands are read
+    assert np.array_equal(orc.dgemm_ex("T", "N", 1.0, np.asfortranarray(A.T), B, 0.0, Cn, 12), P)
+    assert np.array_equal(orc.dgemm_ex("N", "T", 1.0, A, np.asfortranarray(B.T), 0.0, Cn, 12), P)
