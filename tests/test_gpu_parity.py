@@ -358,3 +358,19 @@ def test_dgemm_ex_degenerate_cases():
     assert L.oz2_dgemm_ex(b"T", b"N", 4, 4, 9, 1.0, dX.data_ptr(), 8, dX.data_ptr(), 9, 0.0, dC.data_ptr(), 4, 8, st) == -8
     assert L.oz2_dgemm_ex(b"N", b"T", 4, 7, 9, 1.0, dX.data_ptr(), 4, dX.data_ptr(), 6, 0.0, dC.data_ptr(), 4, 8, st) == -10
     del ws
+
+
+def test_inner_dimension_beyond_int32_exactness():
+    # k > 2^17: one INT32 accumulation would overflow (Section 3.1); the default k-block of 65536 applies
+    rng = np.random.default_rng(13)
+    m, n, k, N = 48, 40, 140000, 16
+    A = rng.standard_normal((m, k))
+    B = rng.standard_normal((k, n))
+    # a row and a column whose scaled integers are 2^(kappa-1) + 128: residue -128 modulo 256 in every
+    # position, so the exact product for that modulus is k * 16384 > 2^31
+    kap = orc.kappa(N, k)
+    A[0, :] = 1.0 + 128.0 * 2.0 ** -(kap - 1)
+    B[:, 0] = 1.0 + 128.0 * 2.0 ** -(kap - 1)
+    got, ref = check_against_oracle(A, B, N, products_exact=False)
+    # the exact products really exceed INT32 somewhere, so blocking was needed
+    assert np.max(np.abs(ref.Cprod)) > 2**31
