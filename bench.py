@@ -33,6 +33,8 @@ def main():
     ap.add_argument("--no-context", action="store_true")
     ap.add_argument("--shift-mode", type=int, default=0,
                     help="0: shifts from maxima (Section 3, default); 1: Cauchy-Schwarz bound (Section 4.1)")
+    ap.add_argument("--product-format", type=int, default=-1,
+                    help="0: INT32 product planes; 1: UINT8 residue planes (library default)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain device copy of A (known size) so that rocprofv3 byte counters can be scaled")
     args = ap.parse_args()
@@ -66,6 +68,8 @@ def main():
     ws = oz.Workspace(m, n, k, N, device=dev)
     stream = torch.cuda.current_stream()
     oz.oz2_set_shift_mode(args.shift_mode)
+    fmt = args.product_format if args.product_format >= 0 else oz.OZ2_PRODUCT_RESIDUE_U8
+    oz.oz2_set_product_format(fmt)
 
     hip = ctypes.CDLL("libamdhip64.so")
     def new_event():
@@ -105,7 +109,7 @@ def main():
     gemm_ms = float(avg[1])
     gemm_tops = 2.0 * m * n * k * N / (gemm_ms * 1e-3) / 1e12
     s1_bytes = (16 + N) * (m * k + k * n) + 4 * (m + n)
-    s3_bytes = (4 * N + 8) * m * n + 4 * (m + n)
+    s3_bytes = ((1 if fmt == oz.OZ2_PRODUCT_RESIDUE_U8 else 4) * N + 8) * m * n + 4 * (m + n)
     roofline = {"bound": "mfma", "kernel": "gemm_i8_kernel", "achieved": round(gemm_tops, 2),
                 "peak": INT8_MFMA_PEAK_TOPS, "unit": "TOP/s", "frac": round(gemm_tops / INT8_MFMA_PEAK_TOPS, 4),
                 "traffic": None, "avg_launch_ms": round(gemm_ms, 4)}
@@ -129,7 +133,8 @@ def main():
         "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "int8", "data": "synthetic",
         "config": {"workload": "%s: m=%d n=%d k=%d phi=%g, %d moduli, seed %d" % (args.workload, m, n, k, phi, N, cfg["seed"]),
-                   "num_moduli": N, "entry_point": "oz2_dgemm", "shift_mode": args.shift_mode, "host_input_generation_s": round(gen_s, 1)},
+                   "num_moduli": N, "entry_point": "oz2_dgemm", "shift_mode": args.shift_mode,
+                   "product_format": "uint8 residues" if fmt == oz.OZ2_PRODUCT_RESIDUE_U8 else "int32", "host_input_generation_s": round(gen_s, 1)},
         "roofline": roofline, "stages": stages,
     }
 

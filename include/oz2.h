@@ -32,6 +32,9 @@ extern "C" {
 #define OZ2_ERR_BUDGET 2
 #define OZ2_ERR_HIP 3
 
+#define OZ2_PRODUCT_INT32 0      /* stage 2 writes the INT32 products C'_t (Algorithm 1 line 6) */
+#define OZ2_PRODUCT_RESIDUE_U8 1 /* stage 2 writes C''_t = C'_t mod p_t as UINT8 (lines 6 and 7 together); default */
+
 #define OZ2_SHIFT_MAX 0            /* shifts from row/column maxima: the simple bound of Section 3 */
 #define OZ2_SHIFT_CAUCHY_SCHWARZ 1 /* shifts from row/column 2-norms: Section 4.1, the "fast" variant */
 
@@ -65,7 +68,9 @@ int oz2_set_workspace(void* dev_ptr, size_t bytes);
  *               ((t*m_pad + 256*(i/256)) * k_pad) + (l/64)*16384 + (i%256)*64 + (l%64)
  *   5 B planes: num_moduli x n_pad x k_pad int8 residues of B' (line 5), same blocking with the column
  *               index j of B in the place of i and n_pad in the place of m_pad
- *   6 C planes: num_moduli x n_pad x m_pad int32, plane t element (i,j) at ((t*n_pad)+j)*m_pad + i
+ *   6 C planes: num_moduli x n_pad x m_pad, plane t element (i,j) at index ((t*n_pad)+j)*m_pad + i; the
+ *               elements are int32 products (OZ2_PRODUCT_INT32) or uint8 residues in [0, p_t)
+ *               (OZ2_PRODUCT_RESIDUE_U8, the planes then fill the first quarter of the region)
  *   7 rownorm : m_pad uint64, integer norm bound S_i of A's rows (Cauchy-Schwarz shift mode only)
  *   8 colnorm : n_pad uint64, same per column of B
  * dims[0..2] = m_pad, n_pad, k_pad (m, n rounded up to 256, k to 64; padding holds zeros).
@@ -92,12 +97,20 @@ int oz2_dgemm_ex(char transa, char transb, int64_t m, int64_t n, int64_t k, doub
 /* The three device stages of oz2_dgemm as separate calls (same kernels, same workspace); running them
  * in order is identical to oz2_dgemm.  They exist so that each stage can be tested and timed alone.
  *   oz2_stage1_convert : Algorithm 1 lines 1-5 (shifts, truncation, INT8 residues of A and B)
- *   oz2_stage2_gemm    : line 6 (INT32 products of the residue planes, all moduli)
+ *   oz2_stage2_gemm    : line 6 (products of the residue planes, all moduli; with line 7 in its epilogue
+ *                        in the default product format)
  *   oz2_stage3_crt     : lines 7-11 (residues of the products, CRT accumulation, mod M, inverse scaling) */
 int oz2_stage1_convert(int64_t m, int64_t n, int64_t k, const double* A, int64_t lda, const double* B,
                        int64_t ldb, int num_moduli, void* stream);
 int oz2_stage2_gemm(int64_t m, int64_t n, int64_t k, int num_moduli, void* stream);
 int oz2_stage3_crt(int64_t m, int64_t n, int64_t k, double* C, int64_t ldc, int num_moduli, void* stream);
+
+/* What stage 2 leaves in the C planes, for all later calls.  OZ2_PRODUCT_RESIDUE_U8 (default): the GEMM
+ * epilogue takes Algorithm 1 line 7 (c'' = c' - floor(c'/p_t) p_t) and stores one byte per element, so that
+ * stage 3 reads a quarter of the bytes.  OZ2_PRODUCT_INT32: the INT32 products themselves are stored (exact
+ * for k < 2^17; with k-blocking a value congruent to the product modulo p_t) and stage 3 takes line 7.
+ * The final C is identical in both formats.  Returns 0 or -1. */
+int oz2_set_product_format(int format);
 
 /* How Algorithm 1 line 1 picks the shifts, for all later calls (default OZ2_SHIFT_MAX).
  *   OZ2_SHIFT_MAX: sa_i = kappa - 1 - floor(log2 max_l |a_il|) with the bit budget kappa of Section 3.

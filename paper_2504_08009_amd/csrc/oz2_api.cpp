@@ -12,6 +12,7 @@ struct State {
   size_t ws_bytes = 0;
   int64_t kblock = 65536;
   int shift_mode = 0;
+  int product_format = OZ2_PRODUCT_RESIDUE_U8;
   hipEvent_t ev[4] = {nullptr, nullptr, nullptr, nullptr};
   bool ev_on = false;
   Oz2Plan plan;
@@ -129,6 +130,14 @@ int oz2_set_shift_mode(int mode) {
   return OZ2_OK;
 }
 
+int oz2_set_product_format(int format) {
+  if (format != OZ2_PRODUCT_INT32 && format != OZ2_PRODUCT_RESIDUE_U8) return -1;
+  State& s = state();
+  std::lock_guard<std::mutex> lock(s.mu);
+  s.product_format = format;
+  return OZ2_OK;
+}
+
 int oz2_set_kblock(int64_t kblock) {
   if (kblock < OZ2_TILE_K || kblock > 65536 || kblock % OZ2_TILE_K) return -1;
   State& s = state();
@@ -173,7 +182,7 @@ int oz2_stage2_gemm(int64_t m, int64_t n, int64_t k, int num_moduli, void* strea
   Oz2Layout lay;
   int rc = prepare(s, m, n, k, num_moduli, &plan, &lay);
   if (rc) return rc;
-  hipError_t e = oz2_launch_stage2(*plan, lay, s.ws, s.kblock, static_cast<hipStream_t>(stream));
+  hipError_t e = oz2_launch_stage2(*plan, lay, s.ws, s.kblock, s.product_format, static_cast<hipStream_t>(stream));
   return e == hipSuccess ? OZ2_OK : OZ2_ERR_HIP;
 }
 
@@ -194,7 +203,7 @@ int oz2_stage3_crt(int64_t m, int64_t n, int64_t k, double* C, int64_t ldc, int 
   Oz2Layout lay;
   int rc = prepare(s, m, n, k, num_moduli, &plan, &lay);
   if (rc) return rc;
-  hipError_t e = oz2_launch_stage3(m, n, 1.0, 0.0, C, ldc, *plan, lay, s.ws, st);
+  hipError_t e = oz2_launch_stage3(m, n, 1.0, 0.0, C, ldc, *plan, lay, s.ws, s.product_format, st);
   return e == hipSuccess ? OZ2_OK : OZ2_ERR_HIP;
 }
 
@@ -241,8 +250,9 @@ int oz2_dgemm_ex(char transa, char transb, int64_t m, int64_t n, int64_t k, doub
   if (!mark(0)) return OZ2_ERR_HIP;
   if (oz2_launch_stage1(ta, tb, m, n, k, A, lda, B, ldb, *plan, s.shift_mode, lay, s.ws, st) != hipSuccess || !mark(1))
     return OZ2_ERR_HIP;
-  if (oz2_launch_stage2(*plan, lay, s.ws, s.kblock, st) != hipSuccess || !mark(2)) return OZ2_ERR_HIP;
-  if (oz2_launch_stage3(m, n, alpha, beta, C, ldc, *plan, lay, s.ws, st) != hipSuccess || !mark(3)) return OZ2_ERR_HIP;
+  if (oz2_launch_stage2(*plan, lay, s.ws, s.kblock, s.product_format, st) != hipSuccess || !mark(2)) return OZ2_ERR_HIP;
+  if (oz2_launch_stage3(m, n, alpha, beta, C, ldc, *plan, lay, s.ws, s.product_format, st) != hipSuccess || !mark(3))
+    return OZ2_ERR_HIP;
   return OZ2_OK;
 }
 

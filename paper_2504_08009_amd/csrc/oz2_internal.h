@@ -63,9 +63,10 @@ void oz2_make_layout(int64_t m, int64_t n, int64_t k, int N, Oz2Layout* lay);
 hipError_t oz2_launch_stage1(int transa, int transb, int64_t m, int64_t n, int64_t k, const double* A, int64_t lda,
                              const double* B, int64_t ldb, const Oz2Plan& plan, int shift_mode, const Oz2Layout& lay,
                              char* ws, hipStream_t st);
-hipError_t oz2_launch_stage2(const Oz2Plan& plan, const Oz2Layout& lay, char* ws, int64_t kblock, hipStream_t st);
+hipError_t oz2_launch_stage2(const Oz2Plan& plan, const Oz2Layout& lay, char* ws, int64_t kblock, int residue_u8,
+                             hipStream_t st);
 hipError_t oz2_launch_stage3(int64_t m, int64_t n, double alpha, double beta, double* C, int64_t ldc,
-                             const Oz2Plan& plan, const Oz2Layout& lay, char* ws, hipStream_t st);
+                             const Oz2Plan& plan, const Oz2Layout& lay, char* ws, int residue_u8, hipStream_t st);
 hipError_t oz2_launch_scale_c(int64_t m, int64_t n, double beta, double* C, int64_t ldc, hipStream_t st);
 
 hipError_t oz2_launch_mfma_calibration(int workgroups, int iters, int random_operands, int* sink, long long* clocks,

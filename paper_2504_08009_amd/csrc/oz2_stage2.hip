@@ -7,7 +7,8 @@
 // Rows and the inner dimension are zero padded to the tile sizes, so the kernel has no edge cases, and
 // every global -> LDS copy of a k-tile reads contiguous kilobytes (a row-major plane with a power-of-two
 // pitch would hit the same L2 channels with all 256 rows of a tile).  Output plane t holds element (i,j)
-// at (j*m_pad + i), i contiguous.
+// at (j*m_pad + i), i contiguous: either the INT32 product itself, or (RESIDUE_U8) its residue in [0, p_t) as
+// one byte (Algorithm 1 line 7 taken in the epilogue; four times less to write here and to read in stage 3).
 //
 // One workgroup (4 waves, one per SIMD) computes a 256 x 256 tile of one modulus.  Each wave owns a
 // 128 x 128 sub-tile = 4 x 4 MFMA tiles of 32 x 32 (256 accumulator registers).  The inner dimension is
@@ -94,6 +95,7 @@ struct Frag {
   v4i a[4], b[4];
 };
 
+template <bool RESIDUE_U8>
 __global__ void __launch_bounds__(kThreads) gemm_i8_kernel(const GemmArgs g) {
   extern __shared__ __attribute__((aligned(1024))) char lds[];
 
@@ -170,8 +172,16 @@ __global__ void __launch_bounds__(kThreads) gemm_i8_kernel(const GemmArgs g) {
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc[x][y][e] = 0;
 
-#define OZ2_MFMA(F, q)                                                                                       \
-  acc[(q) >> 2][(q)&3] = __builtin_amdgcn_mfma_i32_32x32x32_i8(F.b[(q) >> 2], F.a[(q)&3], acc[(q) >> 2][(q)&3], 0, 0, 0)
+// Operand roles of v_mfma_i32_32x32x32_i8: the rows of the first operand run over the result registers
+// (lane l, register e: row 8 (e / 4) + 4 (l / 32) + e % 4), the rows of the second over the lanes (row l % 32).
+//   INT32 export: first = B' (columns j over registers), second = A' (rows i over lanes): every register is
+//   stored as 2 x 128 contiguous bytes of a column of C'.
+//   UINT8 export: first = A', second = B': each group of four registers holds four consecutive rows i of
+//   one column, i.e. the four bytes of one 32-bit store.
+#define OZ2_MFMA(F, q)                                                                                        \
+  acc[(q)&3][(q) >> 2] =                                                                                      \
+      RESIDUE_U8 ? __builtin_amdgcn_mfma_i32_32x32x32_i8(F.a[(q)&3], F.b[(q) >> 2], acc[(q)&3][(q) >> 2], 0, 0, 0) \
+                 : __builtin_amdgcn_mfma_i32_32x32x32_i8(F.b[(q) >> 2], F.a[(q)&3], acc[(q)&3][(q) >> 2], 0, 0, 0)
 
   // ---- prologue: k-tiles 0 .. NS-2 in flight, tile 0 visible, its first fragments in registers
 #pragma unroll
@@ -240,26 +250,67 @@ __global__ void __launch_bounds__(kThreads) gemm_i8_kernel(const GemmArgs g) {
   }
 #undef OZ2_MFMA
 
-  // ---- epilogue: lane holds i = lane%32 (second operand), registers run over j
-  int* c_tile = g.c + ((size_t)t * g.n_pad + (size_t)tn * BN + wn * 128) * g.m_pad + (size_t)tm * BM + wm * 128;
-  const unsigned lane_off = (unsigned)(4 * half) * (unsigned)g.m_pad + (lane & 31);
+  // ---- epilogue
+  if (RESIDUE_U8) {
+    // Algorithm 1 line 7 here: c'' = c' mod p in [0, p), four residues per 32-bit store.  Lane holds column
+    // j = lane % 32 of a 32 x 32 tile, each group of four registers four consecutive rows i.
+    //   u = c' + 2^31 as an unsigned word with bytes b3..b0;  r1 = sum_i b_i (2^(8i) mod p) + ((-2^31) mod p)
+    //   is congruent to c' and below 2^18 (one v_dot4_u32_u8), hence exact in FP32.  floor((r1 + 1/2)/p)
+    //   == floor(r1/p), and (r1 + 1/2)/p stays 2^-9 away from every integer while the FP32 evaluation errs
+    //   by less than 2^-12 (quotient below 2^11), so the floor and the remainder are exact.
+    const unsigned pu = (unsigned)p_int;
+    const unsigned k1 = 256u % pu, k2 = (k1 * k1) % pu, k3 = (k2 * k1) % pu;
+    const unsigned kpack = 1u | (k1 << 8) | (k2 << 16) | (k3 << 24);
+    const unsigned two31 = (((k3 * 128u) % pu));            // 2^31 = 2^24 * 2^7
+    const unsigned bias = (pu - two31) % pu;
+    const float pf = g.p[t], ipf = 1.0f / pf, hipf = 0.5f / pf;
+    const size_t col = (size_t)tn * BN + wn * 128 + (lane & 31);       // + tj*32
+    const size_t row0 = (size_t)tm * BM + wm * 128 + 4 * half;         // + ti*32 + 8*a
+    uint8_t* plane = reinterpret_cast<uint8_t*>(g.c) + (size_t)t * g.n_pad * g.m_pad;
 #pragma unroll
-  for (int tj = 0; tj < 4; ++tj)
+    for (int tj = 0; tj < 4; ++tj) {
+      uint8_t* cj = plane + (col + tj * 32) * g.m_pad + row0;
 #pragma unroll
-    for (int e = 0; e < 16; ++e) {
-      int* row = c_tile + (size_t)(tj * 32 + 8 * (e >> 2) + (e & 3)) * g.m_pad;
+      for (int ti = 0; ti < 4; ++ti)
 #pragma unroll
-      for (int ti = 0; ti < 4; ++ti) row[lane_off + ti * 32] = acc[tj][ti][e];
+        for (int a = 0; a < 4; ++a) {
+          unsigned v = 0;
+#pragma unroll
+          for (int b = 0; b < 4; ++b) {
+            const unsigned u = (unsigned)acc[ti][tj][4 * a + b] ^ 0x80000000u;
+            const float x = (float)__builtin_amdgcn_udot4(u, kpack, bias, false);
+            const float q = floorf(fmaf(x, ipf, hipf));
+            v = __builtin_amdgcn_cvt_pk_u8_f32(fmaf(-q, pf, x), b, v);
+          }
+          *reinterpret_cast<unsigned*>(cj + ti * 32 + 8 * a) = v;
+        }
     }
+  } else {
+    // lane holds row i = lane % 32 of a 32 x 32 tile, register e column 8 (e / 4) + 4 (lane / 32) + e % 4
+    const size_t row = (size_t)tm * BM + wm * 128 + (lane & 31);       // + ti*32
+    const size_t col0 = (size_t)tn * BN + wn * 128 + 4 * half;         // + tj*32 + 8*(e/4) + e%4
+    int* plane = g.c + (size_t)t * g.n_pad * g.m_pad + row;
+#pragma unroll
+    for (int tj = 0; tj < 4; ++tj)
+#pragma unroll
+      for (int ti = 0; ti < 4; ++ti)
+#pragma unroll
+        for (int e = 0; e < 16; ++e)
+          plane[(col0 + tj * 32 + 8 * (e >> 2) + (e & 3)) * g.m_pad + ti * 32] = acc[ti][tj][e];
+  }
 }
 
 }  // namespace
 
-hipError_t oz2_launch_stage2(const Oz2Plan& plan, const Oz2Layout& lay, char* ws, int64_t kblock, hipStream_t st) {
+hipError_t oz2_launch_stage2(const Oz2Plan& plan, const Oz2Layout& lay, char* ws, int64_t kblock, int residue_u8,
+                             hipStream_t st) {
   static bool attr_set = false;
   if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_i8_kernel),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_i8_kernel<false>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
+    if (e == hipSuccess)
+      e = hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_i8_kernel<true>),
+                              hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
     if (e != hipSuccess) return e;
     attr_set = true;
   }
@@ -281,6 +332,9 @@ hipError_t oz2_launch_stage2(const Oz2Plan& plan, const Oz2Layout& lay, char* ws
   g.ktiles = (int)(lay.k_pad / BK);
   g.ktiles_per_block = (int)(kblock / BK);
   for (int t = 0; t < OZ2_MAX_N; ++t) g.p[t] = t < plan.N ? (float)plan.moduli[t] : 1.0f;
-  hipLaunchKernelGGL(gemm_i8_kernel, dim3((unsigned)(g.chunk * 8)), dim3(kThreads), kLdsBytes, st, g);
+  if (residue_u8)
+    hipLaunchKernelGGL(gemm_i8_kernel<true>, dim3((unsigned)(g.chunk * 8)), dim3(kThreads), kLdsBytes, st, g);
+  else
+    hipLaunchKernelGGL(gemm_i8_kernel<false>, dim3((unsigned)(g.chunk * 8)), dim3(kThreads), kLdsBytes, st, g);
   return hipGetLastError();
 }

@@ -2,73 +2,96 @@
 //   per output element: c''_t = c'_t mod p_t (line 7), Y = sum_t c''_t W_t on 40-bit FP64 limbs (line 9),
 //   X = Y mod M in the symmetric range (line 10), one rounding to FP64 and the exact power-of-two
 //   scaling by 2^-(sa_i + sb_j) (line 11).
-// Bound by HBM traffic: 4N bytes read and 8 written per element.
+// Bound by HBM traffic: 4N (INT32 planes) or N (UINT8 residue planes) bytes read and 8 written per element.
 #include "oz2_math.h"
 
 namespace {
 
 constexpr int kThreads = 256;
-constexpr int kRowsPerThread = 4;
 
-// One thread: four consecutive rows i of one column j.  The INT32 planes are read with 16-byte loads, one
-// plane ahead of the arithmetic, so that each wave keeps two kilobytes in flight.
-template <int L>
-__global__ void __launch_bounds__(kThreads) crt_kernel(const int* __restrict__ cplanes, int64_t m_pad, int64_t n_pad,
-                                                       const int* __restrict__ sa, const int* __restrict__ sb,
-                                                       double* __restrict__ C, int64_t ldc, int64_t m, int64_t n,
-                                                       const double alpha, const double beta, const Oz2CrtConsts cc) {
-  const int64_t j = blockIdx.x;
-  const int64_t i0 = ((int64_t)blockIdx.y * kThreads + threadIdx.x) * kRowsPerThread;
-  if (i0 >= m) return;
-  const size_t plane_stride = (size_t)n_pad * m_pad;
-  const int4* src = reinterpret_cast<const int4*>(cplanes + (size_t)j * m_pad + i0);
-  const size_t stride4 = plane_stride / 4;
-
-  double S[kRowsPerThread][L];
-#pragma unroll
-  for (int r = 0; r < kRowsPerThread; ++r)
-#pragma unroll
-    for (int l = 0; l < L; ++l) S[r][l] = 0.0;
-
-  int4 cur = src[0];
-  for (int t = 0; t < cc.N; ++t) {
-    const int4 c = cur;
-    if (t + 1 < cc.N) cur = src[(size_t)(t + 1) * stride4];
-    const double p = cc.p[t], ip = cc.inv_p[t], hip_ = cc.half_inv_p[t];
-    double res[kRowsPerThread];
+// One plane's values for R consecutive rows: INT32 products (16-byte loads, R = 4) or UINT8 residues that
+// the GEMM epilogue already reduced (8-byte loads, R = 8).
+template <bool U8>
+struct PlaneLoad;
+template <>
+struct PlaneLoad<false> {
+  static constexpr int R = 4;
+  typedef int4 Raw;
+  static __device__ __forceinline__ void residues(const Raw& c, double p, double ip, double hip_, double* res) {
     res[0] = oz2_floor_mod(c.x, p, ip, hip_);
     res[1] = oz2_floor_mod(c.y, p, ip, hip_);
     res[2] = oz2_floor_mod(c.z, p, ip, hip_);
     res[3] = oz2_floor_mod(c.w, p, ip, hip_);
+  }
+};
+template <>
+struct PlaneLoad<true> {
+  static constexpr int R = 8;
+  typedef uint2 Raw;
+  static __device__ __forceinline__ void residues(const Raw& c, double, double, double, double* res) {
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      res[r] = (double)((c.x >> (8 * r)) & 0xffu);
+      res[4 + r] = (double)((c.y >> (8 * r)) & 0xffu);
+    }
+  }
+};
+
+// One thread: R consecutive rows i of one column j.  Planes are read one ahead of the arithmetic so that
+// every wave keeps two loads in flight.
+template <int L, bool U8>
+__global__ void __launch_bounds__(kThreads) crt_kernel(const void* __restrict__ cplanes, int64_t m_pad, int64_t n_pad,
+                                                       const int* __restrict__ sa, const int* __restrict__ sb,
+                                                       double* __restrict__ C, int64_t ldc, int64_t m, int64_t n,
+                                                       const double alpha, const double beta, const Oz2CrtConsts cc) {
+  typedef PlaneLoad<U8> PL;
+  typedef typename PL::Raw Raw;
+  constexpr int R = PL::R;
+  const int64_t j = blockIdx.x;
+  const int64_t i0 = ((int64_t)blockIdx.y * kThreads + threadIdx.x) * R;
+  if (i0 >= m) return;
+  // element (i, j) of plane t sits at index (t*n_pad + j)*m_pad + i, in units of int32 or of bytes
+  const size_t elem = (size_t)j * m_pad + i0;
+  const Raw* src = reinterpret_cast<const Raw*>(static_cast<const char*>(cplanes) + elem * (U8 ? 1 : 4));
+  const size_t stride = (size_t)n_pad * m_pad * (U8 ? 1 : 4) / sizeof(Raw);
+
+  double S[R][L];
+#pragma unroll
+  for (int r = 0; r < R; ++r)
+#pragma unroll
+    for (int l = 0; l < L; ++l) S[r][l] = 0.0;
+
+  Raw cur = src[0];
+  for (int t = 0; t < cc.N; ++t) {
+    const Raw c = cur;
+    if (t + 1 < cc.N) cur = src[(size_t)(t + 1) * stride];
+    double res[R];
+    PL::residues(c, cc.p[t], cc.inv_p[t], cc.half_inv_p[t], res);
 #pragma unroll
     for (int l = 0; l < L; ++l) {
       const double w = cc.w[t][l];
 #pragma unroll
-      for (int r = 0; r < kRowsPerThread; ++r) S[r][l] = fma(res[r], w, S[r][l]);
+      for (int r = 0; r < R; ++r) S[r][l] = fma(res[r], w, S[r][l]);
     }
   }
   const int sbj = sb[j];
-  double out[kRowsPerThread];
-#pragma unroll
-  for (int r = 0; r < kRowsPerThread; ++r) {
-    int e2;
-    double x = oz2_crt_reduce<L>(S[r], cc, &e2);
-    out[r] = ldexp(x, e2 - sa[i0 + r] - sbj);   // sa is padded to m_pad (a multiple of 256): always readable
-  }
   double* dst = C + i0 + j * ldc;
-  if (alpha == 1.0 && beta == 0.0) {
+  const bool plain = alpha == 1.0 && beta == 0.0;
 #pragma unroll
-    for (int r = 0; r < kRowsPerThread; ++r)
-      if (i0 + r < m) dst[r] = out[r];
-  } else {
-    // C := alpha * P + beta * C with one rounding of beta * C and one fused multiply-add; C is not read
-    // when beta is zero (BLAS convention)
-#pragma unroll
-    for (int r = 0; r < kRowsPerThread; ++r)
-      if (i0 + r < m) {
-        const double t = beta == 0.0 ? 0.0 : beta * dst[r];
-        dst[r] = fma(alpha, out[r], t);
+  for (int r = 0; r < R; ++r) {
+    int e2;
+    const double x = oz2_crt_reduce<L>(S[r], cc, &e2);
+    const double out = ldexp(x, e2 - sa[i0 + r] - sbj);  // sa is padded to m_pad (a multiple of 256): readable
+    if (i0 + r < m) {
+      if (plain) {
+        dst[r] = out;
+      } else {
+        // C := alpha * P + beta * C with one rounding of beta * C and one fused multiply-add; C is not
+        // read when beta is zero (BLAS convention)
+        const double tt = beta == 0.0 ? 0.0 : beta * dst[r];
+        dst[r] = fma(alpha, out, tt);
       }
+    }
   }
 }
 
@@ -97,17 +120,21 @@ double host_crt(const Oz2CrtConsts& cc, const int32_t* cprod) {
 }  // namespace
 
 hipError_t oz2_launch_stage3(int64_t m, int64_t n, double alpha, double beta, double* C, int64_t ldc,
-                             const Oz2Plan& plan, const Oz2Layout& lay, char* ws, hipStream_t st) {
-  const int* cplanes = reinterpret_cast<const int*>(ws + lay.off_c);
+                             const Oz2Plan& plan, const Oz2Layout& lay, char* ws, int residue_u8, hipStream_t st) {
+  const void* cplanes = ws + lay.off_c;
   const int* sa = reinterpret_cast<const int*>(ws + lay.off_sa);
   const int* sb = reinterpret_cast<const int*>(ws + lay.off_sb);
-  const int64_t per_block = (int64_t)kThreads * kRowsPerThread;
+  const int64_t per_block = (int64_t)kThreads * (residue_u8 ? PlaneLoad<true>::R : PlaneLoad<false>::R);
   dim3 grid((unsigned)n, (unsigned)((m + per_block - 1) / per_block));
   switch (plan.crt.L) {
-#define OZ2_CASE(LL)                                                                                          \
-  case LL:                                                                                                    \
-    hipLaunchKernelGGL(crt_kernel<LL>, grid, dim3(kThreads), 0, st, cplanes, lay.m_pad, lay.n_pad, sa, sb, C, \
-                       ldc, m, n, alpha, beta, plan.crt);                                                                  \
+#define OZ2_CASE(LL)                                                                                              \
+  case LL:                                                                                                        \
+    if (residue_u8)                                                                                               \
+      hipLaunchKernelGGL((crt_kernel<LL, true>), grid, dim3(kThreads), 0, st, cplanes, lay.m_pad, lay.n_pad, sa,  \
+                         sb, C, ldc, m, n, alpha, beta, plan.crt);                                                \
+    else                                                                                                          \
+      hipLaunchKernelGGL((crt_kernel<LL, false>), grid, dim3(kThreads), 0, st, cplanes, lay.m_pad, lay.n_pad, sa, \
+                         sb, C, ldc, m, n, alpha, beta, plan.crt);                                                \
     break;
     OZ2_CASE(1)
     OZ2_CASE(2)

@@ -19,7 +19,7 @@ def _dev(x):
     return torch.from_numpy(np.ascontiguousarray(x.T)).cuda().t()
 
 
-def run_stages(A, B, N, kblock=None, mode=0):
+def run_stages(A, B, N, kblock=None, mode=0, fmt=0):
     m, k = A.shape
     _, n = B.shape
     ws = oz.Workspace(m, n, k, N)
@@ -29,8 +29,9 @@ def run_stages(A, B, N, kblock=None, mode=0):
     if kblock is not None:
         oz.oz2_set_kblock(kblock)
     oz.oz2_set_shift_mode(mode)
+    oz.oz2_set_product_format(fmt)
     try:
-        print("stage1 m=%d n=%d k=%d N=%d mode=%d" % (m, n, k, N, mode), flush=True)
+        print("stage1 m=%d n=%d k=%d N=%d mode=%d fmt=%d" % (m, n, k, N, mode, fmt), flush=True)
         oz.oz2_stage1_convert(m, n, k, dA.data_ptr(), m, dB.data_ptr(), k, N)
         torch.cuda.synchronize()
         print("stage2", flush=True)
@@ -41,6 +42,7 @@ def run_stages(A, B, N, kblock=None, mode=0):
         torch.cuda.synchronize()
     finally:
         oz.oz2_set_shift_mode(0)
+        oz.oz2_set_product_format(1)
         if kblock is not None:
             oz.oz2_set_kblock(65536)
     mp, np_, kp = lay["m_pad"], lay["n_pad"], lay["k_pad"]
@@ -55,16 +57,19 @@ def run_stages(A, B, N, kblock=None, mode=0):
         sb=ws.view(lay["sb"], np_, torch.int32).cpu().numpy(),
         Ap=planes(lay["a_planes"], mp),
         Bp=planes(lay["b_planes"], np_),
-        Cp=ws.view(lay["c_planes"], N * np_ * mp, torch.int32).view(N, np_, mp).cpu().numpy(),
+        Cp=(ws.view(lay["c_planes"], N * np_ * mp, torch.int32) if fmt == 0 else
+            ws.view(lay["c_planes"], N * np_ * mp, torch.uint8)).view(N, np_, mp).cpu().numpy(),
         C=dC.cpu().numpy(),
     )
     return out
 
 
-def check_against_oracle(A, B, N, kblock=None, products_exact=True, mode=0):
+def check_against_oracle(A, B, N, kblock=None, products_exact=True, mode=0, fmt=0):
+    """fmt 0: INT32 product planes (compared with the exact products); fmt 1: UINT8 residue planes written by
+    the GEMM epilogue (compared with the oracle's residues of line 7)."""
     m, k = A.shape
     _, n = B.shape
-    got = run_stages(A, B, N, kblock, mode)
+    got = run_stages(A, B, N, kblock, mode, fmt)
     ref = orc.dgemm(A, B, N, want=("C", "shifts", "Ares", "Bres", "Cprod", "Cres"), mode=mode)
     assert np.array_equal(got["sa"][:m], ref.sa), "row shifts"
     assert np.array_equal(got["sb"][:n], ref.sb), "column shifts"
@@ -74,7 +79,9 @@ def check_against_oracle(A, B, N, kblock=None, products_exact=True, mode=0):
     assert not got["Ap"][:, m:, :].any() and not got["Ap"][:, :, k:].any()
     assert not got["Bp"][:, n:, :].any() and not got["Bp"][:, :, k:].any()
     prod = got["Cp"][:, :n, :m].transpose(0, 2, 1).astype(np.int64)
-    if products_exact:
+    if fmt == 1:
+        assert np.array_equal(prod, ref.Cres.astype(np.int64)), "UINT8 residues of the products"
+    elif products_exact:
         assert np.array_equal(prod, ref.Cprod), "INT32 products"
     else:
         mods = np.array(orc.moduli(N), dtype=np.int64)[:, None, None]
@@ -88,10 +95,11 @@ def check_against_oracle(A, B, N, kblock=None, products_exact=True, mode=0):
     return got, ref
 
 
-def test_c1_all_stages():
+@pytest.mark.parametrize("fmt", [0, 1])
+def test_c1_all_stages(fmt):
     cfg = inputs.CONFIGS["c1"]
     A, B = inputs.gemm_inputs(cfg["seed"], cfg["m"], cfg["n"], cfg["k"], cfg["phi"])
-    check_against_oracle(A, B, 14)
+    check_against_oracle(A, B, 14, fmt=fmt)
 
 
 @pytest.mark.parametrize("m,n,k,N,phi", [
@@ -102,11 +110,12 @@ def test_c1_all_stages():
     (5, 3, 1, 26, 0.5),           # k = 1, largest moduli count
     (1, 1, 7, 2, 0.5),            # smallest everything
 ])
-def test_ragged_shapes(m, n, k, N, phi):
+@pytest.mark.parametrize("fmt", [0, 1])
+def test_ragged_shapes(m, n, k, N, phi, fmt):
     rng = np.random.default_rng(m * 1000 + n)
     A = (rng.random((m, k)) - 0.5) * np.exp(phi * rng.standard_normal((m, k)))
     B = (rng.random((k, n)) - 0.5) * np.exp(phi * rng.standard_normal((k, n)))
-    check_against_oracle(A, B, N)
+    check_against_oracle(A, B, N, fmt=fmt)
 
 
 def test_zero_rows_columns_and_extreme_exponents():
@@ -186,6 +195,8 @@ def test_k_blocking_matches_unblocked():
     blocked, _ = check_against_oracle(A, B, N, kblock=256, products_exact=False)
     assert np.array_equal(blocked["C"], base["C"])
     assert not np.array_equal(blocked["Cp"], base["Cp"])  # the reduction between blocks really ran
+    blocked8, _ = check_against_oracle(A, B, N, kblock=256, fmt=1)
+    assert np.array_equal(blocked8["C"], base["C"])
 
 
 def test_determinism_two_runs():
@@ -195,6 +206,8 @@ def test_determinism_two_runs():
     r2 = run_stages(A, B, 16)
     for key in ("sa", "sb", "Ap", "Bp", "Cp"):
         assert np.array_equal(r1[key], r2[key])
+    r3 = run_stages(A, B, 16, fmt=1)
+    assert np.array_equal(r1["C"].view(np.uint64), r3["C"].view(np.uint64))  # both product formats, same C
     assert np.array_equal(r1["C"].view(np.uint64), r2["C"].view(np.uint64))
 
 
@@ -372,5 +385,6 @@ def test_inner_dimension_beyond_int32_exactness():
     A[0, :] = 1.0 + 128.0 * 2.0 ** -(kap - 1)
     B[:, 0] = 1.0 + 128.0 * 2.0 ** -(kap - 1)
     got, ref = check_against_oracle(A, B, N, products_exact=False)
+    check_against_oracle(A, B, N, fmt=1)
     # the exact products really exceed INT32 somewhere, so blocking was needed
     assert np.max(np.abs(ref.Cprod)) > 2**31
