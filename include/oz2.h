@@ -37,6 +37,7 @@ extern "C" {
 
 #define OZ2_SHIFT_MAX 0            /* shifts from row/column maxima: the simple bound of Section 3 */
 #define OZ2_SHIFT_CAUCHY_SCHWARZ 1 /* shifts from row/column 2-norms: Section 4.1, the "fast" variant */
+#define OZ2_SHIFT_INT8_PRODUCT 2   /* shifts from an INT8 product of upper bounds: Section 4.1, the "accu" variant */
 
 /* Smallest and largest supported number of moduli (Section 3.1: the table starts at s = 2). */
 int oz2_min_moduli(void);
@@ -118,6 +119,12 @@ int oz2_set_product_format(int format);
  *     largest with 2^sa_i nu_i <= 2^beta, 2^sb_j nu_j <= 2^beta, 4^beta <= M/2 - 1, where nu is an integer
  *     upper bound of the 2-norm: e = floor(log2 max |a|), q_l = ceil(|a_l| 2^(19-e)), S = sum q_l^2,
  *     h = min{h : 4^h >= S}, nu = 2^(e-19+h), sa = beta - (e - 19 + h).  One more pass over A and B.
+ *   OZ2_SHIFT_INT8_PRODUCT (Section 4.1): |A| <= D'' A'', |B| <= B'' E'' with A''_il = ceil(|a_il| 2^(5-e_i)) and
+ *     B''_lj = ceil(|b_lj| 2^(5-f_j)) in [0, 64] (e_i, f_j = floor(log2) of the row / column maximum), P = A''B''
+ *     on the matrix cores, R_i = max_j P_ij, C_j = max_i P_ij, t = min{t : 2^t >= R_i (C_j)}, b = max{b : 2^b <=
+ *     M/2 - 1}, sa_i = floor((b - t_i)/2) - (e_i - 5), sb_j likewise; then (|A'||B'|)_ij <= 2^b.  One more pass
+ *     over A and B, one more INT8 product and a pass over P; needs k (rounded up to 64) below 2^19, else calls
+ *     return OZ2_ERR_BUDGET.
  * Returns 0 or -1. */
 int oz2_set_shift_mode(int mode);
 

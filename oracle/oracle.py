@@ -34,6 +34,7 @@ def lib():
         _lib.oz2o_sym_mod.argtypes = [ctypes.c_int64, ctypes.c_int]
         _lib.oz2o_kappa.argtypes = [ctypes.c_int, ctypes.c_void_p, ctypes.c_int64]
         _lib.oz2o_beta.argtypes = [ctypes.c_int, ctypes.c_void_p]
+        _lib.oz2o_log2_budget.argtypes = [ctypes.c_int, ctypes.c_void_p]
         _lib.oz2o_axpby.argtypes = [ctypes.c_int64, ctypes.c_double, ctypes.c_void_p, ctypes.c_double, ctypes.c_void_p]
         _lib.oz2o_shifts.argtypes = [ctypes.c_int, ctypes.c_int64, ctypes.c_int64, ctypes.c_void_p,
                                      ctypes.c_int64, ctypes.c_int, ctypes.c_void_p]
@@ -82,6 +83,12 @@ def beta(N, mods=None):
     return int(lib().oz2o_beta(int(N), _ptr(mods)))
 
 
+def log2_budget(N, mods=None):
+    """Largest b with 2^b <= M/2 - 1 (INT8-product shift selection)."""
+    mods = np.asarray(moduli(N) if mods is None else mods, dtype=np.int32)
+    return lib().oz2o_log2_budget(int(N), _ptr(mods))
+
+
 def crt_constants(N, mods=None):
     """Return (M, [W_1..W_N]) as Python ints."""
     mods = np.asarray(moduli(N) if mods is None else mods, dtype=np.int32)
@@ -107,7 +114,9 @@ class Result(dict):
 
 def dgemm(A, B, N, mods=None, rows=None, cols=None, want=("C",), mode=0):
     """Run Algorithm 1 on the CPU.  mode 0: shifts from the row/column maxima (Section 3); mode 1: shifts
-    from the Cauchy-Schwarz bound (Section 4.1, "fast").  A (m x k), B (k x n): numpy float64, any layout (copied to
+    from the Cauchy-Schwarz bound (Section 4.1, "fast"); mode 2: shifts from the INT8 product of 6-bit upper
+    bounds (Section 4.1, "accu"; the row and column maxima of that product always run over the whole of A and B,
+    so A and B must be the full operands even when rows / cols select a subset).  A (m x k), B (k x n): numpy float64, any layout (copied to
     column-major).  rows / cols: optional index lists selecting the outputs to compute.
     want: any of "C", "shifts", "Ap", "Bp", "Ares", "Bres", "Cprod", "Cres", "X".
     Ap/Bp/X come back as nested Python-int lists (tiny inputs only)."""

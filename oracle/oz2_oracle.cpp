@@ -25,6 +25,16 @@
 // replaced by an integer upper bound: with e_i = floor(log2 max_l |a_il|), q_il = ceil(|a_il| 2^(19-e_i)) (an
 // integer below 2^20), S_i = sum_l q_il^2 and h_i the smallest integer with 4^h_i >= S_i, one has
 // ||A(i,:)||_2 <= 2^(e_i-19+h_i) and sa_i = beta - (e_i - 19 + h_i).
+// Mode 2 is the INT8-product bound of Section 4.1 (the paper's "OS II-accu"): |A| <= D'' A'', |B| <= B'' E'' with
+// non-negative INT8 matrices A'', B'' and power-of-two diagonals, so (|A||B|)_ij <= D''_ii (A''B'')_ij E''_jj.
+// Reading taken here (the paper fixes neither the width of A'' nor how D, E follow "in reverse"):
+//   e_i = floor(log2 max_l |a_il|), A''_il = ceil(|a_il| 2^(5-e_i)) in [0, 64], D''_ii = 2^(e_i-5); f_j and
+//   B''_lj = ceil(|b_lj| 2^(5-f_j)) likewise;  P = A''B'' in exact integers;  R_i = max_j P_ij, C_j = max_i P_ij;
+//   t_i = min{t : 2^t >= R_i}, t_j = min{t : 2^t >= C_j};  b = max{b : 2^b <= M/2 - 1};
+//   sa_i = floor((b - t_i)/2) - (e_i - 5),  sb_j = floor((b - t_j)/2) - (f_j - 5).
+// Since P_ij <= min(R_i, C_j) <= sqrt(R_i C_j) <= 2^((t_i+t_j)/2), this gives
+//   (|A'||B'|)_ij <= 2^(sa_i+sb_j) 2^(e_i-5) P_ij 2^(f_j-5) <= 2^b <= M/2 - 1.
+// The maxima R_i and C_j run over ALL columns and rows, also when only a subset of outputs is asked for.
 // The moduli are the greedy descending pairwise-coprime sequence starting at 256 (Section 3.1 asks for
 // the largest possible pairwise-coprime values not above 256); a caller may pass any other list, e.g. the
 // sixteen values the paper prints.
@@ -359,6 +369,38 @@ int fast_shift(const double* x, int64_t k, int64_t stride, int beta) {
   return beta - (e - 19 + h);
 }
 
+// Section 4.1 (INT8-product variant): largest b with 2^b <= M/2 - 1
+int log2_budget(const BigU& M) {
+  BigU half = shr1(M);
+  if (is_zero(half)) return -1;
+  BigU lim = sub(half, BigU(1));
+  if (is_zero(lim)) return -1;
+  return bit_length(lim) - 1;
+}
+
+// ceil(|x| * 2^(5 - e)) for |x| < 2^(e+1): an integer in [0, 64]; never 0 for x != 0
+int bound6(double x, int e) {
+  int neg, ex;
+  uint64_t mant;
+  decompose(x, &neg, &mant, &ex);
+  if (mant == 0) return 0;
+  int sh = ex + 5 - e;  // |x| = mant * 2^ex
+  if (sh >= 0) return (int)(mant << sh);
+  if (-sh >= 64) return 1;
+  uint64_t q = mant >> (-sh);
+  if ((q << (-sh)) != mant) q += 1;
+  return (int)q;
+}
+
+// smallest t with 2^t >= v (v >= 1)
+int ceil_log2_u64(uint64_t v) {
+  int t = 0;
+  while (((uint64_t)1 << t) < v) ++t;
+  return t;
+}
+
+int floor_div2(int x) { return x >= 0 ? x / 2 : -((-x + 1) / 2); }
+
 int validate(int64_t m, int64_t n, int64_t k, int64_t lda, int64_t ldb, int N) {
   if (m < 0 || n < 0 || k < 0) return -1;
   if (lda < (m > 1 ? m : 1) || ldb < (k > 1 ? k : 1)) return -2;
@@ -376,6 +418,12 @@ int oz2o_words(void) { return WORDS; }
 int oz2o_moduli(int N, int* out) {
   if (N < 1 || N > 28) return -1;
   return greedy_moduli(N, out);
+}
+
+// Bit budget of the INT8-product variant for a moduli list: largest b with 2^b <= M/2 - 1.
+int oz2o_log2_budget(int N, const int* moduli) {
+  if (N < 1 || N > 28) return -1;
+  return log2_budget(product(N, moduli));
 }
 
 // beta of the Cauchy-Schwarz variant for a moduli list: largest beta with 4^beta <= M/2 - 1.
@@ -444,7 +492,7 @@ int oz2o_dgemm_sub(int64_t m, int64_t n, int64_t k, const double* A, int64_t lda
                    uint8_t* X_sign, uint32_t* X_mag) {
   int rc = validate(m, n, k, lda, ldb, N);
   if (rc) return rc;
-  if (mode != 0 && mode != 1) return -4;
+  if (mode != 0 && mode != 1 && mode != 2) return -4;
   if (!I) nI = m;
   if (!J) nJ = n;
   if (nI == 0 || nJ == 0) return 0;
@@ -470,11 +518,55 @@ int oz2o_dgemm_sub(int64_t m, int64_t n, int64_t k, const double* A, int64_t lda
   if (kappa > 120) return -3;
   const int beta = beta_of(M);
   if (mode == 1 && (beta < 1 || beta > 120)) return 2;
+  const int budget = log2_budget(M);
+  if (mode == 2 && (budget < 2 || budget > 240)) return 2;
 
   // line 1: shifts
   std::vector<int32_t> sa(nI), sb(nJ);
+  if (mode == 2) {
+    // bound matrices for ALL rows and columns (the maxima of P need them), then P row by row
+    std::vector<int> ea(m), fb(n);
+    std::vector<uint8_t> a2((size_t)m * k), b2((size_t)n * k);  // A''[i*k + l], B''[j*k + l]
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < m; ++i) {
+      double mx = 0.0;
+      for (int64_t l = 0; l < k; ++l) mx = std::fmax(mx, std::fabs(A[i + l * lda]));
+      ea[i] = mx == 0.0 ? 0 : ilog2_abs(mx);
+      for (int64_t l = 0; l < k; ++l) a2[(size_t)i * k + l] = mx == 0.0 ? 0 : (uint8_t)bound6(A[i + l * lda], ea[i]);
+    }
+#pragma omp parallel for schedule(static)
+    for (int64_t j = 0; j < n; ++j) {
+      double mx = 0.0;
+      for (int64_t l = 0; l < k; ++l) mx = std::fmax(mx, std::fabs(B[l + j * ldb]));
+      fb[j] = mx == 0.0 ? 0 : ilog2_abs(mx);
+      for (int64_t l = 0; l < k; ++l) b2[(size_t)j * k + l] = mx == 0.0 ? 0 : (uint8_t)bound6(B[l + j * ldb], fb[j]);
+    }
+#pragma omp parallel for schedule(static)
+    for (int64_t r = 0; r < nI; ++r) {
+      int64_t i = I ? I[r] : r;
+      uint64_t R = 0;  // max over all columns j of (A''B'')_ij
+      for (int64_t j = 0; j < n; ++j) {
+        uint64_t acc = 0;
+        for (int64_t l = 0; l < k; ++l) acc += (uint64_t)a2[(size_t)i * k + l] * b2[(size_t)j * k + l];
+        if (acc > R) R = acc;
+      }
+      sa[r] = R == 0 ? 0 : floor_div2(budget - ceil_log2_u64(R)) - (ea[i] - 5);
+    }
+#pragma omp parallel for schedule(static)
+    for (int64_t c = 0; c < nJ; ++c) {
+      int64_t j = J ? J[c] : c;
+      uint64_t Cm = 0;  // max over all rows i
+      for (int64_t i = 0; i < m; ++i) {
+        uint64_t acc = 0;
+        for (int64_t l = 0; l < k; ++l) acc += (uint64_t)a2[(size_t)i * k + l] * b2[(size_t)j * k + l];
+        if (acc > Cm) Cm = acc;
+      }
+      sb[c] = Cm == 0 ? 0 : floor_div2(budget - ceil_log2_u64(Cm)) - (fb[j] - 5);
+    }
+  }
 #pragma omp parallel for schedule(static)
   for (int64_t r = 0; r < nI; ++r) {
+    if (mode == 2) continue;
     int64_t i = I ? I[r] : r;
     if (mode == 1) {
       sa[r] = fast_shift(A + i, k, lda, beta);
@@ -486,6 +578,7 @@ int oz2o_dgemm_sub(int64_t m, int64_t n, int64_t k, const double* A, int64_t lda
   }
 #pragma omp parallel for schedule(static)
   for (int64_t c = 0; c < nJ; ++c) {
+    if (mode == 2) continue;
     int64_t j = J ? J[c] : c;
     if (mode == 1) {
       sb[c] = fast_shift(B + j * ldb, k, 1, beta);

@@ -94,11 +94,11 @@ def oz2_set_kblock(kblock):
 
 
 def oz2_set_shift_mode(mode):
-    """0: shifts from maxima (Section 3); 1: Cauchy-Schwarz bound (Section 4.1)."""
+    """0: shifts from maxima (Section 3); 1: Cauchy-Schwarz bound; 2: INT8-product bound (both Section 4.1)."""
     _check(lib().oz2_set_shift_mode(int(mode)), "oz2_set_shift_mode")
 
 
-OZ2_SHIFT_MAX, OZ2_SHIFT_CAUCHY_SCHWARZ = 0, 1
+OZ2_SHIFT_MAX, OZ2_SHIFT_CAUCHY_SCHWARZ, OZ2_SHIFT_INT8_PRODUCT = 0, 1, 2
 OZ2_PRODUCT_INT32, OZ2_PRODUCT_RESIDUE_U8 = 0, 1
 
 

@@ -53,6 +53,8 @@ int prepare(State& s, int64_t m, int64_t n, int64_t k, int N, const Oz2Plan** pl
   if (rc == 2 && (s.shift_mode == OZ2_SHIFT_MAX || (*plan)->beta < 1)) return OZ2_ERR_BUDGET;
   if (rc == 2) rc = 0;
   if (rc != 0) return -10;
+  // the INT8 product of the 6-bit bounds must stay below 2^31
+  if (s.shift_mode == OZ2_SHIFT_INT8_PRODUCT && (k + 63) / 64 * 64 >= ((int64_t)1 << 19)) return OZ2_ERR_BUDGET;
   oz2_make_layout(m, n, k, N, lay);
   if (!s.ws || s.ws_bytes < lay->total) return OZ2_ERR_WORKSPACE;
   return OZ2_OK;
@@ -123,7 +125,7 @@ int oz2_set_stage_events(void* const events[4]) {
 }
 
 int oz2_set_shift_mode(int mode) {
-  if (mode != OZ2_SHIFT_MAX && mode != OZ2_SHIFT_CAUCHY_SCHWARZ) return -1;
+  if (mode != OZ2_SHIFT_MAX && mode != OZ2_SHIFT_CAUCHY_SCHWARZ && mode != OZ2_SHIFT_INT8_PRODUCT) return -1;
   State& s = state();
   std::lock_guard<std::mutex> lock(s.mu);
   s.shift_mode = mode;

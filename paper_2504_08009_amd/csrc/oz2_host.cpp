@@ -130,13 +130,12 @@ int oz2_table_kappa(int N, int64_t k) {
   return (bits - 1) / 2;  // largest kappa with 4^kappa <= floor((M/2-1)/k)
 }
 
-// largest beta with 4^beta <= M/2 - 1
-static int table_beta(const int* moduli, int N) {
+// largest b with 2^b <= M/2 - 1 (-1 if there is none); the largest beta with 4^beta <= M/2 - 1 is floor(b/2)
+static int table_budget2(const int* moduli, int N) {
   Wide lim = product_of(moduli, N);
   wide_divmod(lim, 2);
   wide_sub_one(lim);
-  int bits = wide_bits(lim);
-  return bits == 0 ? -1 : (bits - 1) / 2;
+  return wide_bits(lim) - 1;
 }
 
 int oz2_build_plan(int N, int64_t k, Oz2Plan* plan) {
@@ -145,7 +144,8 @@ int oz2_build_plan(int N, int64_t k, Oz2Plan* plan) {
   plan->N = N;
   oz2_table_moduli(N, plan->moduli);
   plan->kappa = oz2_table_kappa(N, k);
-  plan->beta = table_beta(plan->moduli, N);
+  plan->budget2 = table_budget2(plan->moduli, N);
+  plan->beta = plan->budget2 < 0 ? -1 : plan->budget2 / 2;
 
   const Wide M = product_of(plan->moduli, N);
   const int mbits = wide_bits(M);

@@ -6,6 +6,8 @@
 #include <stddef.h>
 #include <stdint.h>
 
+#include "../../include/oz2.h"
+
 #define OZ2_MIN_N 2
 #define OZ2_MAX_N 26   // greedy table 256 ... 139; M < 2^200
 #define OZ2_MAX_L 5    // 40-bit limbs of M
@@ -42,7 +44,8 @@ struct Oz2CrtConsts {
 struct Oz2Plan {
   int N;
   int kappa;
-  int beta;   // largest beta with 4^beta <= M/2 - 1 (Cauchy-Schwarz shift mode)
+  int beta;     // largest beta with 4^beta <= M/2 - 1 (Cauchy-Schwarz shift mode)
+  int budget2;  // largest b with 2^b <= M/2 - 1 (INT8-product shift mode)
   int moduli[OZ2_MAX_N];
   Oz2ConvConsts conv;
   Oz2CrtConsts crt;
@@ -65,6 +68,9 @@ hipError_t oz2_launch_stage1(int transa, int transb, int64_t m, int64_t n, int64
                              char* ws, hipStream_t st);
 hipError_t oz2_launch_stage2(const Oz2Plan& plan, const Oz2Layout& lay, char* ws, int64_t kblock, int residue_u8,
                              hipStream_t st);
+// P = A''B'' of the INT8-product shift mode: bound planes in the slots of residue plane 0 -> INT32 in the slot of
+// product plane 0.  Exact for k_pad * 64 * 64 < 2^31.
+hipError_t oz2_launch_bound_gemm(const Oz2Layout& lay, char* ws, hipStream_t st);
 hipError_t oz2_launch_stage3(int64_t m, int64_t n, double alpha, double beta, double* C, int64_t ldc,
                              const Oz2Plan& plan, const Oz2Layout& lay, char* ws, int residue_u8, hipStream_t st);
 hipError_t oz2_launch_scale_c(int64_t m, int64_t n, double beta, double* C, int64_t ldc, hipStream_t st);

@@ -51,6 +51,17 @@ OZ2_HD int oz2_sym_residue(const Oz2Split& s, double p, double inv_p, double c32
 }
 
 // ---------------------------------------------------------------------------------------------------
+// Section 4.1, INT8-product bound: ceil(|a| 2^sh) with sh = 5 - floor(log2 of the vector's maximum), an
+// integer in [0, 64] that bounds |a| 2^sh from above.  The scaling is exact unless it underflows to zero,
+// and the ceiling of any positive value is at least one.
+// ---------------------------------------------------------------------------------------------------
+OZ2_HD int oz2_bound6(double a, int sh) {
+  double q = ceil(ldexp(fabs(a), sh));
+  if (a != 0.0 && q == 0.0) q = 1.0;
+  return (int)q;
+}
+
+// ---------------------------------------------------------------------------------------------------
 // Algorithm 1 line 7: c'' = c' - floor(c'/p) p for an INT32 c', as a double in [0, p).
 //   floor((c' + 1/2)/p) == floor(c'/p) and (c' + 1/2)/p stays 1/(2p) away from every integer, far more
 //   than the rounding error 2^31/p * 2^-52 of the fused multiply-add, so the floor is exact.

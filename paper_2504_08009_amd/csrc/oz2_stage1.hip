@@ -185,6 +185,66 @@ __device__ __forceinline__ unsigned pack4(int r0, int r1, int r2, int r3) {
   return (unsigned)(r0 & 0xff) | ((unsigned)(r1 & 0xff) << 8) | ((unsigned)(r2 & 0xff) << 16) | ((unsigned)r3 << 24);
 }
 
+// sixteen consecutive inner-dimension values of one vector -> sixteen bound bytes
+__device__ __forceinline__ void store_bounds(const double* mine, int shift, int8_t* dst) {
+  int r[16];
+#pragma unroll
+  for (int u = 0; u < 16; ++u) r[u] = oz2_bound6(mine[u], shift);
+  uint4 v;
+  v.x = pack4(r[0], r[1], r[2], r[3]);
+  v.y = pack4(r[4], r[5], r[6], r[7]);
+  v.z = pack4(r[8], r[9], r[10], r[11]);
+  v.w = pack4(r[12], r[13], r[14], r[15]);
+  *reinterpret_cast<uint4*>(dst) = v;
+}
+
+// ---- INT8-product shift mode (Section 4.1): row and column maxima of P = A''B'' (INT32, element (i,j) at
+// j*m_pad + i).  One block: 256 rows x 64 columns; lanes run along the rows.
+constexpr int kProdCols = 64;
+__global__ void __launch_bounds__(kThreads) prodmax_kernel(const int* __restrict__ P, int64_t m_pad, int64_t m, int64_t n,
+                                                           int64_t row_blocks, unsigned long long* __restrict__ rowtop,
+                                                           unsigned long long* __restrict__ coltop) {
+  const int64_t rb = blockIdx.x % row_blocks, cb = blockIdx.x / row_blocks;
+  const int64_t i = rb * kThreads + threadIdx.x;  // < m_pad
+  const int64_t j0 = cb * kProdCols;
+  const int* src = P + i + j0 * m_pad;
+  int rmax = 0;
+  for (int jj = 0; jj < kProdCols; jj += 8) {
+    int v[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) v[u] = (i < m && j0 + jj + u < n) ? src[(int64_t)(jj + u) * m_pad] : 0;
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      rmax = v[u] > rmax ? v[u] : rmax;
+      int c = v[u];
+#pragma unroll
+      for (int off = 32; off >= 1; off >>= 1) {
+        int o = __shfl_xor(c, off, 64);
+        c = o > c ? o : c;
+      }
+      if ((threadIdx.x & 63) == 0 && c > 0) atomicMax(coltop + j0 + jj + u, (unsigned long long)c);
+    }
+  }
+  if (rmax > 0) atomicMax(rowtop + i, (unsigned long long)rmax);
+}
+
+// sa = floor((b - t)/2) - (e - 5) with t the smallest integer such that 2^t >= top; 0 for an all-zero vector
+__global__ void __launch_bounds__(kThreads) shifts_prod_kernel(const unsigned long long* __restrict__ mx,
+                                                               const unsigned long long* __restrict__ top,
+                                                               int* __restrict__ s, int64_t count, int budget) {
+  int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+  if (i >= count) return;
+  const unsigned long long b = mx[i], R = top[i];
+  int out = 0;
+  if (b && R) {
+    const int e = exponent_of_bits(b);
+    const int t = R <= 1 ? 0 : 64 - __clzll((long long)(R - 1));
+    const int d = budget - t;
+    out = (d >= 0 ? d / 2 : -((1 - d) / 2)) - (e - 5);
+  }
+  s[i] = out;
+}
+
 // Plane layout (shared with the GEMM kernel): blocks of 256 rows x 64 bytes of the inner dimension, each
 // block contiguous; element (row, l) of plane t at
 //   ((t*rows_pad + 256*(row/256)) * k_pad) + (l/64)*16384 + (row%256)*64 + (l%64).
@@ -198,7 +258,9 @@ static_assert(OZ2_TILE_M == 256 && OZ2_TILE_N == 256 && OZ2_TILE_K == 64, "plane
 // rows x 64 bytes occupy contiguously in the output block.
 constexpr int kConvARows = 64;
 constexpr int kConvAPitch = 65;  // doubles per row in LDS
-template <bool TWO_LEVEL>
+// KIND 0 / 1: residues of trunc(a 2^shift) with the one- / two-level split; KIND 2: the single plane of 6-bit
+// upper bounds ceil(|a| 2^shift) of Section 4.1 (written where plane 0 goes).
+template <int KIND>
 __global__ void __launch_bounds__(kThreads) convert_a_kernel(const double* __restrict__ A, int64_t lda, int64_t m,
                                                              int64_t k, int64_t m_pad, int64_t k_pad,
                                                              const int* __restrict__ sa, int8_t* __restrict__ planes,
@@ -223,13 +285,18 @@ __global__ void __launch_bounds__(kThreads) convert_a_kernel(const double* __res
   const int chunk = lane & 3;
   const int64_t i = r0 + row;
   const int shift = i < m ? sa[i] : 0;
-  Oz2Split xs[16];
   const double* mine = tile + row * kConvAPitch + chunk * 16;
-#pragma unroll
-  for (int u = 0; u < 16; ++u) xs[u] = oz2_scale_trunc_split<TWO_LEVEL>(mine[u], shift);
   const size_t plane_stride = (size_t)m_pad * k_pad;
   int8_t* dst = planes + (size_t)(i / kBlkRows) * kBlkRows * k_pad + (size_t)kb * (kBlkRows * kBlkK) +
                 (i % kBlkRows) * kBlkK + chunk * 16;
+  if constexpr (KIND == 2) {
+    store_bounds(mine, shift, dst);
+    return;
+  }
+  constexpr bool TWO_LEVEL = KIND == 1;
+  Oz2Split xs[16];
+#pragma unroll
+  for (int u = 0; u < 16; ++u) xs[u] = oz2_scale_trunc_split<TWO_LEVEL>(mine[u], shift);
   for (int t = 0; t < cc.N; ++t) {
     const double p = cc.p[t], ip = cc.inv_p[t], c32 = cc.c32[t], c64 = cc.c64[t];
     int r[16];
@@ -252,7 +319,7 @@ constexpr int kConvBCols = 16;
 constexpr int kConvBKC = 256;
 constexpr int kConvBGroup = 18;     // doubles per 16-element group in LDS (144 bytes)
 constexpr int kConvBColPitch = 296; // doubles per column in LDS: 16 groups + 8 (2368 bytes = 64 mod 256)
-template <bool TWO_LEVEL>
+template <int KIND>
 __global__ void __launch_bounds__(kThreads) convert_b_kernel(const double* __restrict__ B, int64_t ldb, int64_t k,
                                                              int64_t n, int64_t n_pad, int64_t k_pad,
                                                              const int* __restrict__ sb, int8_t* __restrict__ planes,
@@ -277,13 +344,18 @@ __global__ void __launch_bounds__(kThreads) convert_b_kernel(const double* __res
   const int c = lane >> 2;
   const int64_t j = j0 + c;
   const int shift = j < n ? sb[j] : 0;
-  Oz2Split xs[16];
   const double* mine = tile + c * kConvBColPitch + (wv * 4 + (lane & 3)) * kConvBGroup;
-#pragma unroll
-  for (int u = 0; u < 16; ++u) xs[u] = oz2_scale_trunc_split<TWO_LEVEL>(mine[u], shift);
   const size_t plane_stride = (size_t)n_pad * k_pad;
   int8_t* dst = planes + (size_t)(j / kBlkRows) * kBlkRows * k_pad + (size_t)(l0 / kBlkK) * (kBlkRows * kBlkK) +
                 (j % kBlkRows) * kBlkK + (l0 % kBlkK);
+  if constexpr (KIND == 2) {
+    store_bounds(mine, shift, dst);
+    return;
+  }
+  constexpr bool TWO_LEVEL = KIND == 1;
+  Oz2Split xs[16];
+#pragma unroll
+  for (int u = 0; u < 16; ++u) xs[u] = oz2_scale_trunc_split<TWO_LEVEL>(mine[u], shift);
   for (int t = 0; t < cc.N; ++t) {
     const double p = cc.p[t], ip = cc.inv_p[t], c32 = cc.c32[t], c64 = cc.c64[t];
     int r[16];
@@ -302,50 +374,63 @@ __global__ void __launch_bounds__(kThreads) convert_b_kernel(const double* __res
 
 namespace {
 
-// Everything stage 1 does for one operand.  The operand is a set of `nvec` vectors of length k (rows of
-// op(A) or columns of op(B)).  strided: element (v, l) at X[v + l*ld] (vectors are rows of a column-major
-// matrix); otherwise element (v, l) at X[l + v*ld] (vectors are its columns).
-void convert_operand(const double* X, int64_t ld, bool strided, int64_t nvec, int64_t nvec_pad, int64_t k, int64_t k_pad,
-                     unsigned long long* vmax, unsigned long long* vnorm, int* shifts, int8_t* planes,
-                     const Oz2Plan& plan, int shift_mode, hipStream_t st) {
-  auto blocks = [](int64_t v, int64_t per) { return (unsigned)((v + per - 1) / per); };
+unsigned blocks_of(int64_t v, int64_t per) { return (unsigned)((v + per - 1) / per); }
+
+// One operand of stage 1: a set of `nvec` vectors of length k (rows of op(A) or columns of op(B)).
+// strided: element (v, l) at X[v + l*ld] (vectors are rows of a column-major matrix); otherwise element
+// (v, l) at X[l + v*ld] (vectors are its columns).
+struct Operand {
+  const double* X;
+  int64_t ld;
+  bool strided;
+  int64_t nvec, nvec_pad, k, k_pad;
+  unsigned long long* vmax;   // bit pattern of the largest magnitude per vector
+  unsigned long long* vaux;   // per-vector integer norm bound, or largest element of the bound product
+  int* shifts;
+  int8_t* planes;
+};
+
+void launch_max(const Operand& o, hipStream_t st) {
   const dim3 thr(kThreads);
-  const dim3 g_vec(blocks(nvec_pad, kThreads));
-  const dim3 g_str(blocks(nvec, kThreads), blocks(k, kRowMaxKC));
-  const dim3 g_con((unsigned)nvec, blocks(k, kColMaxKC));
-  hipLaunchKernelGGL(fill_u64_kernel, g_vec, thr, 0, st, vmax, nvec_pad);
-  if (strided)
-    hipLaunchKernelGGL(rowmax_kernel, g_str, thr, 0, st, X, ld, nvec, k, vmax);
+  hipLaunchKernelGGL(fill_u64_kernel, dim3(blocks_of(o.nvec_pad, kThreads)), thr, 0, st, o.vmax, o.nvec_pad);
+  if (o.strided)
+    hipLaunchKernelGGL(rowmax_kernel, dim3(blocks_of(o.nvec, kThreads), blocks_of(o.k, kRowMaxKC)), thr, 0, st, o.X, o.ld,
+                       o.nvec, o.k, o.vmax);
   else
-    hipLaunchKernelGGL(colmax_kernel, g_con, thr, 0, st, X, ld, k, vmax);
-  // |x'| < 2^xbits decides how deep the conversion kernels split an element
-  int xbits = plan.kappa;
-  if (shift_mode == 1) {
-    hipLaunchKernelGGL(fill_u64_kernel, g_vec, thr, 0, st, vnorm, nvec_pad);
-    if (strided)
-      hipLaunchKernelGGL(rownorm_kernel, g_str, thr, 0, st, X, ld, nvec, k, vmax, vnorm);
-    else
-      hipLaunchKernelGGL(colnorm_kernel, g_con, thr, 0, st, X, ld, k, vmax, vnorm);
-    hipLaunchKernelGGL(shifts_cs_kernel, g_vec, thr, 0, st, vmax, vnorm, shifts, nvec_pad, plan.beta);
-    xbits = plan.beta + 1;
+    hipLaunchKernelGGL(colmax_kernel, dim3((unsigned)o.nvec, blocks_of(o.k, kColMaxKC)), thr, 0, st, o.X, o.ld, o.k, o.vmax);
+}
+
+void launch_norm(const Operand& o, hipStream_t st) {
+  const dim3 thr(kThreads);
+  hipLaunchKernelGGL(fill_u64_kernel, dim3(blocks_of(o.nvec_pad, kThreads)), thr, 0, st, o.vaux, o.nvec_pad);
+  if (o.strided)
+    hipLaunchKernelGGL(rownorm_kernel, dim3(blocks_of(o.nvec, kThreads), blocks_of(o.k, kRowMaxKC)), thr, 0, st, o.X, o.ld,
+                       o.nvec, o.k, o.vmax, o.vaux);
+  else
+    hipLaunchKernelGGL(colnorm_kernel, dim3((unsigned)o.nvec, blocks_of(o.k, kColMaxKC)), thr, 0, st, o.X, o.ld, o.k, o.vmax,
+                       o.vaux);
+}
+
+// kind 0 / 1: residue planes with the one- / two-level split; kind 2: the bound plane
+void launch_convert(const Operand& o, int kind, const Oz2ConvConsts& conv, hipStream_t st) {
+  const dim3 thr(kThreads);
+  const dim3 ga((unsigned)(o.nvec_pad / kConvARows), (unsigned)(o.k_pad / kBlkK));
+  const dim3 gb((unsigned)(o.nvec_pad / kConvBCols), blocks_of(o.k_pad, kConvBKC));
+#define OZ2_CONV(KIND)                                                                                              \
+  if (o.strided)                                                                                                    \
+    hipLaunchKernelGGL(convert_a_kernel<KIND>, ga, thr, 0, st, o.X, o.ld, o.nvec, o.k, o.nvec_pad, o.k_pad, o.shifts, \
+                       o.planes, conv);                                                                             \
+  else                                                                                                              \
+    hipLaunchKernelGGL(convert_b_kernel<KIND>, gb, thr, 0, st, o.X, o.ld, o.k, o.nvec, o.nvec_pad, o.k_pad, o.shifts, \
+                       o.planes, conv);
+  if (kind == 0) {
+    OZ2_CONV(0)
+  } else if (kind == 1) {
+    OZ2_CONV(1)
   } else {
-    hipLaunchKernelGGL(shifts_kernel, g_vec, thr, 0, st, vmax, shifts, nvec_pad, plan.kappa);
+    OZ2_CONV(2)
   }
-  Oz2ConvConsts conv = plan.conv;
-  conv.two_level = xbits > 75;
-  const dim3 ga((unsigned)(nvec_pad / kConvARows), (unsigned)(k_pad / kBlkK));
-  const dim3 gb((unsigned)(nvec_pad / kConvBCols), blocks(k_pad, kConvBKC));
-  if (strided) {
-    if (conv.two_level)
-      hipLaunchKernelGGL(convert_a_kernel<true>, ga, thr, 0, st, X, ld, nvec, k, nvec_pad, k_pad, shifts, planes, conv);
-    else
-      hipLaunchKernelGGL(convert_a_kernel<false>, ga, thr, 0, st, X, ld, nvec, k, nvec_pad, k_pad, shifts, planes, conv);
-  } else {
-    if (conv.two_level)
-      hipLaunchKernelGGL(convert_b_kernel<true>, gb, thr, 0, st, X, ld, k, nvec, nvec_pad, k_pad, shifts, planes, conv);
-    else
-      hipLaunchKernelGGL(convert_b_kernel<false>, gb, thr, 0, st, X, ld, k, nvec, nvec_pad, k_pad, shifts, planes, conv);
-  }
+#undef OZ2_CONV
 }
 
 }  // namespace
@@ -354,16 +439,56 @@ void convert_operand(const double* X, int64_t ld, bool strided, int64_t nvec, in
 hipError_t oz2_launch_stage1(int transa, int transb, int64_t m, int64_t n, int64_t k, const double* A, int64_t lda,
                              const double* B, int64_t ldb, const Oz2Plan& plan, int shift_mode, const Oz2Layout& lay,
                              char* ws, hipStream_t st) {
-  // rows of op(A): strided in a stored m x k matrix, contiguous in a stored k x m matrix
-  convert_operand(A, lda, transa == 0, m, lay.m_pad, k, lay.k_pad,
-                  reinterpret_cast<unsigned long long*>(ws + lay.off_rowmax),
-                  reinterpret_cast<unsigned long long*>(ws + lay.off_rownorm), reinterpret_cast<int*>(ws + lay.off_sa),
-                  reinterpret_cast<int8_t*>(ws + lay.off_a), plan, shift_mode, st);
+  // rows of op(A): strided in a stored m x k matrix, contiguous in a stored k x m matrix;
   // columns of op(B): contiguous in a stored k x n matrix, strided in a stored n x k matrix
-  convert_operand(B, ldb, transb != 0, n, lay.n_pad, k, lay.k_pad,
-                  reinterpret_cast<unsigned long long*>(ws + lay.off_colmax),
-                  reinterpret_cast<unsigned long long*>(ws + lay.off_colnorm), reinterpret_cast<int*>(ws + lay.off_sb),
-                  reinterpret_cast<int8_t*>(ws + lay.off_b), plan, shift_mode, st);
+  const Operand ops[2] = {
+      {A, lda, transa == 0, m, lay.m_pad, k, lay.k_pad, reinterpret_cast<unsigned long long*>(ws + lay.off_rowmax),
+       reinterpret_cast<unsigned long long*>(ws + lay.off_rownorm), reinterpret_cast<int*>(ws + lay.off_sa),
+       reinterpret_cast<int8_t*>(ws + lay.off_a)},
+      {B, ldb, transb != 0, n, lay.n_pad, k, lay.k_pad, reinterpret_cast<unsigned long long*>(ws + lay.off_colmax),
+       reinterpret_cast<unsigned long long*>(ws + lay.off_colnorm), reinterpret_cast<int*>(ws + lay.off_sb),
+       reinterpret_cast<int8_t*>(ws + lay.off_b)}};
+  const dim3 thr(kThreads);
+  Oz2ConvConsts conv = plan.conv;
+  int xbits;  // |x'| < 2^xbits decides how deep the conversion kernels split an element
+  if (shift_mode == OZ2_SHIFT_INT8_PRODUCT) {
+    // bound planes (in the slots of residue plane 0), their INT8 product (in the slot of product plane 0),
+    // its row and column maxima, then the shifts
+    for (const Operand& o : ops) {
+      launch_max(o, st);
+      hipLaunchKernelGGL(shifts_kernel, dim3(blocks_of(o.nvec_pad, kThreads)), thr, 0, st, o.vmax, o.shifts, o.nvec_pad, 6);
+      launch_convert(o, 2, conv, st);
+      hipLaunchKernelGGL(fill_u64_kernel, dim3(blocks_of(o.nvec_pad, kThreads)), thr, 0, st, o.vaux, o.nvec_pad);
+    }
+    hipError_t e = oz2_launch_bound_gemm(lay, ws, st);
+    if (e != hipSuccess) return e;
+    const int64_t row_blocks = lay.m_pad / kThreads;
+    const int64_t nblk = row_blocks * (int64_t)blocks_of(n, kProdCols);
+    if (nblk >= ((int64_t)1 << 31)) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(prodmax_kernel, dim3((unsigned)nblk), thr, 0, st, reinterpret_cast<const int*>(ws + lay.off_c),
+                       lay.m_pad, m, n, row_blocks, ops[0].vaux, ops[1].vaux);
+    for (const Operand& o : ops)
+      hipLaunchKernelGGL(shifts_prod_kernel, dim3(blocks_of(o.nvec_pad, kThreads)), thr, 0, st, o.vmax, o.vaux, o.shifts,
+                         o.nvec_pad, plan.budget2);
+    xbits = plan.budget2 / 2 + 7;  // |x'| < 2^(e + 1 + sa) <= 2^(floor(b/2) + 6)
+  } else if (shift_mode == OZ2_SHIFT_CAUCHY_SCHWARZ) {
+    for (const Operand& o : ops) {
+      launch_max(o, st);
+      launch_norm(o, st);
+      hipLaunchKernelGGL(shifts_cs_kernel, dim3(blocks_of(o.nvec_pad, kThreads)), thr, 0, st, o.vmax, o.vaux, o.shifts,
+                         o.nvec_pad, plan.beta);
+    }
+    xbits = plan.beta + 1;
+  } else {
+    for (const Operand& o : ops) {
+      launch_max(o, st);
+      hipLaunchKernelGGL(shifts_kernel, dim3(blocks_of(o.nvec_pad, kThreads)), thr, 0, st, o.vmax, o.shifts, o.nvec_pad,
+                         plan.kappa);
+    }
+    xbits = plan.kappa;
+  }
+  conv.two_level = xbits > 75;
+  for (const Operand& o : ops) launch_convert(o, conv.two_level ? 1 : 0, conv, st);
   return hipGetLastError();
 }
 

@@ -302,18 +302,25 @@ __global__ void __launch_bounds__(kThreads) gemm_i8_kernel(const GemmArgs g) {
 
 }  // namespace
 
-hipError_t oz2_launch_stage2(const Oz2Plan& plan, const Oz2Layout& lay, char* ws, int64_t kblock, int residue_u8,
-                             hipStream_t st) {
+namespace {
+
+hipError_t set_lds_attributes() {
   static bool attr_set = false;
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_i8_kernel<false>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
-    if (e == hipSuccess)
-      e = hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_i8_kernel<true>),
-                              hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
-    if (e != hipSuccess) return e;
-    attr_set = true;
-  }
+  if (attr_set) return hipSuccess;
+  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_i8_kernel<false>),
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
+  if (e == hipSuccess)
+    e = hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_i8_kernel<true>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
+  if (e == hipSuccess) attr_set = true;
+  return e;
+}
+
+// num_moduli planes of A' (off_a) times planes of B' (off_b) -> planes of C' (off_c)
+hipError_t launch_gemm(const Oz2Layout& lay, char* ws, int num_moduli, const int* moduli, int64_t kblock, int residue_u8,
+                       hipStream_t st) {
+  hipError_t e = set_lds_attributes();
+  if (e != hipSuccess) return e;
   GemmArgs g;
   g.a = reinterpret_cast<const int8_t*>(ws + lay.off_a);
   g.b = reinterpret_cast<const int8_t*>(ws + lay.off_b);
@@ -323,18 +330,32 @@ hipError_t oz2_launch_stage2(const Oz2Plan& plan, const Oz2Layout& lay, char* ws
   g.k_pad = lay.k_pad;
   g.tiles_m = (int)(lay.m_pad / BM);
   g.tiles_n = (int)(lay.n_pad / BN);
-  g.num_moduli = plan.N;
-  const int64_t total = (int64_t)g.tiles_m * g.tiles_n * plan.N;
+  g.num_moduli = num_moduli;
+  const int64_t total = (int64_t)g.tiles_m * g.tiles_n * num_moduli;
   if (total > (int64_t)1 << 30) return hipErrorInvalidValue;
   g.total = (int)total;
   g.chunk = (int)((total + 7) / 8);
   g.superblock = (g.tiles_m % 16 == 0 && g.tiles_n % 16 == 0) ? 1 : 0;
   g.ktiles = (int)(lay.k_pad / BK);
   g.ktiles_per_block = (int)(kblock / BK);
-  for (int t = 0; t < OZ2_MAX_N; ++t) g.p[t] = t < plan.N ? (float)plan.moduli[t] : 1.0f;
+  for (int t = 0; t < OZ2_MAX_N; ++t) g.p[t] = t < num_moduli ? (float)moduli[t] : 1.0f;
   if (residue_u8)
     hipLaunchKernelGGL(gemm_i8_kernel<true>, dim3((unsigned)(g.chunk * 8)), dim3(kThreads), kLdsBytes, st, g);
   else
     hipLaunchKernelGGL(gemm_i8_kernel<false>, dim3((unsigned)(g.chunk * 8)), dim3(kThreads), kLdsBytes, st, g);
   return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t oz2_launch_stage2(const Oz2Plan& plan, const Oz2Layout& lay, char* ws, int64_t kblock, int residue_u8,
+                             hipStream_t st) {
+  return launch_gemm(lay, ws, plan.N, plan.moduli, kblock, residue_u8, st);
+}
+
+// One plain INT8 product with INT32 output and no modular reduction between k-blocks: the caller guarantees
+// k_pad * 64 * 64 < 2^31.
+hipError_t oz2_launch_bound_gemm(const Oz2Layout& lay, char* ws, hipStream_t st) {
+  const int one = 1;
+  return launch_gemm(lay, ws, 1, &one, lay.k_pad, 0, st);
 }

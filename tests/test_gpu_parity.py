@@ -326,6 +326,63 @@ def test_cauchy_schwarz_mode_full_size_c4_sampled():
     del ws
 
 
+@pytest.mark.parametrize("m,n,k,N,phi", [
+    (256, 256, 256, 14, 0.5),     # config 1
+    (300, 200, 333, 5, 0.5),
+    (64, 40, 1000, 20, 4.0),
+    (33, 17, 50, 26, 4.0),        # 2^(b/2 + 7) > 2^75: two-level split
+    (530, 70, 130, 16, 1.0),      # three row blocks and two column chunks of the product-maximum kernel
+    (1, 1, 1, 2, 0.5),
+])
+def test_int8_product_mode_all_stages(m, n, k, N, phi):
+    rng = np.random.default_rng(m * 11 + n)
+    A = (rng.random((m, k)) - 0.5) * np.exp(phi * rng.standard_normal((m, k)))
+    B = (rng.random((k, n)) - 0.5) * np.exp(phi * rng.standard_normal((k, n)))
+    if m > 4:
+        A[3, :] = 0.0
+        A[4, 1:] = 0.0
+        A[2, :] *= 2.0**-200
+        A[5, 0] = 2.0**-1074      # far below the row's unit: its bound is one unit, not zero
+        B[:, 1] = 0.0
+    check_against_oracle(A, B, N, mode=2)
+
+
+def test_int8_product_mode_full_size_c3_sampled_and_transposed():
+    # the shifts depend on all rows and columns; both operands are handed over transposed, so each is read
+    # by the stage-1 kernels of the other orientation
+    cfg = inputs.CONFIGS["c3"]
+    m, n, k, phi, N = cfg["m"], cfg["n"], cfg["k"], cfg["phi"], 15
+    A = inputs.block(cfg["seed"], 0, m, k, phi)
+    B = inputs.block(cfg["seed"], 1, k, n, phi)
+    rng = np.random.default_rng(5)
+    rows = np.unique(np.concatenate([[0, m - 1], rng.choice(m, 20, replace=False)]))
+    cols = np.unique(np.concatenate([[0, n - 1], rng.choice(n, 20, replace=False)]))
+    ref = orc.dgemm(A, B, N, mode=2, rows=rows, cols=cols, want=("C", "shifts"))
+    dAt, dBt = _dev(A.T), _dev(B.T)      # stored k x m and n x k, column-major
+    dC = torch.full((n, m), float("nan"), dtype=torch.float64, device="cuda").t()
+    ws = oz.Workspace(m, n, k, N)
+    oz.oz2_set_shift_mode(2)
+    try:
+        print("int8-product mode, transposed operands, m=%d n=%d k=%d N=%d" % (m, n, k, N), flush=True)
+        oz.oz2_dgemm_ex("T", "T", m, n, k, 1.0, dAt.data_ptr(), k, dBt.data_ptr(), n, 0.0, dC.data_ptr(), m, N)
+        torch.cuda.synchronize()
+    finally:
+        oz.oz2_set_shift_mode(0)
+    lay = oz.workspace_layout(m, n, k, N)
+    sa = ws.view(lay["sa"], lay["m_pad"], torch.int32).cpu().numpy()
+    sb = ws.view(lay["sb"], lay["n_pad"], torch.int32).cpu().numpy()
+    assert np.array_equal(sa[rows], ref.sa) and np.array_equal(sb[cols], ref.sb)
+    got = dC[torch.from_numpy(rows).cuda()][:, torch.from_numpy(cols).cuda()].cpu().numpy()
+    assert np.array_equal(got, ref.C)
+    Asub, Bsub = np.asfortranarray(A[rows, :]), np.asfortranarray(B[:, cols])
+    Cx, S = orc.exact(Asub, Bsub)
+    e_prod = np.max(np.abs(got - Cx) / S)
+    e_plain = np.max(np.abs(orc.dgemm(Asub, Bsub, N, mode=0).C - Cx) / S)
+    print("N=15 at 4096^3: componentwise error INT8-product bound %.3g, simple bound %.3g" % (e_prod, e_plain), flush=True)
+    assert e_prod < e_plain
+    del ws
+
+
 @pytest.mark.parametrize("ta,tb", [("N", "N"), ("T", "N"), ("N", "T"), ("T", "T")])
 @pytest.mark.parametrize("alpha,beta", [(1.0, 0.0), (-0.75, 1.5), (2.0, 1.0)])
 def test_dgemm_ex_transposes_and_scalars(ta, tb, alpha, beta):

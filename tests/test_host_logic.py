@@ -58,6 +58,14 @@ def test_argument_validation_without_gpu():
     assert L.oz2_dgemm(4, 4, 4, None, 4, None, 4, None, 4, 4, None) == -8     # C is NULL
     assert L.oz2_dgemm(0, 0, 0, None, 1, None, 1, None, 1, 4, None) == 0      # empty: nothing to do
     assert L.oz2_stage2_gemm(4, 4, 4, 4, None) == 1                          # no workspace registered
+    assert L.oz2_set_shift_mode(3) == -1 and L.oz2_set_shift_mode(-1) == -1
+    # the INT8 product of 6-bit bounds must fit INT32: the inner dimension stays below 2^19 in that mode
+    assert L.oz2_set_shift_mode(2) == 0
+    try:
+        assert L.oz2_stage2_gemm(4, 4, (1 << 19) - 64, 26, None) == 1         # accepted; fails later: no workspace
+        assert L.oz2_stage2_gemm(4, 4, (1 << 19) - 63, 26, None) == 2         # budget
+    finally:
+        assert L.oz2_set_shift_mode(0) == 0
     assert oz.lib().oz2_status_string(1).decode().startswith("workspace")
     assert oz.lib().oz2_status_string(-3).decode() == "invalid argument"
 

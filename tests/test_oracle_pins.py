@@ -392,6 +392,79 @@ def test_cauchy_schwarz_reaches_native_accuracy_with_14_or_15_moduli():
     assert err[14] < 4 * native
 
 
+# ------------------------------------------------------------------ Section 4.1: INT8-product shift selection
+@pytest.mark.parametrize("N,phi", [(4, 0.5), (10, 1.0), (16, 0.5), (20, 4.0), (26, 4.0)])
+def test_int8_product_shifts_are_rigorous_and_tight(N, phi):
+    m, n, k = 7, 6, 11
+    A, B = _tiny(700 + N, m, n, k, phi)
+    A[1, :] = 0.0
+    B[:, 2] = 0.0
+    A[3, 0] = 5e-324 if phi > 1 else A[3, 0]      # a subnormal entry still needs a bound of at least one unit
+    mods = orc.moduli(N)
+    M = math.prod(mods)
+    b = orc.log2_budget(N)
+    assert 2**b <= M // 2 - 1 < 2 ** (b + 1)
+    r = orc.dgemm(A, B, N, mode=2, want=("C", "shifts", "Ap", "Bp", "X"))
+    assert r.sa[1] == 0 and r.sb[2] == 0
+
+    def expo(vec):
+        return max(math.frexp(abs(float(x)))[1] - 1 for x in vec if x != 0)
+
+    # the 6-bit upper bounds and their product, from exact rationals
+    ea = [expo(A[i, :]) if np.any(A[i, :]) else 0 for i in range(m)]
+    fb = [expo(B[:, j]) if np.any(B[:, j]) else 0 for j in range(n)]
+    A2 = [[math.ceil(abs(Fraction(float(A[i, l]))) * Fraction(2) ** (5 - ea[i])) for l in range(k)] for i in range(m)]
+    B2 = [[math.ceil(abs(Fraction(float(B[l, j]))) * Fraction(2) ** (5 - fb[j])) for j in range(n)] for l in range(k)]
+    assert max(max(row) for row in A2) <= 64 and max(max(row) for row in B2) <= 64
+    P = [[sum(A2[i][l] * B2[l][j] for l in range(k)) for j in range(n)] for i in range(m)]
+    for i in range(m):
+        R = max(P[i])
+        if R == 0:
+            continue
+        u = int(r.sa[i]) + ea[i] - 5
+        # tight: the row's largest bound, scaled by 4^u, lands in the top two bits of the budget
+        assert Fraction(2) ** (b - 2) < Fraction(4) ** u * R <= Fraction(2) ** b
+    for j in range(n):
+        Cm = max(P[i][j] for i in range(m))
+        if Cm == 0:
+            continue
+        v = int(r.sb[j]) + fb[j] - 5
+        assert Fraction(2) ** (b - 2) < Fraction(4) ** v * Cm <= Fraction(2) ** b
+    # rigorous: the uniqueness premise of Section 3 on the truncated integers themselves, and the bound chain
+    for i in range(m):
+        for j in range(n):
+            absprod = sum(abs(r.Ap[i][l]) * abs(r.Bp[l][j]) for l in range(k))
+            bound = Fraction(2) ** (int(r.sa[i]) + ea[i] - 5 + int(r.sb[j]) + fb[j] - 5) * P[i][j]
+            assert absprod <= bound <= M // 2 - 1
+            ex = sum(r.Ap[i][l] * r.Bp[l][j] for l in range(k))
+            assert r.X[i][j] == ex
+            assert r.C[i, j] == float(Fraction(ex) / Fraction(2) ** (int(r.sa[i]) + int(r.sb[j])))
+    for i in range(m):
+        for l in range(k):
+            assert r.Ap[i][l] == math.trunc(Fraction(float(A[i, l])) * Fraction(2) ** int(r.sa[i]))
+
+
+def test_int8_product_shifts_subset_and_accuracy():
+    # the maxima run over all rows and columns: a subset call must give the shifts of the full call; the
+    # bound is never worse than a few bits below the Cauchy-Schwarz one and the error at 14 moduli is at the
+    # level of native FP64 (Section 4.1: both variants need 14 or 15 moduli at phi = 0.5)
+    cfg = inputs.CONFIGS["c1"]
+    m, n, k = cfg["m"], cfg["n"], cfg["k"]
+    A = inputs.block(cfg["seed"], 0, m, k, cfg["phi"])
+    B = inputs.block(cfg["seed"], 1, k, n, cfg["phi"])
+    full = orc.dgemm(A, B, 14, mode=2, want=("C", "shifts"))
+    rows, cols = np.array([0, 5, 77, 255]), np.array([3, 128, 254])
+    sub = orc.dgemm(A, B, 14, mode=2, rows=rows, cols=cols, want=("C", "shifts"))
+    assert np.array_equal(sub.sa, full.sa[rows]) and np.array_equal(sub.sb, full.sb[cols])
+    assert np.array_equal(sub.C, full.C[np.ix_(rows, cols)])
+    Cx, S = orc.exact(A, B)
+    native = np.max(np.abs(A @ B - Cx) / S)
+    e2 = np.max(np.abs(full.C - Cx) / S)
+    e1 = np.max(np.abs(orc.dgemm(A, B, 14, mode=1).C - Cx) / S)
+    e0 = np.max(np.abs(orc.dgemm(A, B, 14).C - Cx) / S)
+    assert e2 < e0 and e2 < 4 * e1 and e2 < 4 * native
+
+
 def test_blas_update_against_rationals():
     # C := alpha * P + beta * C: one rounding of beta*C, then a fused multiply-add; beta == 0 ignores C
     A, B = _tiny(61, 4, 3, 6, 0.5)
