@@ -265,11 +265,11 @@ __global__ void __launch_bounds__(kThreads) gemm_i8_kernel(const GemmArgs g) {
     const unsigned bias = (pu - two31) % pu;
     const float pf = g.p[t], ipf = 1.0f / pf, hipf = 0.5f / pf;
     const size_t col = (size_t)tn * BN + wn * 128 + (lane & 31);       // + tj*32
-    const size_t row0 = (size_t)tm * BM + wm * 128 + 4 * half;         // + ti*32 + 8*a
     uint8_t* plane = reinterpret_cast<uint8_t*>(g.c) + (size_t)t * g.n_pad * g.m_pad;
 #pragma unroll
     for (int tj = 0; tj < 4; ++tj) {
-      uint8_t* cj = plane + (col + tj * 32) * g.m_pad + row0;
+      // w[ti][a]: rows ti*32 + 8a + 4*half + (0..3) of column j, one byte each
+      unsigned w[4][4];
 #pragma unroll
       for (int ti = 0; ti < 4; ++ti)
 #pragma unroll
@@ -282,8 +282,20 @@ __global__ void __launch_bounds__(kThreads) gemm_i8_kernel(const GemmArgs g) {
             const float q = floorf(fmaf(x, ipf, hipf));
             v = __builtin_amdgcn_cvt_pk_u8_f32(fmaf(-q, pf, x), b, v);
           }
-          *reinterpret_cast<unsigned*>(cj + ti * 32 + 8 * a) = v;
+          w[ti][a] = v;
         }
+      // Lanes l and l + 32 hold the two interleaved halves of the same 32 rows.  Swapping the upper half
+      // of w[ti][a] with the lower half of w[ti][a+2] leaves lane l with rows 0..15 and lane l + 32 with
+      // rows 16..31 of the 32-row group, 16 contiguous bytes each: one 16-byte store per lane and group,
+      // issued together so that the cache lines of the column are complete at once.
+      uint8_t* cj = plane + (col + tj * 32) * g.m_pad + (size_t)tm * BM + wm * 128 + 16 * half;
+#pragma unroll
+      for (int ti = 0; ti < 4; ++ti) {
+        const auto s0 = __builtin_amdgcn_permlane32_swap(w[ti][0], w[ti][2], false, false);
+        const auto s1 = __builtin_amdgcn_permlane32_swap(w[ti][1], w[ti][3], false, false);
+        v4i o = {(int)s0[0], (int)s0[1], (int)s1[0], (int)s1[1]};
+        *reinterpret_cast<v4i*>(cj + ti * 32) = o;
+      }
     }
   } else {
     // lane holds row i = lane % 32 of a 32 x 32 tile, register e column 8 (e / 4) + 4 (lane / 32) + e % 4

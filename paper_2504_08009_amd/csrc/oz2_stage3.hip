@@ -76,22 +76,30 @@ __global__ void __launch_bounds__(kThreads) crt_kernel(const void* __restrict__ 
   }
   const int sbj = sb[j];
   double* dst = C + i0 + j * ldc;
-  const bool plain = alpha == 1.0 && beta == 0.0;
+  double out[R];
 #pragma unroll
   for (int r = 0; r < R; ++r) {
     int e2;
     const double x = oz2_crt_reduce<L>(S[r], cc, &e2);
-    const double out = ldexp(x, e2 - sa[i0 + r] - sbj);  // sa is padded to m_pad (a multiple of 256): readable
-    if (i0 + r < m) {
-      if (plain) {
-        dst[r] = out;
-      } else {
-        // C := alpha * P + beta * C with one rounding of beta * C and one fused multiply-add; C is not
-        // read when beta is zero (BLAS convention)
-        const double tt = beta == 0.0 ? 0.0 : beta * dst[r];
-        dst[r] = fma(alpha, out, tt);
-      }
+    out[r] = ldexp(x, e2 - sa[i0 + r] - sbj);  // sa is padded to m_pad (a multiple of 256): readable
+  }
+  if (alpha != 1.0 || beta != 0.0) {
+    // C := alpha * P + beta * C with one rounding of beta * C and one fused multiply-add; C is not read when
+    // beta is zero (BLAS convention)
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+      const double tt = (beta == 0.0 || i0 + r >= m) ? 0.0 : beta * dst[r];
+      out[r] = fma(alpha, out[r], tt);
     }
+  }
+  // all R results of the thread leave together: its 8 R contiguous bytes complete their cache lines at once
+  if (i0 + R <= m && ((reinterpret_cast<uintptr_t>(dst) & 15) == 0)) {
+#pragma unroll
+    for (int r = 0; r < R; r += 2) *reinterpret_cast<double2*>(dst + r) = make_double2(out[r], out[r + 1]);
+  } else {
+#pragma unroll
+    for (int r = 0; r < R; ++r)
+      if (i0 + r < m) dst[r] = out[r];
   }
 }
 
