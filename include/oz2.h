@@ -59,7 +59,7 @@ size_t oz2_workspace_bytes(int64_t m, int64_t n, int64_t k, int num_moduli);
 int oz2_set_workspace(void* dev_ptr, size_t bytes);
 
 /* Where each intermediate lives inside the workspace, so that a test can read every stage's output.
- * offsets[0..8] (bytes from the workspace start):
+ * offsets[0..9] (bytes from the workspace start):
  *   0 rowmax  : m_pad uint64, bit pattern of max_l |a_il| per row of A
  *   1 colmax  : n_pad uint64, same per column of B
  *   2 sa      : m_pad int32 shifts of A's rows      (Algorithm 1 line 1)
@@ -74,9 +74,10 @@ int oz2_set_workspace(void* dev_ptr, size_t bytes);
  *               (OZ2_PRODUCT_RESIDUE_U8, the planes then fill the first quarter of the region)
  *   7 rownorm : m_pad uint64, integer norm bound S_i of A's rows (Cauchy-Schwarz shift mode only)
  *   8 colnorm : n_pad uint64, same per column of B
+ *   9 flags   : 32 uint64; word 0 is 1 after a stage 1 that found an infinity or a NaN in A or B, else 0
  * dims[0..2] = m_pad, n_pad, k_pad (m, n rounded up to 256, k to 64; padding holds zeros).
  * Returns 0 or a negative argument code. */
-int oz2_workspace_layout(int64_t m, int64_t n, int64_t k, int num_moduli, size_t offsets[9], int64_t dims[3]);
+int oz2_workspace_layout(int64_t m, int64_t n, int64_t k, int num_moduli, size_t offsets[10], int64_t dims[3]);
 
 /* The whole of Algorithm 1:  C := A*B  with num_moduli INT8 products.
  *   A: m x k, lda >= max(1,m);  B: k x n, ldb >= max(1,k);  C: m x n, ldc >= max(1,m).
@@ -105,6 +106,17 @@ int oz2_stage1_convert(int64_t m, int64_t n, int64_t k, const double* A, int64_t
                        int64_t ldb, int num_moduli, void* stream);
 int oz2_stage2_gemm(int64_t m, int64_t n, int64_t k, int num_moduli, void* stream);
 int oz2_stage3_crt(int64_t m, int64_t n, int64_t k, double* C, int64_t ldc, int num_moduli, void* stream);
+
+/* Exceptional values (Section 3.1, closing remark: the emulation covers products of finite matrices; NaNs
+ * and infinities need detection and a fallback to ordinary FP64 arithmetic).  With the check on (default),
+ * stage 1 of oz2_dgemm / oz2_dgemm_ex records in the workspace whether A or B holds an infinity or a NaN
+ * (free: the row / column maxima are taken on bit patterns); stage 3 then leaves C alone and an FP64 kernel
+ * launched behind it forms C := alpha op(A) op(B) + beta C by the IEEE rules.  The decision is taken on the
+ * device, the call does not synchronise; the workspace flag (oz2_workspace_layout, entry 9) tells afterwards
+ * which way it went.  Signed zeros are not tracked: an emulated result that is zero is +0.  With the check
+ * off the extra launch is skipped and non-finite inputs give unspecified values in C.  The staged entry points
+ * (oz2_stage1_convert ...) never fall back.  on: 0 or 1.  Returns 0 or -1. */
+int oz2_set_nonfinite_check(int on);
 
 /* What stage 2 leaves in the C planes, for all later calls.  OZ2_PRODUCT_RESIDUE_U8 (default): the GEMM
  * epilogue takes Algorithm 1 line 7 (c'' = c' - floor(c'/p_t) p_t) and stores one byte per element, so that

@@ -35,6 +35,9 @@ def lib():
         _lib.oz2o_kappa.argtypes = [ctypes.c_int, ctypes.c_void_p, ctypes.c_int64]
         _lib.oz2o_beta.argtypes = [ctypes.c_int, ctypes.c_void_p]
         _lib.oz2o_log2_budget.argtypes = [ctypes.c_int, ctypes.c_void_p]
+        _lib.oz2o_native_gemm.argtypes = [ctypes.c_int, ctypes.c_int] + [ctypes.c_int64] * 3 + [
+            ctypes.c_void_p, ctypes.c_int64, ctypes.c_void_p, ctypes.c_int64, ctypes.c_void_p]
+        _lib.oz2o_has_nonfinite.argtypes = [ctypes.c_int64, ctypes.c_int64, ctypes.c_void_p, ctypes.c_int64]
         _lib.oz2o_axpby.argtypes = [ctypes.c_int64, ctypes.c_double, ctypes.c_void_p, ctypes.c_double, ctypes.c_void_p]
         _lib.oz2o_shifts.argtypes = [ctypes.c_int, ctypes.c_int64, ctypes.c_int64, ctypes.c_void_p,
                                      ctypes.c_int64, ctypes.c_int, ctypes.c_void_p]
@@ -172,14 +175,35 @@ def dgemm(A, B, N, mods=None, rows=None, cols=None, want=("C",), mode=0):
     return out
 
 
-def dgemm_ex(transa, transb, alpha, A, B, beta, C, N, mode=0):
+def native_gemm(opA, opB):
+    """Textbook FP64 product (oz2o_native_gemm): the fallback for inputs with infinities or NaNs."""
+    A = np.asfortranarray(opA, dtype=np.float64)
+    B = np.asfortranarray(opB, dtype=np.float64)
+    m, k = A.shape
+    _, n = B.shape
+    P = np.zeros((m, n), order="F")
+    rc = lib().oz2o_native_gemm(0, 0, m, n, k, _ptr(A), max(1, m), _ptr(B), max(1, k), _ptr(P))
+    if rc:
+        raise ValueError("oz2o_native_gemm -> %d" % rc)
+    return P
+
+
+def has_nonfinite(X):
+    X = np.asfortranarray(X, dtype=np.float64)
+    return bool(lib().oz2o_has_nonfinite(X.shape[0], X.shape[1], _ptr(X), max(1, X.shape[0])))
+
+
+def dgemm_ex(transa, transb, alpha, A, B, beta, C, N, mode=0, check_nonfinite=True):
     """C := alpha * op(A) op(B) + beta * C with the product formed by Algorithm 1 (see oz2o_axpby for the
-    order of the floating-point operations of the update).  A, B as stored; returns the new C."""
+    order of the floating-point operations of the update), or by the textbook FP64 loop when check_nonfinite
+    is set and A or B holds an infinity or a NaN.  A, B as stored; returns the new C."""
     opA = A.T if transa in "TtCc" else A
     opB = B.T if transb in "TtCc" else B
     m, k = opA.shape
     if k == 0 or alpha == 0.0:
         P = np.zeros((m, opB.shape[1]), order="F")
+    elif check_nonfinite and (has_nonfinite(opA) or has_nonfinite(opB)):
+        P = native_gemm(opA, opB)
     else:
         P = dgemm(opA, opB, N, mode=mode).C
     out = np.array(C, dtype=np.float64, order="F", copy=True)

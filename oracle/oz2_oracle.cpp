@@ -672,6 +672,36 @@ int oz2o_axpby(int64_t count, double alpha, const double* P, double beta, double
   return 0;
 }
 
+// Ordinary FP64 product for inputs the emulation does not cover (Section 3.1, closing remark: NaNs and
+// infinities need detection and a fallback to a native binary64 routine): the textbook triple loop,
+// P_ij = sum over l = 0 .. k-1 in that order of a_il * b_lj, every product and every sum rounded to FP64.
+// op(A) is m x k, op(B) is k x n; transa / transb != 0 mean the arrays hold the transposes.
+int oz2o_native_gemm(int transa, int transb, int64_t m, int64_t n, int64_t k, const double* A, int64_t lda,
+                     const double* B, int64_t ldb, double* P) {
+  if (m < 0 || n < 0 || k < 0) return -1;
+#pragma omp parallel for schedule(static)
+  for (int64_t j = 0; j < n; ++j)
+    for (int64_t i = 0; i < m; ++i) {
+      volatile double acc = 0.0;  // volatile: no fused or reassociated evaluation
+      for (int64_t l = 0; l < k; ++l) {
+        const double a = transa ? A[l + i * lda] : A[i + l * lda];
+        const double b = transb ? B[j + l * ldb] : B[l + j * ldb];
+        volatile double prod = a * b;
+        acc = acc + prod;
+      }
+      P[i + j * m] = acc;
+    }
+  return 0;
+}
+
+// 1 when any of the count doubles at X (column-major rows x cols with leading dimension ld) is an infinity or a NaN
+int oz2o_has_nonfinite(int64_t rows, int64_t cols, const double* X, int64_t ld) {
+  for (int64_t c = 0; c < cols; ++c)
+    for (int64_t r = 0; r < rows; ++r)
+      if (!std::isfinite(X[r + c * ld])) return 1;
+  return 0;
+}
+
 // Reference product on the same subset in binary128: every product of two doubles is exact in 113 bits,
 // the sum is accumulated in binary128 (relative error about k * 2^-113 of sum |a||b|).
 // C_ref = rounded-to-double sum, absAB = sum_l |a_il| |b_lj| rounded to double.

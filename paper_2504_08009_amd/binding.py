@@ -9,7 +9,7 @@ _lib = None
 SYMBOLS = [
     "oz2_min_moduli", "oz2_max_moduli", "oz2_get_moduli", "oz2_workspace_bytes", "oz2_set_workspace",
     "oz2_workspace_layout", "oz2_dgemm", "oz2_dgemm_ex", "oz2_stage1_convert", "oz2_stage2_gemm", "oz2_stage3_crt",
-    "oz2_set_kblock", "oz2_set_shift_mode", "oz2_set_product_format", "oz2_set_stage_events", "oz2_calibrate_mfma", "oz2_host_crt_element", "oz2_host_residues", "oz2_status_string",
+    "oz2_set_kblock", "oz2_set_shift_mode", "oz2_set_product_format", "oz2_set_nonfinite_check", "oz2_set_stage_events", "oz2_calibrate_mfma", "oz2_host_crt_element", "oz2_host_residues", "oz2_status_string",
 ]
 
 
@@ -39,6 +39,7 @@ def lib():
         L.oz2_set_kblock.argtypes = [i64]
         L.oz2_set_shift_mode.argtypes = [ci]
         L.oz2_set_product_format.argtypes = [ci]
+        L.oz2_set_nonfinite_check.argtypes = [ci]
         L.oz2_set_stage_events.argtypes = [vp]
         L.oz2_calibrate_mfma.argtypes = [ci, ci, ci, vp, vp, vp]
         L.oz2_host_crt_element.argtypes = [ci, vp, vp]
@@ -76,10 +77,10 @@ def workspace_bytes(m, n, k, num_moduli):
 
 def workspace_layout(m, n, k, num_moduli):
     """dict of byte offsets and padded dims (see include/oz2.h)."""
-    offs = (ctypes.c_size_t * 9)()
+    offs = (ctypes.c_size_t * 10)()
     dims = (ctypes.c_int64 * 3)()
     _check(lib().oz2_workspace_layout(m, n, k, num_moduli, offs, dims), "oz2_workspace_layout")
-    names = ["rowmax", "colmax", "sa", "sb", "a_planes", "b_planes", "c_planes", "rownorm", "colnorm"]
+    names = ["rowmax", "colmax", "sa", "sb", "a_planes", "b_planes", "c_planes", "rownorm", "colnorm", "flags"]
     out = {nm: int(o) for nm, o in zip(names, offs)}
     out.update(m_pad=int(dims[0]), n_pad=int(dims[1]), k_pad=int(dims[2]))
     return out
@@ -105,6 +106,11 @@ OZ2_PRODUCT_INT32, OZ2_PRODUCT_RESIDUE_U8 = 0, 1
 def oz2_set_product_format(fmt):
     """0: INT32 products in the C planes; 1 (default): UINT8 residues written by the GEMM epilogue."""
     _check(lib().oz2_set_product_format(int(fmt)), "oz2_set_product_format")
+
+
+def oz2_set_nonfinite_check(on):
+    """1 (default): infinities / NaNs in A or B are detected and C is formed by the FP64 fallback kernel."""
+    _check(lib().oz2_set_nonfinite_check(int(on)), "oz2_set_nonfinite_check")
 
 
 def oz2_set_stage_events(events):

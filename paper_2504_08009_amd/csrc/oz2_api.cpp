@@ -12,6 +12,7 @@ struct State {
   size_t ws_bytes = 0;
   int64_t kblock = 65536;
   int shift_mode = 0;
+  int nonfinite_check = 1;
   int product_format = OZ2_PRODUCT_RESIDUE_U8;
   hipEvent_t ev[4] = {nullptr, nullptr, nullptr, nullptr};
   bool ev_on = false;
@@ -91,7 +92,7 @@ int oz2_set_workspace(void* dev_ptr, size_t bytes) {
   return OZ2_OK;
 }
 
-int oz2_workspace_layout(int64_t m, int64_t n, int64_t k, int num_moduli, size_t offsets[9], int64_t dims[3]) {
+int oz2_workspace_layout(int64_t m, int64_t n, int64_t k, int num_moduli, size_t offsets[10], int64_t dims[3]) {
   if (m < 0) return -1;
   if (n < 0) return -2;
   if (k < 0) return -3;
@@ -110,6 +111,7 @@ int oz2_workspace_layout(int64_t m, int64_t n, int64_t k, int num_moduli, size_t
   offsets[6] = lay.off_c;
   offsets[7] = lay.off_rownorm;
   offsets[8] = lay.off_colnorm;
+  offsets[9] = lay.off_flags;
   dims[0] = lay.m_pad;
   dims[1] = lay.n_pad;
   dims[2] = lay.k_pad;
@@ -129,6 +131,14 @@ int oz2_set_shift_mode(int mode) {
   State& s = state();
   std::lock_guard<std::mutex> lock(s.mu);
   s.shift_mode = mode;
+  return OZ2_OK;
+}
+
+int oz2_set_nonfinite_check(int on) {
+  if (on != 0 && on != 1) return -1;
+  State& s = state();
+  std::lock_guard<std::mutex> lock(s.mu);
+  s.nonfinite_check = on;
   return OZ2_OK;
 }
 
@@ -205,7 +215,7 @@ int oz2_stage3_crt(int64_t m, int64_t n, int64_t k, double* C, int64_t ldc, int 
   Oz2Layout lay;
   int rc = prepare(s, m, n, k, num_moduli, &plan, &lay);
   if (rc) return rc;
-  hipError_t e = oz2_launch_stage3(m, n, 1.0, 0.0, C, ldc, *plan, lay, s.ws, s.product_format, st);
+  hipError_t e = oz2_launch_stage3(m, n, 1.0, 0.0, C, ldc, *plan, lay, s.ws, s.product_format, 0, st);
   return e == hipSuccess ? OZ2_OK : OZ2_ERR_HIP;
 }
 
@@ -253,7 +263,13 @@ int oz2_dgemm_ex(char transa, char transb, int64_t m, int64_t n, int64_t k, doub
   if (oz2_launch_stage1(ta, tb, m, n, k, A, lda, B, ldb, *plan, s.shift_mode, lay, s.ws, st) != hipSuccess || !mark(1))
     return OZ2_ERR_HIP;
   if (oz2_launch_stage2(*plan, lay, s.ws, s.kblock, s.product_format, st) != hipSuccess || !mark(2)) return OZ2_ERR_HIP;
-  if (oz2_launch_stage3(m, n, alpha, beta, C, ldc, *plan, lay, s.ws, s.product_format, st) != hipSuccess || !mark(3))
+  if (oz2_launch_stage3(m, n, alpha, beta, C, ldc, *plan, lay, s.ws, s.product_format, s.nonfinite_check, st) !=
+          hipSuccess ||
+      !mark(3))
+    return OZ2_ERR_HIP;
+  if (s.nonfinite_check &&
+      oz2_launch_fallback(reinterpret_cast<const unsigned long long*>(s.ws + lay.off_flags), ta, tb, m, n, k, alpha, A, lda,
+                          B, ldb, beta, C, ldc, st) != hipSuccess)
     return OZ2_ERR_HIP;
   return OZ2_OK;
 }

@@ -1,0 +1,86 @@
+// Exceptional inputs (Section 3.1, closing remark): the emulation reproduces FP64 products of finite matrices
+// only, so infinities and NaNs in A or B are detected in stage 1 (the row / column maxima are taken on bit
+// patterns, where every non-finite value compares above every finite one) and the whole update
+//   C := alpha * op(A) * op(B) + beta * C
+// is then formed in ordinary FP64 arithmetic by the kernel below, which propagates them by the IEEE rules.
+// The kernel is launched after stage 3 of every checked call and returns at once when the flag is clear, so
+// the decision needs no device-to-host synchronisation.  It is a plain LDS-tiled FP64 kernel (128 x 128 tile,
+// 8 x 8 outputs per thread), not tuned: it only runs for inputs the method does not cover.
+#include "oz2_internal.h"
+
+namespace {
+
+constexpr int kThreads = 256;
+constexpr int FT = 128;  // tile of C
+constexpr int FK = 8;    // inner-dimension step
+
+__global__ void __launch_bounds__(kThreads) fp64_fallback_kernel(const unsigned long long* __restrict__ flag, int transa,
+                                                                 int transb, int64_t m, int64_t n, int64_t k, double alpha,
+                                                                 const double* __restrict__ A, int64_t lda,
+                                                                 const double* __restrict__ B, int64_t ldb, double beta,
+                                                                 double* __restrict__ C, int64_t ldc, int64_t tiles_m) {
+  if (*flag == 0ull) return;
+  __shared__ double As[FK][FT];
+  __shared__ double Bs[FK][FT];
+  const int64_t i0 = (int64_t)(blockIdx.x % tiles_m) * FT, j0 = (int64_t)(blockIdx.x / tiles_m) * FT;
+  const int tx = threadIdx.x & 15, ty = threadIdx.x >> 4;
+  double acc[8][8];
+#pragma unroll
+  for (int r = 0; r < 8; ++r)
+#pragma unroll
+    for (int c = 0; c < 8; ++c) acc[r][c] = 0.0;
+  for (int64_t l0 = 0; l0 < k; l0 += FK) {
+    // 128 x 8 elements of op(A) and of op(B): four each per thread; out-of-range elements are zero
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const int e = threadIdx.x + q * kThreads;
+      int ii, ll;
+      if (transa) { ll = e % FK; ii = e / FK; } else { ii = e % FT; ll = e / FT; }
+      const int64_t i = i0 + ii, l = l0 + ll;
+      As[ll][ii] = (i < m && l < k) ? (transa ? A[l + i * lda] : A[i + l * lda]) : 0.0;
+      int jj, lb;
+      if (transb) { jj = e % FT; lb = e / FT; } else { lb = e % FK; jj = e / FK; }
+      const int64_t j = j0 + jj, lq = l0 + lb;
+      Bs[lb][jj] = (j < n && lq < k) ? (transb ? B[j + lq * ldb] : B[lq + j * ldb]) : 0.0;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int l = 0; l < FK; ++l) {
+      double a[8], b[8];
+#pragma unroll
+      for (int r = 0; r < 8; ++r) a[r] = As[l][tx + 16 * r];
+#pragma unroll
+      for (int c = 0; c < 8; ++c) b[c] = Bs[l][ty + 16 * c];
+#pragma unroll
+      for (int r = 0; r < 8; ++r)
+#pragma unroll
+        for (int c = 0; c < 8; ++c) acc[r][c] = fma(a[r], b[c], acc[r][c]);
+    }
+    __syncthreads();
+  }
+#pragma unroll
+  for (int c = 0; c < 8; ++c) {
+    const int64_t j = j0 + ty + 16 * c;
+    if (j >= n) continue;
+#pragma unroll
+    for (int r = 0; r < 8; ++r) {
+      const int64_t i = i0 + tx + 16 * r;
+      if (i >= m) continue;
+      double* dst = C + i + j * ldc;
+      const double t = beta == 0.0 ? 0.0 : beta * *dst;  // C is not read when beta is zero
+      *dst = fma(alpha, acc[r][c], t);
+    }
+  }
+}
+
+}  // namespace
+
+hipError_t oz2_launch_fallback(const unsigned long long* flag, int transa, int transb, int64_t m, int64_t n, int64_t k,
+                               double alpha, const double* A, int64_t lda, const double* B, int64_t ldb, double beta,
+                               double* C, int64_t ldc, hipStream_t st) {
+  const int64_t tiles_m = (m + FT - 1) / FT, tiles_n = (n + FT - 1) / FT;
+  if (tiles_m * tiles_n >= ((int64_t)1 << 31)) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(fp64_fallback_kernel, dim3((unsigned)(tiles_m * tiles_n)), dim3(kThreads), 0, st, flag, transa, transb, m,
+                     n, k, alpha, A, lda, B, ldb, beta, C, ldc, tiles_m);
+  return hipGetLastError();
+}

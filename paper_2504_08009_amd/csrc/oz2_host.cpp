@@ -204,6 +204,8 @@ void oz2_make_layout(int64_t m, int64_t n, int64_t k, int N, Oz2Layout* lay) {
   size_t off = 0;
   lay->off_rowmax = off;
   off = up256(off + (size_t)lay->m_pad * 8);
+  lay->off_flags = off;  // directly behind the row maxima: one fill clears both
+  off += 256;
   lay->off_colmax = off;
   off = up256(off + (size_t)lay->n_pad * 8);
   lay->off_sa = off;

@@ -16,6 +16,10 @@ __global__ void __launch_bounds__(kThreads) fill_u64_kernel(unsigned long long* 
   if (i < count) p[i] = 0ull;
 }
 
+// Bit pattern of +infinity: as unsigned integers the magnitudes of infinities and NaNs are the values at or
+// above it, every finite magnitude is below.
+constexpr unsigned long long kInfBits = 0x7ff0000000000000ull;
+
 __device__ __forceinline__ unsigned long long abs_bits(double v) {
   return (unsigned long long)__double_as_longlong(v) & 0x7fffffffffffffffull;
 }
@@ -23,7 +27,8 @@ __device__ __forceinline__ unsigned long long abs_bits(double v) {
 // A is m x k column-major: lanes run along rows (coalesced), each block covers 256 rows x KC columns.
 constexpr int kRowMaxKC = 128;
 __global__ void __launch_bounds__(kThreads) rowmax_kernel(const double* __restrict__ A, int64_t lda, int64_t m,
-                                                          int64_t k, unsigned long long* __restrict__ rowmax) {
+                                                          int64_t k, unsigned long long* __restrict__ rowmax,
+                                                          unsigned long long* __restrict__ nonfinite) {
   int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
   if (i >= m) return;
   int64_t l0 = (int64_t)blockIdx.y * kRowMaxKC;
@@ -45,12 +50,14 @@ __global__ void __launch_bounds__(kThreads) rowmax_kernel(const double* __restri
     p += lda;
   }
   if (mx) atomicMax(rowmax + i, mx);
+  if (mx >= kInfBits) *nonfinite = 1ull;
 }
 
 // B is k x n column-major: one block per (column, chunk of KC rows); lanes run down the column.
 constexpr int kColMaxKC = 4096;
 __global__ void __launch_bounds__(kThreads) colmax_kernel(const double* __restrict__ B, int64_t ldb, int64_t k,
-                                                          unsigned long long* __restrict__ colmax) {
+                                                          unsigned long long* __restrict__ colmax,
+                                                          unsigned long long* __restrict__ nonfinite) {
   int64_t j = blockIdx.x;
   int64_t l0 = (int64_t)blockIdx.y * kColMaxKC;
   const double* p = B + j * ldb;
@@ -75,6 +82,7 @@ __global__ void __launch_bounds__(kThreads) colmax_kernel(const double* __restri
 #pragma unroll
     for (int w = 1; w < kThreads / 64; ++w) mx = part[w] > mx ? part[w] : mx;
     if (mx) atomicMax(colmax + j, mx);
+    if (mx >= kInfBits) *nonfinite = 1ull;
   }
 }
 
@@ -386,18 +394,21 @@ struct Operand {
   int64_t nvec, nvec_pad, k, k_pad;
   unsigned long long* vmax;   // bit pattern of the largest magnitude per vector
   unsigned long long* vaux;   // per-vector integer norm bound, or largest element of the bound product
+  unsigned long long* flag;   // set to 1 when the operand holds an infinity or a NaN
+  int64_t fill;               // entries to clear from vmax on (A's count includes the flag word behind it)
   int* shifts;
   int8_t* planes;
 };
 
 void launch_max(const Operand& o, hipStream_t st) {
   const dim3 thr(kThreads);
-  hipLaunchKernelGGL(fill_u64_kernel, dim3(blocks_of(o.nvec_pad, kThreads)), thr, 0, st, o.vmax, o.nvec_pad);
+  hipLaunchKernelGGL(fill_u64_kernel, dim3(blocks_of(o.fill, kThreads)), thr, 0, st, o.vmax, o.fill);
   if (o.strided)
     hipLaunchKernelGGL(rowmax_kernel, dim3(blocks_of(o.nvec, kThreads), blocks_of(o.k, kRowMaxKC)), thr, 0, st, o.X, o.ld,
-                       o.nvec, o.k, o.vmax);
+                       o.nvec, o.k, o.vmax, o.flag);
   else
-    hipLaunchKernelGGL(colmax_kernel, dim3((unsigned)o.nvec, blocks_of(o.k, kColMaxKC)), thr, 0, st, o.X, o.ld, o.k, o.vmax);
+    hipLaunchKernelGGL(colmax_kernel, dim3((unsigned)o.nvec, blocks_of(o.k, kColMaxKC)), thr, 0, st, o.X, o.ld, o.k, o.vmax,
+                       o.flag);
 }
 
 void launch_norm(const Operand& o, hipStream_t st) {
@@ -441,13 +452,17 @@ hipError_t oz2_launch_stage1(int transa, int transb, int64_t m, int64_t n, int64
                              char* ws, hipStream_t st) {
   // rows of op(A): strided in a stored m x k matrix, contiguous in a stored k x m matrix;
   // columns of op(B): contiguous in a stored k x n matrix, strided in a stored n x k matrix
+  // The flag words sit directly behind A's row maxima, so the fill that clears those (the first launch of the
+  // call) clears the flag as well; B's pass only ever sets it.
+  if (lay.off_flags != lay.off_rowmax + (size_t)lay.m_pad * 8) return hipErrorInvalidValue;
+  unsigned long long* flag = reinterpret_cast<unsigned long long*>(ws + lay.off_flags);
   const Operand ops[2] = {
       {A, lda, transa == 0, m, lay.m_pad, k, lay.k_pad, reinterpret_cast<unsigned long long*>(ws + lay.off_rowmax),
-       reinterpret_cast<unsigned long long*>(ws + lay.off_rownorm), reinterpret_cast<int*>(ws + lay.off_sa),
-       reinterpret_cast<int8_t*>(ws + lay.off_a)},
+       reinterpret_cast<unsigned long long*>(ws + lay.off_rownorm), flag, lay.m_pad + 32,
+       reinterpret_cast<int*>(ws + lay.off_sa), reinterpret_cast<int8_t*>(ws + lay.off_a)},
       {B, ldb, transb != 0, n, lay.n_pad, k, lay.k_pad, reinterpret_cast<unsigned long long*>(ws + lay.off_colmax),
-       reinterpret_cast<unsigned long long*>(ws + lay.off_colnorm), reinterpret_cast<int*>(ws + lay.off_sb),
-       reinterpret_cast<int8_t*>(ws + lay.off_b)}};
+       reinterpret_cast<unsigned long long*>(ws + lay.off_colnorm), flag, lay.n_pad,
+       reinterpret_cast<int*>(ws + lay.off_sb), reinterpret_cast<int8_t*>(ws + lay.off_b)}};
   const dim3 thr(kThreads);
   Oz2ConvConsts conv = plan.conv;
   int xbits;  // |x'| < 2^xbits decides how deep the conversion kernels split an element

@@ -43,7 +43,11 @@ template <int L, bool U8>
 __global__ void __launch_bounds__(kThreads) crt_kernel(const void* __restrict__ cplanes, int64_t m_pad, int64_t n_pad,
                                                        const int* __restrict__ sa, const int* __restrict__ sb,
                                                        double* __restrict__ C, int64_t ldc, int64_t m, int64_t n,
-                                                       const double alpha, const double beta, const Oz2CrtConsts cc) {
+                                                       const double alpha, const double beta,
+                                                       const unsigned long long* __restrict__ skip_flag,
+                                                       const Oz2CrtConsts cc) {
+  // a non-finite input was found in stage 1: C is left to the FP64 fallback (uniform over the grid)
+  if (skip_flag != nullptr && *skip_flag != 0ull) return;
   typedef PlaneLoad<U8> PL;
   typedef typename PL::Raw Raw;
   constexpr int R = PL::R;
@@ -128,8 +132,10 @@ double host_crt(const Oz2CrtConsts& cc, const int32_t* cprod) {
 }  // namespace
 
 hipError_t oz2_launch_stage3(int64_t m, int64_t n, double alpha, double beta, double* C, int64_t ldc,
-                             const Oz2Plan& plan, const Oz2Layout& lay, char* ws, int residue_u8, hipStream_t st) {
+                             const Oz2Plan& plan, const Oz2Layout& lay, char* ws, int residue_u8, int check_flag,
+                             hipStream_t st) {
   const void* cplanes = ws + lay.off_c;
+  const unsigned long long* skip = check_flag ? reinterpret_cast<const unsigned long long*>(ws + lay.off_flags) : nullptr;
   const int* sa = reinterpret_cast<const int*>(ws + lay.off_sa);
   const int* sb = reinterpret_cast<const int*>(ws + lay.off_sb);
   const int64_t per_block = (int64_t)kThreads * (residue_u8 ? PlaneLoad<true>::R : PlaneLoad<false>::R);
@@ -139,10 +145,10 @@ hipError_t oz2_launch_stage3(int64_t m, int64_t n, double alpha, double beta, do
   case LL:                                                                                                        \
     if (residue_u8)                                                                                               \
       hipLaunchKernelGGL((crt_kernel<LL, true>), grid, dim3(kThreads), 0, st, cplanes, lay.m_pad, lay.n_pad, sa,  \
-                         sb, C, ldc, m, n, alpha, beta, plan.crt);                                                \
+                         sb, C, ldc, m, n, alpha, beta, skip, plan.crt);                                          \
     else                                                                                                          \
       hipLaunchKernelGGL((crt_kernel<LL, false>), grid, dim3(kThreads), 0, st, cplanes, lay.m_pad, lay.n_pad, sa, \
-                         sb, C, ldc, m, n, alpha, beta, plan.crt);                                                \
+                         sb, C, ldc, m, n, alpha, beta, skip, plan.crt);                                          \
     break;
     OZ2_CASE(1)
     OZ2_CASE(2)

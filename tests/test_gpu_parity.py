@@ -445,3 +445,87 @@ def test_inner_dimension_beyond_int32_exactness():
     check_against_oracle(A, B, N, fmt=1)
     # the exact products really exceed INT32 somewhere, so blocking was needed
     assert np.max(np.abs(ref.Cprod)) > 2**31
+
+
+# ------------------------------------------------------------------ exceptional inputs: detection and FP64 fallback
+def _flag(ws, m, n, k, N):
+    lay = oz.workspace_layout(m, n, k, N)
+    return int(ws.view(lay["flags"], 32, torch.int64).cpu().numpy()[0])
+
+
+@pytest.mark.parametrize("ta,tb", [("N", "N"), ("T", "N"), ("N", "T"), ("T", "T")])
+@pytest.mark.parametrize("where", ["A", "B"])
+@pytest.mark.parametrize("mode", [0, 1, 2])
+def test_nonfinite_inputs_fall_back_to_fp64(ta, tb, where, mode):
+    rng = np.random.default_rng(21)
+    m, n, k, N = 300, 200, 150, 12
+    opA = (rng.random((m, k)) - 0.5) * np.exp(rng.standard_normal((m, k)))
+    opB = (rng.random((k, n)) - 0.5) * np.exp(rng.standard_normal((k, n)))
+    X = opA if where == "A" else opB
+    X[7, 3] = np.inf
+    X[7, 9] = -np.inf
+    X[140, 100] = np.nan
+    X[m - 1 if where == "A" else k - 1, 0] = np.inf
+    opB[3, 5] = 0.0 if where == "A" else opB[3, 5]          # inf * 0
+    alpha, beta = -0.5, 2.0
+    As = np.asfortranarray(opA.T if ta == "T" else opA)
+    Bs = np.asfortranarray(opB.T if tb == "T" else opB)
+    C0 = np.asfortranarray(rng.standard_normal((m, n)))
+    dA, dB = _dev(As), _dev(Bs)
+    dC = torch.from_numpy(np.ascontiguousarray(C0.T)).cuda().t()
+    ws = oz.Workspace(m, n, k, N)
+    oz.oz2_set_shift_mode(mode)
+    try:
+        print("non-finite %s, op %s%s, shift mode %d" % (where, ta, tb, mode), flush=True)
+        oz.oz2_dgemm_ex(ta, tb, m, n, k, alpha, dA.data_ptr(), As.shape[0], dB.data_ptr(), Bs.shape[0], beta,
+                        dC.data_ptr(), m, N)
+        torch.cuda.synchronize()
+    finally:
+        oz.oz2_set_shift_mode(0)
+    assert _flag(ws, m, n, k, N) == 1
+    got = dC.cpu().numpy()
+    ref = orc.dgemm_ex(ta, tb, alpha, As, Bs, beta, C0, N)
+    # what is unique: where the NaNs and the infinities are, and the signs of the infinities
+    assert np.array_equal(np.isnan(got), np.isnan(ref))
+    inf = np.isinf(ref)
+    assert np.array_equal(np.isinf(got), inf) and np.array_equal(got[inf], ref[inf])
+    # the rest: two FP64 evaluations of the same sums in different orders
+    fin = np.isfinite(ref)
+    S = abs(alpha) * (np.abs(np.nan_to_num(opA, nan=0.0, posinf=0.0, neginf=0.0)) @
+                      np.abs(np.nan_to_num(opB, nan=0.0, posinf=0.0, neginf=0.0))) + abs(beta) * np.abs(C0)
+    assert np.all(np.abs(got[fin] - ref[fin]) <= 2 * (k + 2) * 2.0**-53 * S[fin])
+    assert fin.sum() > m * n // 2
+    # the same buffers with finite inputs again: the flag clears and the emulation is back
+    X[~np.isfinite(X)] = 1.0
+    As = np.asfortranarray(opA.T if ta == "T" else opA)
+    Bs = np.asfortranarray(opB.T if tb == "T" else opB)
+    dA, dB = _dev(As), _dev(Bs)
+    dC = torch.from_numpy(np.ascontiguousarray(C0.T)).cuda().t()
+    oz.oz2_dgemm_ex(ta, tb, m, n, k, alpha, dA.data_ptr(), As.shape[0], dB.data_ptr(), Bs.shape[0], beta, dC.data_ptr(), m, N)
+    torch.cuda.synchronize()
+    assert _flag(ws, m, n, k, N) == 0
+    assert np.array_equal(dC.cpu().numpy(), orc.dgemm_ex(ta, tb, alpha, As, Bs, beta, C0, N))
+    del ws
+
+
+def test_nonfinite_check_can_be_switched_off():
+    rng = np.random.default_rng(22)
+    m, n, k, N = 64, 64, 64, 10
+    A = rng.standard_normal((m, k))
+    B = rng.standard_normal((k, n))
+    A[1, 1] = np.nan
+    dA, dB = _dev(A), _dev(B)
+    dC = torch.full((n, m), 7.0, dtype=torch.float64, device="cuda").t()
+    ws = oz.Workspace(m, n, k, N)
+    oz.oz2_set_nonfinite_check(0)
+    try:
+        oz.oz2_dgemm(m, n, k, dA.data_ptr(), m, dB.data_ptr(), k, dC.data_ptr(), m, N)
+        torch.cuda.synchronize()
+    finally:
+        oz.oz2_set_nonfinite_check(1)
+    assert _flag(ws, m, n, k, N) == 1          # stage 1 still records what it saw
+    got = dC.cpu().numpy()
+    # rows of A without the NaN are untouched by it: the emulated values, not the 7.0 fill
+    ref = orc.dgemm(np.delete(A, 1, axis=0), B, N).C
+    assert np.array_equal(np.delete(got, 1, axis=0), ref)
+    del ws

@@ -59,6 +59,7 @@ def test_argument_validation_without_gpu():
     assert L.oz2_dgemm(0, 0, 0, None, 1, None, 1, None, 1, 4, None) == 0      # empty: nothing to do
     assert L.oz2_stage2_gemm(4, 4, 4, 4, None) == 1                          # no workspace registered
     assert L.oz2_set_shift_mode(3) == -1 and L.oz2_set_shift_mode(-1) == -1
+    assert L.oz2_set_nonfinite_check(2) == -1 and L.oz2_set_nonfinite_check(1) == 0
     # the INT8 product of 6-bit bounds must fit INT32: the inner dimension stays below 2^19 in that mode
     assert L.oz2_set_shift_mode(2) == 0
     try:
@@ -76,11 +77,12 @@ def test_workspace_layout_is_consistent():
         mp, npad, kp = lay["m_pad"], lay["n_pad"], lay["k_pad"]
         assert mp % 256 == 0 and npad % 256 == 0 and kp % 64 == 0
         assert mp >= m and npad >= n and kp >= k and mp - m < 256 and kp - k < 64
-        order = ["rowmax", "colmax", "sa", "sb", "a_planes", "b_planes", "c_planes"]
-        sizes = [8 * mp, 8 * npad, 4 * mp, 4 * npad, N * mp * kp, N * npad * kp, 4 * N * npad * mp]
+        order = ["rowmax", "flags", "colmax", "sa", "sb", "a_planes", "b_planes", "c_planes", "rownorm", "colnorm"]
+        sizes = [8 * mp, 256, 8 * npad, 4 * mp, 4 * npad, N * mp * kp, N * npad * kp, 4 * N * npad * mp, 8 * mp, 8 * npad]
         for a, b, sz in zip(order, order[1:], sizes):
             assert lay[a] % 256 == 0 and lay[a] + sz <= lay[b]
-        assert lay["c_planes"] + sizes[-1] <= oz.workspace_bytes(m, n, k, N)
+        assert lay["flags"] == lay["rowmax"] + 8 * mp      # cleared by the same fill as the row maxima
+        assert lay["colnorm"] + sizes[-1] <= oz.workspace_bytes(m, n, k, N)
     assert oz.workspace_bytes(16384, 16384, 16384, 16) < 25 * 2**30
 
 

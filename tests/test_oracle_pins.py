@@ -482,3 +482,44 @@ def test_blas_update_against_rationals():
     # transposes only change how the operands are read
     assert np.array_equal(orc.dgemm_ex("T", "N", 1.0, np.asfortranarray(A.T), B, 0.0, Cn, 12), P)
     assert np.array_equal(orc.dgemm_ex("N", "T", 1.0, A, np.asfortranarray(B.T), 0.0, Cn, 12), P)
+
+
+# ------------------------------------------------------------------ Section 3.1, closing remark: exceptional values
+def test_native_fallback_follows_ieee_rules_and_the_textbook_sum():
+    inf, nan = float("inf"), float("nan")
+    A, B = _tiny(91, 5, 4, 7, 0.5)
+    # finite inputs: within the classical bound k * 2^-53 * (|A||B|) of the exact product
+    P = orc.native_gemm(A, B)
+    for i in range(5):
+        for j in range(4):
+            ex = sum(Fraction(float(A[i, l])) * Fraction(float(B[l, j])) for l in range(7))
+            ab = sum(abs(Fraction(float(A[i, l])) * Fraction(float(B[l, j]))) for l in range(7))
+            assert abs(Fraction(float(P[i, j])) - ex) <= 7 * Fraction(2) ** -53 * ab
+    assert not orc.has_nonfinite(A) and not orc.has_nonfinite(B)
+    # special values, by the rules of IEEE 754 arithmetic
+    A2 = A.copy()
+    B2 = B.copy()
+    A2[0, 2] = inf              # row 0: inf * b_2j decides the sign unless b_2j == 0 (inf * 0 = NaN)
+    B2[2, 1] = 0.0
+    A2[1, 3] = nan              # row 1: NaN everywhere
+    A2[2, 0], A2[2, 1] = inf, inf   # row 2: inf * b_0j + inf * b_1j: NaN when the signs differ
+    B2[0, :] = [1.0, 1.0, -2.0, 3.0]
+    B2[1, :] = [1.0, -1.0, -5.0, 0.5]
+    assert orc.has_nonfinite(A2) and not orc.has_nonfinite(B2)
+    P2 = orc.native_gemm(A2, B2)
+    for j in range(4):
+        if B2[2, j] == 0.0:
+            assert math.isnan(P2[0, j])
+        else:
+            assert P2[0, j] == math.copysign(inf, B2[2, j])
+        assert math.isnan(P2[1, j])
+    assert P2[2, 0] == inf and math.isnan(P2[2, 1]) and P2[2, 2] == -inf and P2[2, 3] == inf
+    # rows without exceptional values are what the finite product gives
+    P_fin = orc.native_gemm(A, B2)
+    assert np.array_equal(P2[3:, :], P_fin[3:, :])
+    # the BLAS-form oracle switches to this product exactly when an input is not finite
+    C0 = np.zeros((5, 4), order="F")
+    assert np.array_equal(orc.dgemm_ex("N", "N", 1.0, A2, B2, 0.0, C0, 12), P2, equal_nan=True)
+    assert np.array_equal(orc.dgemm_ex("N", "N", 1.0, A, B, 0.0, C0, 12), orc.dgemm(A, B, 12).C)
+    At = np.asfortranarray(A2.T)
+    assert np.array_equal(orc.dgemm_ex("T", "N", 1.0, At, B2, 0.0, C0, 12), P2, equal_nan=True)
