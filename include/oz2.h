@@ -96,6 +96,18 @@ int oz2_dgemm(int64_t m, int64_t n, int64_t k, const double* A, int64_t lda, con
 int oz2_dgemm_ex(char transa, char transb, int64_t m, int64_t n, int64_t k, double alpha, const double* A, int64_t lda,
                  const double* B, int64_t ldb, double beta, double* C, int64_t ldc, int num_moduli, void* stream);
 
+/* Symmetric rank-k update in BLAS form (Section 2.3: for structured products the GEMM of part 2-b becomes the
+ * routine that fits, here the SYRK shape):
+ *   trans 'N':        C := alpha * A * A^T + beta * C,  A is n x k, lda >= max(1,n);
+ *   trans 'T' or 'C': C := alpha * A^T * A + beta * C,  A is k x n, lda >= max(1,k).
+ * C is n x n; only its uplo ('L' or 'U') triangle is read and written.  A is converted once and its residue
+ * planes serve as both operands; only the tiles of that triangle are multiplied, so stage 1 does half and
+ * stage 2 about half of the work of oz2_dgemm_ex on (A, A^T).  Every written element equals what oz2_dgemm_ex
+ * gives there (the product of the truncated integers is symmetric).  Workspace: oz2_workspace_bytes(n, n, k,
+ * num_moduli).  Argument codes are 1-based over this parameter list. */
+int oz2_dsyrk(char uplo, char trans, int64_t n, int64_t k, double alpha, const double* A, int64_t lda, double beta,
+              double* C, int64_t ldc, int num_moduli, void* stream);
+
 /* The three device stages of oz2_dgemm as separate calls (same kernels, same workspace); running them
  * in order is identical to oz2_dgemm.  They exist so that each stage can be tested and timed alone.
  *   oz2_stage1_convert : Algorithm 1 lines 1-5 (shifts, truncation, INT8 residues of A and B)

@@ -214,6 +214,19 @@ def dgemm_ex(transa, transb, alpha, A, B, beta, C, N, mode=0, check_nonfinite=Tr
     return out
 
 
+def dsyrk(uplo, trans, alpha, A, beta, C, N, mode=0, check_nonfinite=True):
+    """Symmetric rank-k update: the uplo triangle of C := alpha * op(A) op(A)^T + beta * C, every element of it as
+    dgemm_ex forms it from (A, A^T); the other triangle of C comes back unchanged."""
+    other = "T" if trans in "Nn" else "N"
+    full = dgemm_ex(trans, other, alpha, A, A, beta, C, N, mode=mode, check_nonfinite=check_nonfinite)
+    out = np.array(C, dtype=np.float64, order="F", copy=True)
+    n = out.shape[0]
+    ii, jj = np.meshgrid(np.arange(n), np.arange(n), indexing="ij")
+    tri = (ii >= jj) if uplo in "Ll" else (ii <= jj)
+    out[tri] = full[tri]
+    return out
+
+
 def exact(A, B, rows=None, cols=None):
     """binary128 reference: returns (C_ref, |A||B|) on the selected outputs, both rounded to double."""
     A = np.asfortranarray(A, dtype=np.float64)

@@ -194,7 +194,7 @@ int oz2_stage2_gemm(int64_t m, int64_t n, int64_t k, int num_moduli, void* strea
   Oz2Layout lay;
   int rc = prepare(s, m, n, k, num_moduli, &plan, &lay);
   if (rc) return rc;
-  hipError_t e = oz2_launch_stage2(*plan, lay, s.ws, s.kblock, s.product_format, static_cast<hipStream_t>(stream));
+  hipError_t e = oz2_launch_stage2(*plan, lay, s.ws, s.kblock, s.product_format, 0, static_cast<hipStream_t>(stream));
   return e == hipSuccess ? OZ2_OK : OZ2_ERR_HIP;
 }
 
@@ -208,14 +208,14 @@ int oz2_stage3_crt(int64_t m, int64_t n, int64_t k, double* C, int64_t ldc, int 
   if (m == 0 || n == 0) return OZ2_OK;
   if (!C) return -4;
   hipStream_t st = static_cast<hipStream_t>(stream);
-  if (k == 0) return oz2_launch_scale_c(m, n, 0.0, C, ldc, st) == hipSuccess ? OZ2_OK : OZ2_ERR_HIP;
+  if (k == 0) return oz2_launch_scale_c(m, n, 0.0, C, ldc, 0, st) == hipSuccess ? OZ2_OK : OZ2_ERR_HIP;
   State& s = state();
   std::lock_guard<std::mutex> lock(s.mu);
   const Oz2Plan* plan;
   Oz2Layout lay;
   int rc = prepare(s, m, n, k, num_moduli, &plan, &lay);
   if (rc) return rc;
-  hipError_t e = oz2_launch_stage3(m, n, 1.0, 0.0, C, ldc, *plan, lay, s.ws, s.product_format, 0, st);
+  hipError_t e = oz2_launch_stage3(m, n, 1.0, 0.0, C, ldc, *plan, lay, s.ws, s.product_format, 0, 0, st);
   return e == hipSuccess ? OZ2_OK : OZ2_ERR_HIP;
 }
 
@@ -248,7 +248,7 @@ int oz2_dgemm_ex(char transa, char transb, int64_t m, int64_t n, int64_t k, doub
   hipStream_t st = static_cast<hipStream_t>(stream);
   if (k == 0 || alpha == 0.0) {
     if (beta == 1.0) return OZ2_OK;
-    return oz2_launch_scale_c(m, n, beta, C, ldc, st) == hipSuccess ? OZ2_OK : OZ2_ERR_HIP;
+    return oz2_launch_scale_c(m, n, beta, C, ldc, 0, st) == hipSuccess ? OZ2_OK : OZ2_ERR_HIP;
   }
   if (!A) return -7;
   if (!B) return -9;
@@ -262,14 +262,60 @@ int oz2_dgemm_ex(char transa, char transb, int64_t m, int64_t n, int64_t k, doub
   if (!mark(0)) return OZ2_ERR_HIP;
   if (oz2_launch_stage1(ta, tb, m, n, k, A, lda, B, ldb, *plan, s.shift_mode, lay, s.ws, st) != hipSuccess || !mark(1))
     return OZ2_ERR_HIP;
-  if (oz2_launch_stage2(*plan, lay, s.ws, s.kblock, s.product_format, st) != hipSuccess || !mark(2)) return OZ2_ERR_HIP;
-  if (oz2_launch_stage3(m, n, alpha, beta, C, ldc, *plan, lay, s.ws, s.product_format, s.nonfinite_check, st) !=
+  if (oz2_launch_stage2(*plan, lay, s.ws, s.kblock, s.product_format, 0, st) != hipSuccess || !mark(2)) return OZ2_ERR_HIP;
+  if (oz2_launch_stage3(m, n, alpha, beta, C, ldc, *plan, lay, s.ws, s.product_format, s.nonfinite_check, 0, st) !=
           hipSuccess ||
       !mark(3))
     return OZ2_ERR_HIP;
   if (s.nonfinite_check &&
       oz2_launch_fallback(reinterpret_cast<const unsigned long long*>(s.ws + lay.off_flags), ta, tb, m, n, k, alpha, A, lda,
-                          B, ldb, beta, C, ldc, st) != hipSuccess)
+                          B, ldb, beta, C, ldc, 0, st) != hipSuccess)
+    return OZ2_ERR_HIP;
+  return OZ2_OK;
+}
+
+int oz2_dsyrk(char uplo, char trans, int64_t n, int64_t k, double alpha, const double* A, int64_t lda, double beta,
+              double* C, int64_t ldc, int num_moduli, void* stream) {
+  const int tri = (uplo == 'L' || uplo == 'l') ? 1 : (uplo == 'U' || uplo == 'u') ? 2 : 0;
+  const int ta = trans_code(trans);
+  if (tri == 0) return -1;
+  if (ta < 0) return -2;
+  if (n < 0) return -3;
+  if (k < 0) return -4;
+  if (!dims_ok(n, n, k)) return -3;
+  const int64_t rows_a = ta ? k : n;
+  if (lda < (rows_a > 1 ? rows_a : 1)) return -7;
+  if (ldc < (n > 1 ? n : 1)) return -10;
+  if (!n_ok(num_moduli)) return -11;
+  if (n == 0) return OZ2_OK;
+  if (!C) return -9;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  if (k == 0 || alpha == 0.0) {
+    if (beta == 1.0) return OZ2_OK;
+    return oz2_launch_scale_c(n, n, beta, C, ldc, tri, st) == hipSuccess ? OZ2_OK : OZ2_ERR_HIP;
+  }
+  if (!A) return -6;
+  State& s = state();
+  std::lock_guard<std::mutex> lock(s.mu);
+  const Oz2Plan* plan;
+  Oz2Layout lay;
+  int rc = prepare(s, n, n, k, num_moduli, &plan, &lay);
+  if (rc) return rc;
+  auto mark = [&](int i) { return !s.ev_on || hipEventRecord(s.ev[i], st) == hipSuccess; };
+  if (!mark(0)) return OZ2_ERR_HIP;
+  // op(A) op(A)^T: the columns of the second operand are the rows of the first, so A is converted once and
+  // its planes serve as both operands
+  if (oz2_launch_stage1(ta, 0, n, n, k, A, lda, nullptr, 0, *plan, s.shift_mode, lay, s.ws, st) != hipSuccess || !mark(1))
+    return OZ2_ERR_HIP;
+  if (oz2_launch_stage2(*plan, lay, s.ws, s.kblock, s.product_format, tri, st) != hipSuccess || !mark(2)) return OZ2_ERR_HIP;
+  if (oz2_launch_stage3(n, n, alpha, beta, C, ldc, *plan, lay, s.ws, s.product_format, s.nonfinite_check, tri, st) !=
+          hipSuccess ||
+      !mark(3))
+    return OZ2_ERR_HIP;
+  // fallback: op(B) = op(A)^T is A read with the other orientation
+  if (s.nonfinite_check &&
+      oz2_launch_fallback(reinterpret_cast<const unsigned long long*>(s.ws + lay.off_flags), ta, !ta, n, n, k, alpha, A, lda,
+                          A, lda, beta, C, ldc, tri, st) != hipSuccess)
     return OZ2_ERR_HIP;
   return OZ2_OK;
 }

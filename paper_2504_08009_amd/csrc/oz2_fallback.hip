@@ -18,8 +18,13 @@ __global__ void __launch_bounds__(kThreads) fp64_fallback_kernel(const unsigned 
                                                                  int transb, int64_t m, int64_t n, int64_t k, double alpha,
                                                                  const double* __restrict__ A, int64_t lda,
                                                                  const double* __restrict__ B, int64_t ldb, double beta,
-                                                                 double* __restrict__ C, int64_t ldc, int64_t tiles_m) {
+                                                                 double* __restrict__ C, int64_t ldc, int64_t tiles_m,
+                                                                 int triangle) {
   if (*flag == 0ull) return;
+  // symmetric update: tiles wholly outside the lower (1) / upper (2) triangle have nothing to write
+  if ((triangle == 1 && (int64_t)(blockIdx.x % tiles_m) < (int64_t)(blockIdx.x / tiles_m)) ||
+      (triangle == 2 && (int64_t)(blockIdx.x % tiles_m) > (int64_t)(blockIdx.x / tiles_m)))
+    return;
   __shared__ double As[FK][FT];
   __shared__ double Bs[FK][FT];
   const int64_t i0 = (int64_t)(blockIdx.x % tiles_m) * FT, j0 = (int64_t)(blockIdx.x / tiles_m) * FT;
@@ -65,7 +70,7 @@ __global__ void __launch_bounds__(kThreads) fp64_fallback_kernel(const unsigned 
 #pragma unroll
     for (int r = 0; r < 8; ++r) {
       const int64_t i = i0 + tx + 16 * r;
-      if (i >= m) continue;
+      if (i >= m || (triangle == 1 && i < j) || (triangle == 2 && i > j)) continue;
       double* dst = C + i + j * ldc;
       const double t = beta == 0.0 ? 0.0 : beta * *dst;  // C is not read when beta is zero
       *dst = fma(alpha, acc[r][c], t);
@@ -77,10 +82,10 @@ __global__ void __launch_bounds__(kThreads) fp64_fallback_kernel(const unsigned 
 
 hipError_t oz2_launch_fallback(const unsigned long long* flag, int transa, int transb, int64_t m, int64_t n, int64_t k,
                                double alpha, const double* A, int64_t lda, const double* B, int64_t ldb, double beta,
-                               double* C, int64_t ldc, hipStream_t st) {
+                               double* C, int64_t ldc, int triangle, hipStream_t st) {
   const int64_t tiles_m = (m + FT - 1) / FT, tiles_n = (n + FT - 1) / FT;
   if (tiles_m * tiles_n >= ((int64_t)1 << 31)) return hipErrorInvalidValue;
   hipLaunchKernelGGL(fp64_fallback_kernel, dim3((unsigned)(tiles_m * tiles_n)), dim3(kThreads), 0, st, flag, transa, transb, m,
-                     n, k, alpha, A, lda, B, ldb, beta, C, ldc, tiles_m);
+                     n, k, alpha, A, lda, B, ldb, beta, C, ldc, tiles_m, triangle);
   return hipGetLastError();
 }

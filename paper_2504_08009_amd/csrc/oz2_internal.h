@@ -66,20 +66,22 @@ void oz2_make_layout(int64_t m, int64_t n, int64_t k, int N, Oz2Layout* lay);
 hipError_t oz2_launch_stage1(int transa, int transb, int64_t m, int64_t n, int64_t k, const double* A, int64_t lda,
                              const double* B, int64_t ldb, const Oz2Plan& plan, int shift_mode, const Oz2Layout& lay,
                              char* ws, hipStream_t st);
+// triangle: 0 = general product; 1 / 2 = symmetric product op(A) op(A)^T (B's planes are A's), only the tiles of
+// the lower / upper triangle are computed
 hipError_t oz2_launch_stage2(const Oz2Plan& plan, const Oz2Layout& lay, char* ws, int64_t kblock, int residue_u8,
-                             hipStream_t st);
+                             int triangle, hipStream_t st);
 // P = A''B'' of the INT8-product shift mode: bound planes in the slots of residue plane 0 -> INT32 in the slot of
 // product plane 0.  Exact for k_pad * 64 * 64 < 2^31.
-hipError_t oz2_launch_bound_gemm(const Oz2Layout& lay, char* ws, hipStream_t st);
+hipError_t oz2_launch_bound_gemm(const Oz2Layout& lay, char* ws, bool symmetric, hipStream_t st);
 // check_flag != 0: do nothing when stage 1 found a non-finite input (the fallback forms C instead)
 hipError_t oz2_launch_stage3(int64_t m, int64_t n, double alpha, double beta, double* C, int64_t ldc,
                              const Oz2Plan& plan, const Oz2Layout& lay, char* ws, int residue_u8, int check_flag,
-                             hipStream_t st);
+                             int triangle, hipStream_t st);
 // C := alpha * op(A) * op(B) + beta * C in plain FP64, only if *flag != 0 (checked on the device)
 hipError_t oz2_launch_fallback(const unsigned long long* flag, int transa, int transb, int64_t m, int64_t n, int64_t k,
                                double alpha, const double* A, int64_t lda, const double* B, int64_t ldb, double beta,
-                               double* C, int64_t ldc, hipStream_t st);
-hipError_t oz2_launch_scale_c(int64_t m, int64_t n, double beta, double* C, int64_t ldc, hipStream_t st);
+                               double* C, int64_t ldc, int triangle, hipStream_t st);
+hipError_t oz2_launch_scale_c(int64_t m, int64_t n, double beta, double* C, int64_t ldc, int triangle, hipStream_t st);
 
 hipError_t oz2_launch_mfma_calibration(int workgroups, int iters, int random_operands, int* sink, long long* clocks,
                                        hipStream_t st);

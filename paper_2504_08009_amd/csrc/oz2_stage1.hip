@@ -447,6 +447,7 @@ void launch_convert(const Operand& o, int kind, const Oz2ConvConsts& conv, hipSt
 }  // namespace
 
 // transa / transb: 0 = the operand is stored as op(X) (column-major), 1 = it is stored transposed.
+// B == nullptr: the symmetric product op(A) op(A)^T (n == m); only A's vectors, shifts and planes are produced.
 hipError_t oz2_launch_stage1(int transa, int transb, int64_t m, int64_t n, int64_t k, const double* A, int64_t lda,
                              const double* B, int64_t ldb, const Oz2Plan& plan, int shift_mode, const Oz2Layout& lay,
                              char* ws, hipStream_t st) {
@@ -464,30 +465,36 @@ hipError_t oz2_launch_stage1(int transa, int transb, int64_t m, int64_t n, int64
        reinterpret_cast<unsigned long long*>(ws + lay.off_colnorm), flag, lay.n_pad,
        reinterpret_cast<int*>(ws + lay.off_sb), reinterpret_cast<int8_t*>(ws + lay.off_b)}};
   const dim3 thr(kThreads);
+  const int nops = B ? 2 : 1;
   Oz2ConvConsts conv = plan.conv;
   int xbits;  // |x'| < 2^xbits decides how deep the conversion kernels split an element
   if (shift_mode == OZ2_SHIFT_INT8_PRODUCT) {
     // bound planes (in the slots of residue plane 0), their INT8 product (in the slot of product plane 0),
-    // its row and column maxima, then the shifts
-    for (const Operand& o : ops) {
+    // its row and column maxima, then the shifts.  In the symmetric case the product is A''A''^T and its
+    // row maxima are its column maxima (those land in the unused column array).
+    for (int x = 0; x < nops; ++x) {
+      const Operand& o = ops[x];
       launch_max(o, st);
       hipLaunchKernelGGL(shifts_kernel, dim3(blocks_of(o.nvec_pad, kThreads)), thr, 0, st, o.vmax, o.shifts, o.nvec_pad, 6);
       launch_convert(o, 2, conv, st);
       hipLaunchKernelGGL(fill_u64_kernel, dim3(blocks_of(o.nvec_pad, kThreads)), thr, 0, st, o.vaux, o.nvec_pad);
     }
-    hipError_t e = oz2_launch_bound_gemm(lay, ws, st);
+    hipError_t e = oz2_launch_bound_gemm(lay, ws, B == nullptr, st);
     if (e != hipSuccess) return e;
     const int64_t row_blocks = lay.m_pad / kThreads;
     const int64_t nblk = row_blocks * (int64_t)blocks_of(n, kProdCols);
     if (nblk >= ((int64_t)1 << 31)) return hipErrorInvalidValue;
     hipLaunchKernelGGL(prodmax_kernel, dim3((unsigned)nblk), thr, 0, st, reinterpret_cast<const int*>(ws + lay.off_c),
                        lay.m_pad, m, n, row_blocks, ops[0].vaux, ops[1].vaux);
-    for (const Operand& o : ops)
+    for (int x = 0; x < nops; ++x) {
+      const Operand& o = ops[x];
       hipLaunchKernelGGL(shifts_prod_kernel, dim3(blocks_of(o.nvec_pad, kThreads)), thr, 0, st, o.vmax, o.vaux, o.shifts,
                          o.nvec_pad, plan.budget2);
+    }
     xbits = plan.budget2 / 2 + 7;  // |x'| < 2^(e + 1 + sa) <= 2^(floor(b/2) + 6)
   } else if (shift_mode == OZ2_SHIFT_CAUCHY_SCHWARZ) {
-    for (const Operand& o : ops) {
+    for (int x = 0; x < nops; ++x) {
+      const Operand& o = ops[x];
       launch_max(o, st);
       launch_norm(o, st);
       hipLaunchKernelGGL(shifts_cs_kernel, dim3(blocks_of(o.nvec_pad, kThreads)), thr, 0, st, o.vmax, o.vaux, o.shifts,
@@ -495,7 +502,8 @@ hipError_t oz2_launch_stage1(int transa, int transb, int64_t m, int64_t n, int64
     }
     xbits = plan.beta + 1;
   } else {
-    for (const Operand& o : ops) {
+    for (int x = 0; x < nops; ++x) {
+      const Operand& o = ops[x];
       launch_max(o, st);
       hipLaunchKernelGGL(shifts_kernel, dim3(blocks_of(o.nvec_pad, kThreads)), thr, 0, st, o.vmax, o.shifts, o.nvec_pad,
                          plan.kappa);
@@ -503,7 +511,7 @@ hipError_t oz2_launch_stage1(int transa, int transb, int64_t m, int64_t n, int64
     xbits = plan.kappa;
   }
   conv.two_level = xbits > 75;
-  for (const Operand& o : ops) launch_convert(o, conv.two_level ? 1 : 0, conv, st);
+  for (int x = 0; x < nops; ++x) launch_convert(ops[x], conv.two_level ? 1 : 0, conv, st);
   return hipGetLastError();
 }
 

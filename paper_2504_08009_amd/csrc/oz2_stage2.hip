@@ -61,6 +61,7 @@ struct GemmArgs {
   int superblock;          // 1: tiles_m and tiles_n are multiples of 16, use the super-block order
   int ktiles;              // k_pad / BK
   int ktiles_per_block;    // k-tiles between modular reductions of the accumulators
+  int triangle;            // 0: all tiles; 1: only tiles with tm >= tn (lower); 2: only tm <= tn (upper)
   float p[OZ2_MAX_N];
 };
 
@@ -127,6 +128,9 @@ __global__ void __launch_bounds__(kThreads) gemm_i8_kernel(const GemmArgs g) {
     tm = first_m + rr % gsize;
     tn = rr / gsize;
   }
+
+  // symmetric product: the other triangle of tiles is never needed
+  if ((g.triangle == 1 && tm < tn) || (g.triangle == 2 && tm > tn)) return;
 
   const int lane = threadIdx.x & 63;
   const int wv = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -329,13 +333,16 @@ hipError_t set_lds_attributes() {
 }
 
 // num_moduli planes of A' (off_a) times planes of B' (off_b) -> planes of C' (off_c)
+// b_is_a: the second operand's planes are the first operand's (symmetric product; m_pad == n_pad)
 hipError_t launch_gemm(const Oz2Layout& lay, char* ws, int num_moduli, const int* moduli, int64_t kblock, int residue_u8,
-                       hipStream_t st) {
+                       int triangle, bool b_is_a, hipStream_t st) {
   hipError_t e = set_lds_attributes();
   if (e != hipSuccess) return e;
   GemmArgs g;
   g.a = reinterpret_cast<const int8_t*>(ws + lay.off_a);
-  g.b = reinterpret_cast<const int8_t*>(ws + lay.off_b);
+  g.b = reinterpret_cast<const int8_t*>(ws + (b_is_a ? lay.off_a : lay.off_b));
+  if (b_is_a && lay.m_pad != lay.n_pad) return hipErrorInvalidValue;
+  g.triangle = triangle;
   g.c = reinterpret_cast<int*>(ws + lay.off_c);
   g.m_pad = lay.m_pad;
   g.n_pad = lay.n_pad;
@@ -361,13 +368,13 @@ hipError_t launch_gemm(const Oz2Layout& lay, char* ws, int num_moduli, const int
 }  // namespace
 
 hipError_t oz2_launch_stage2(const Oz2Plan& plan, const Oz2Layout& lay, char* ws, int64_t kblock, int residue_u8,
-                             hipStream_t st) {
-  return launch_gemm(lay, ws, plan.N, plan.moduli, kblock, residue_u8, st);
+                             int triangle, hipStream_t st) {
+  return launch_gemm(lay, ws, plan.N, plan.moduli, kblock, residue_u8, triangle, triangle != 0, st);
 }
 
 // One plain INT8 product with INT32 output and no modular reduction between k-blocks: the caller guarantees
 // k_pad * 64 * 64 < 2^31.
-hipError_t oz2_launch_bound_gemm(const Oz2Layout& lay, char* ws, hipStream_t st) {
+hipError_t oz2_launch_bound_gemm(const Oz2Layout& lay, char* ws, bool symmetric, hipStream_t st) {
   const int one = 1;
-  return launch_gemm(lay, ws, 1, &one, lay.k_pad, 0, st);
+  return launch_gemm(lay, ws, 1, &one, lay.k_pad, 0, 0, symmetric, st);
 }

@@ -45,7 +45,7 @@ __global__ void __launch_bounds__(kThreads) crt_kernel(const void* __restrict__ 
                                                        double* __restrict__ C, int64_t ldc, int64_t m, int64_t n,
                                                        const double alpha, const double beta,
                                                        const unsigned long long* __restrict__ skip_flag,
-                                                       const Oz2CrtConsts cc) {
+                                                       const int triangle, const Oz2CrtConsts cc) {
   // a non-finite input was found in stage 1: C is left to the FP64 fallback (uniform over the grid)
   if (skip_flag != nullptr && *skip_flag != 0ull) return;
   typedef PlaneLoad<U8> PL;
@@ -54,6 +54,8 @@ __global__ void __launch_bounds__(kThreads) crt_kernel(const void* __restrict__ 
   const int64_t j = blockIdx.x;
   const int64_t i0 = ((int64_t)blockIdx.y * kThreads + threadIdx.x) * R;
   if (i0 >= m) return;
+  // symmetric product: only the lower (1: i >= j) or upper (2: i <= j) triangle of C exists and is written
+  if ((triangle == 1 && i0 + R - 1 < j) || (triangle == 2 && i0 > j)) return;
   // element (i, j) of plane t sits at index (t*n_pad + j)*m_pad + i, in units of int32 or of bytes
   const size_t elem = (size_t)j * m_pad + i0;
   const Raw* src = reinterpret_cast<const Raw*>(static_cast<const char*>(cplanes) + elem * (U8 ? 1 : 4));
@@ -92,25 +94,29 @@ __global__ void __launch_bounds__(kThreads) crt_kernel(const void* __restrict__ 
     // beta is zero (BLAS convention)
 #pragma unroll
     for (int r = 0; r < R; ++r) {
-      const double tt = (beta == 0.0 || i0 + r >= m) ? 0.0 : beta * dst[r];
+      const bool mine = i0 + r < m && !(triangle == 1 && i0 + r < j) && !(triangle == 2 && i0 + r > j);
+      const double tt = (beta == 0.0 || !mine) ? 0.0 : beta * dst[r];
       out[r] = fma(alpha, out[r], tt);
     }
   }
   // all R results of the thread leave together: its 8 R contiguous bytes complete their cache lines at once
-  if (i0 + R <= m && ((reinterpret_cast<uintptr_t>(dst) & 15) == 0)) {
+  const bool whole = triangle == 0 || (triangle == 1 && i0 >= j) || (triangle == 2 && i0 + R - 1 <= j);
+  if (whole && i0 + R <= m && ((reinterpret_cast<uintptr_t>(dst) & 15) == 0)) {
 #pragma unroll
     for (int r = 0; r < R; r += 2) *reinterpret_cast<double2*>(dst + r) = make_double2(out[r], out[r + 1]);
   } else {
 #pragma unroll
     for (int r = 0; r < R; ++r)
-      if (i0 + r < m) dst[r] = out[r];
+      if (i0 + r < m && !(triangle == 1 && i0 + r < j) && !(triangle == 2 && i0 + r > j)) dst[r] = out[r];
   }
 }
 
 // C := beta * C (zero without reading C when beta is zero): the k == 0 and alpha == 0 cases
-__global__ void __launch_bounds__(kThreads) scale_c_kernel(double* __restrict__ C, int64_t ldc, int64_t m, double beta) {
+__global__ void __launch_bounds__(kThreads) scale_c_kernel(double* __restrict__ C, int64_t ldc, int64_t m, double beta,
+                                                           int triangle) {
   int64_t i = (int64_t)blockIdx.y * kThreads + threadIdx.x;
-  if (i < m) {
+  const int64_t j = blockIdx.x;
+  if (i < m && !(triangle == 1 && i < j) && !(triangle == 2 && i > j)) {
     double* p = C + i + (int64_t)blockIdx.x * ldc;
     *p = beta == 0.0 ? 0.0 : beta * *p;
   }
@@ -133,11 +139,11 @@ double host_crt(const Oz2CrtConsts& cc, const int32_t* cprod) {
 
 hipError_t oz2_launch_stage3(int64_t m, int64_t n, double alpha, double beta, double* C, int64_t ldc,
                              const Oz2Plan& plan, const Oz2Layout& lay, char* ws, int residue_u8, int check_flag,
-                             hipStream_t st) {
+                             int triangle, hipStream_t st) {
   const void* cplanes = ws + lay.off_c;
   const unsigned long long* skip = check_flag ? reinterpret_cast<const unsigned long long*>(ws + lay.off_flags) : nullptr;
   const int* sa = reinterpret_cast<const int*>(ws + lay.off_sa);
-  const int* sb = reinterpret_cast<const int*>(ws + lay.off_sb);
+  const int* sb = triangle ? sa : reinterpret_cast<const int*>(ws + lay.off_sb);  // symmetric: columns are A's rows
   const int64_t per_block = (int64_t)kThreads * (residue_u8 ? PlaneLoad<true>::R : PlaneLoad<false>::R);
   dim3 grid((unsigned)n, (unsigned)((m + per_block - 1) / per_block));
   switch (plan.crt.L) {
@@ -145,10 +151,10 @@ hipError_t oz2_launch_stage3(int64_t m, int64_t n, double alpha, double beta, do
   case LL:                                                                                                        \
     if (residue_u8)                                                                                               \
       hipLaunchKernelGGL((crt_kernel<LL, true>), grid, dim3(kThreads), 0, st, cplanes, lay.m_pad, lay.n_pad, sa,  \
-                         sb, C, ldc, m, n, alpha, beta, skip, plan.crt);                                          \
+                         sb, C, ldc, m, n, alpha, beta, skip, triangle, plan.crt);                                \
     else                                                                                                          \
       hipLaunchKernelGGL((crt_kernel<LL, false>), grid, dim3(kThreads), 0, st, cplanes, lay.m_pad, lay.n_pad, sa, \
-                         sb, C, ldc, m, n, alpha, beta, skip, plan.crt);                                          \
+                         sb, C, ldc, m, n, alpha, beta, skip, triangle, plan.crt);                                \
     break;
     OZ2_CASE(1)
     OZ2_CASE(2)
@@ -162,9 +168,9 @@ hipError_t oz2_launch_stage3(int64_t m, int64_t n, double alpha, double beta, do
   return hipGetLastError();
 }
 
-hipError_t oz2_launch_scale_c(int64_t m, int64_t n, double beta, double* C, int64_t ldc, hipStream_t st) {
+hipError_t oz2_launch_scale_c(int64_t m, int64_t n, double beta, double* C, int64_t ldc, int triangle, hipStream_t st) {
   dim3 grid((unsigned)n, (unsigned)((m + kThreads - 1) / kThreads));
-  hipLaunchKernelGGL(scale_c_kernel, grid, dim3(kThreads), 0, st, C, ldc, m, beta);
+  hipLaunchKernelGGL(scale_c_kernel, grid, dim3(kThreads), 0, st, C, ldc, m, beta, triangle);
   return hipGetLastError();
 }
 

@@ -529,3 +529,77 @@ def test_nonfinite_check_can_be_switched_off():
     ref = orc.dgemm(np.delete(A, 1, axis=0), B, N).C
     assert np.array_equal(np.delete(got, 1, axis=0), ref)
     del ws
+
+
+# ------------------------------------------------------------------ symmetric rank-k update
+@pytest.mark.parametrize("uplo", ["L", "U"])
+@pytest.mark.parametrize("trans", ["N", "T"])
+@pytest.mark.parametrize("mode,fmt", [(0, 1), (1, 1), (2, 1), (0, 0)])
+def test_dsyrk_matches_the_oracle_and_leaves_the_other_triangle(uplo, trans, mode, fmt):
+    rng = np.random.default_rng(31)
+    n, k, N = 600, 200, 13          # 3 x 3 tiles: six of them in the triangle
+    opA = (rng.random((n, k)) - 0.5) * np.exp(rng.standard_normal((n, k)))
+    opA[5, :] = 0.0
+    As = np.asfortranarray(opA.T if trans == "T" else opA)
+    alpha, beta = 1.5, -0.25
+    C0 = np.asfortranarray(rng.standard_normal((n, n)))
+    ii, jj = np.meshgrid(np.arange(n), np.arange(n), indexing="ij")
+    outside = (ii < jj) if uplo == "L" else (ii > jj)
+    C0[outside] = np.nan            # never read, never written
+    dA = _dev(As)
+    dC = torch.from_numpy(np.ascontiguousarray(C0.T)).cuda().t()
+    ws = oz.Workspace(n, n, k, N)
+    oz.oz2_set_shift_mode(mode)
+    oz.oz2_set_product_format(fmt)
+    try:
+        print("dsyrk uplo=%s trans=%s mode=%d fmt=%d" % (uplo, trans, mode, fmt), flush=True)
+        oz.oz2_dsyrk(uplo, trans, n, k, alpha, dA.data_ptr(), As.shape[0], beta, dC.data_ptr(), n, N)
+        torch.cuda.synchronize()
+    finally:
+        oz.oz2_set_shift_mode(0)
+        oz.oz2_set_product_format(1)
+    got = dC.cpu().numpy()
+    assert np.all(np.isnan(got[outside])) and not np.any(np.isnan(got[~outside]))
+    C0z = np.where(outside, 0.0, C0)
+    ref = orc.dsyrk(uplo, trans, alpha, As, beta, np.asfortranarray(C0z), N, mode=mode)
+    assert np.array_equal(got[~outside], ref[~outside])
+    del ws
+
+
+def test_dsyrk_degenerate_and_nonfinite():
+    rng = np.random.default_rng(32)
+    n, k, N = 70, 40, 9
+    A = np.asfortranarray(rng.standard_normal((n, k)))
+    C0 = np.asfortranarray(rng.standard_normal((n, n)))
+    low = np.tril(np.ones((n, n), dtype=bool))
+    ws = oz.Workspace(n, n, k, N)
+    dA = _dev(A)
+    # alpha == 0 and k == 0: only the triangle is scaled
+    for kk, alpha in ((k, 0.0), (0, 1.0)):
+        dC = torch.from_numpy(np.ascontiguousarray(C0.T)).cuda().t()
+        oz.oz2_dsyrk("L", "N", n, kk, alpha, dA.data_ptr(), n, 3.0, dC.data_ptr(), n, N)
+        torch.cuda.synchronize()
+        got = dC.cpu().numpy()
+        assert np.array_equal(got[low], 3.0 * C0[low]) and np.array_equal(got[~low], C0[~low])
+    # an infinity in A: FP64 fallback on the triangle only
+    A2 = A.copy()
+    A2[3, 4] = np.inf
+    dA2 = _dev(A2)
+    dC = torch.from_numpy(np.ascontiguousarray(C0.T)).cuda().t()
+    oz.oz2_dsyrk("L", "N", n, k, 1.0, dA2.data_ptr(), n, 0.0, dC.data_ptr(), n, N)
+    torch.cuda.synchronize()
+    got = dC.cpu().numpy()
+    ref = orc.dsyrk("L", "N", 1.0, A2, 0.0, C0, N)
+    assert np.array_equal(got[~low], C0[~low])
+    assert np.array_equal(np.isnan(got), np.isnan(ref)) and np.array_equal(np.isinf(got), np.isinf(ref))
+    fin = np.isfinite(ref) & low
+    S = np.abs(np.nan_to_num(A2, posinf=0.0)) @ np.abs(np.nan_to_num(A2, posinf=0.0)).T
+    assert np.all(np.abs(got[fin] - ref[fin]) <= 2 * (k + 2) * 2.0**-53 * S[fin])
+    # argument checks
+    L = oz.lib()
+    assert L.oz2_dsyrk(b"X", b"N", n, k, 1.0, dA.data_ptr(), n, 0.0, dC.data_ptr(), n, N, None) == -1
+    assert L.oz2_dsyrk(b"L", b"Q", n, k, 1.0, dA.data_ptr(), n, 0.0, dC.data_ptr(), n, N, None) == -2
+    assert L.oz2_dsyrk(b"L", b"N", n, k, 1.0, dA.data_ptr(), n - 1, 0.0, dC.data_ptr(), n, N, None) == -7
+    assert L.oz2_dsyrk(b"L", b"T", n, k, 1.0, dA.data_ptr(), k - 1, 0.0, dC.data_ptr(), n, N, None) == -7
+    assert L.oz2_dsyrk(b"L", b"N", n, k, 1.0, dA.data_ptr(), n, 0.0, dC.data_ptr(), n - 1, N, None) == -10
+    del ws

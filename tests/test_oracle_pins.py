@@ -523,3 +523,25 @@ def test_native_fallback_follows_ieee_rules_and_the_textbook_sum():
     assert np.array_equal(orc.dgemm_ex("N", "N", 1.0, A, B, 0.0, C0, 12), orc.dgemm(A, B, 12).C)
     At = np.asfortranarray(A2.T)
     assert np.array_equal(orc.dgemm_ex("T", "N", 1.0, At, B2, 0.0, C0, 12), P2, equal_nan=True)
+
+
+# ------------------------------------------------------------------ Section 2.3: structured products (SYRK shape)
+@pytest.mark.parametrize("mode", [0, 1, 2])
+def test_symmetric_product_is_exactly_symmetric_and_touches_one_triangle(mode):
+    # A' A'^T is a symmetric integer matrix and the shifts of its columns are those of its rows, so the
+    # emulated product of (A, A^T) is symmetric bit for bit; the update only writes the named triangle
+    A, _ = _tiny(33, 9, 2, 13, 1.0)
+    P = orc.dgemm(A, A.T, 12, mode=mode, want=("C", "shifts"))
+    assert np.array_equal(P.C, P.C.T) and np.array_equal(P.sa, P.sb)
+    C0 = np.asfortranarray(np.random.default_rng(3).standard_normal((9, 9)))
+    for uplo in "LU":
+        for trans, As in (("N", A), ("T", np.asfortranarray(A.T))):
+            got = orc.dsyrk(uplo, trans, 0.5, As, -2.0, C0, 12, mode=mode)
+            for i in range(9):
+                for j in range(9):
+                    inside = i >= j if uplo == "L" else i <= j
+                    if inside:
+                        t = float(Fraction(-2.0) * Fraction(float(C0[i, j])))
+                        assert got[i, j] == float(Fraction(0.5) * Fraction(float(P.C[i, j])) + Fraction(t))
+                    else:
+                        assert got[i, j] == C0[i, j]
