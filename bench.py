@@ -113,11 +113,13 @@ def main():
     roofline = {"bound": "mfma", "kernel": "gemm_i8_kernel", "achieved": round(gemm_tops, 2),
                 "peak": INT8_MFMA_PEAK_TOPS, "unit": "TOP/s", "frac": round(gemm_tops / INT8_MFMA_PEAK_TOPS, 4),
                 "traffic": None, "avg_launch_ms": round(gemm_ms, 4)}
-    if args.workload == "c4" and N == 16 and not args.mnk:
+    if args.workload == "c4" and N == 16 and not args.mnk and args.shift_mode == 0:
         # HBM-side bytes per launch from the rocprofv3 counter runs summarised in
-        # profiles/c4_oz2_dgemm_counters.md: FETCH_SIZE 54.186 GiB x 2.0 (copy-kernel scale) + WRITE_SIZE 19.125 GiB
-        roofline["traffic"] = round((54.186 * 2.0 + 19.125) * 2**30)
-        roofline["traffic_unit"] = "bytes per launch (L2 misses + write-backs; algorithmic minimum 24 GiB)"
+        # profiles/c4_oz2_dgemm_counters.md: FETCH_SIZE x 2.0 (copy-kernel scale) + WRITE_SIZE, in GiB, for the
+        # UINT8 and the INT32 product format
+        fetch_gib, write_gib, min_gib = (53.818, 7.000, 12) if fmt == oz.OZ2_PRODUCT_RESIDUE_U8 else (54.186, 19.125, 24)
+        roofline["traffic"] = round((fetch_gib * 2.0 + write_gib) * 2**30)
+        roofline["traffic_unit"] = "bytes per launch (L2 misses + write-backs; algorithmic minimum %d GiB)" % min_gib
     stages = {
         "stage1_convert_ms": round(float(avg[0]), 4),
         "stage2_gemm_ms": round(gemm_ms, 4),
@@ -215,6 +217,20 @@ def main():
                 "emulated_TFLOPS": round(2.0 * m * n * k / mode_t / 1e12, 2),
                 "max_componentwise_err_vs_exact": float(np.max(np.abs(g2 - Cx) / S)),
             }
+        del ws
+        # context: the symmetric rank-k update A A^T of the same A (half the conversion, about half the tiles);
+        # TFLOPS counted with the flops of the full product so that it compares with the lines above
+        ws = oz.Workspace(m, m, k, N, device=dev)
+        dC2 = torch.zeros((m, m), dtype=torch.float64, device=dev).t()
+        oz.oz2_dsyrk("L", "N", m, k, 1.0, dA.data_ptr(), m, 0.0, dC2.data_ptr(), m, N, stream)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(3):
+            oz.oz2_dsyrk("L", "N", m, k, 1.0, dA.data_ptr(), m, 0.0, dC2.data_ptr(), m, N, stream)
+        torch.cuda.synchronize()
+        syrk_t = (time.perf_counter() - t0) / 3
+        out["dsyrk_lower_%d_moduli" % N] = {"ms_per_call": round(syrk_t * 1e3, 3),
+                                            "TFLOPS_as_full_product": round(2.0 * m * m * k / syrk_t / 1e12, 2)}
         del dC2, ws
         ws = oz.Workspace(m, n, k, N, device=dev)
 
