@@ -86,21 +86,6 @@ __global__ void __launch_bounds__(kThreads) colmax_kernel(const double* __restri
   }
 }
 
-// shift = kappa - 1 - floor(log2 max); 0 for an all-zero vector
-__global__ void __launch_bounds__(kThreads) shifts_kernel(const unsigned long long* __restrict__ mx, int* __restrict__ s,
-                                                          int64_t count, int kappa) {
-  int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
-  if (i >= count) return;
-  unsigned long long b = mx[i];
-  int out = 0;
-  if (b) {
-    int be = (int)(b >> 52);
-    int e = be ? be - 1023 : (63 - __clzll((long long)b)) - 1074;
-    out = kappa - 1 - e;
-  }
-  s[i] = out;
-}
-
 // ---- Cauchy-Schwarz shift mode (Section 4.1): integer upper bound of the 2-norm.
 // With e = floor(log2 max |x|):  q_l = ceil(|x_l| 2^(19-e)) <= 2^20,  S = sum_l q_l^2  (exact in 64 bits for
 // fewer than 2^23 terms, and independent of the order of summation).
@@ -171,22 +156,45 @@ __global__ void __launch_bounds__(kThreads) colnorm_kernel(const double* __restr
   }
 }
 
-// sa = beta - (e - 19 + h) with h the smallest integer such that 4^h >= S; 0 for an all-zero vector
-__global__ void __launch_bounds__(kThreads) shifts_cs_kernel(const unsigned long long* __restrict__ mx,
-                                                             const unsigned long long* __restrict__ norm,
-                                                             int* __restrict__ s, int64_t count, int beta) {
+// Shifts of both operands in one launch (Algorithm 1 line 1).  Per vector, from the bit pattern b of its largest
+// magnitude (e = floor(log2) of it) and, in the modes of Section 4.1, a second quantity v:
+//   mode 0 (Section 3):       kappa - 1 - e                         (param = kappa)
+//   mode 1 (Cauchy-Schwarz):  beta - (e - 19 + h), h = min{h : 4^h >= v}, v = integer norm bound S >= 2^38  (param = beta)
+//   mode 2 (INT8 product):    floor((b2 - t)/2) - (e - 5), t = min{t : 2^t >= v}, v = largest element of the bound
+//                             product in the vector's row / column      (param = b2)
+// An all-zero vector gets shift 0.
+struct ShiftJob {
+  const unsigned long long* mx;
+  const unsigned long long* aux;
+  int* s;
+  int64_t count;
+};
+__global__ void __launch_bounds__(kThreads) shifts_kernel(const ShiftJob ja, const ShiftJob jb, int mode, int param) {
   int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
-  if (i >= count) return;
-  unsigned long long b = mx[i];
+  const bool first = i < ja.count;
+  const ShiftJob& j = first ? ja : jb;
+  if (!first) i -= ja.count;
+  if (i >= j.count) return;
+  const unsigned long long b = j.mx[i];
   int out = 0;
   if (b) {
     const int e = exponent_of_bits(b);
-    const unsigned long long S = norm[i];            // >= 2^38: the maximum alone contributes that much
-    const int bits = 64 - __clzll((long long)(S - 1));  // ceil(log2 S)
-    const int h = (bits + 1) >> 1;
-    out = beta - (e - 19 + h);
+    if (mode == 0) {
+      out = param - 1 - e;
+    } else if (mode == 1) {
+      const unsigned long long S = j.aux[i];
+      const int bits = 64 - __clzll((long long)(S - 1));  // ceil(log2 S)
+      out = param - (e - 19 + ((bits + 1) >> 1));
+    } else {
+      const unsigned long long R = j.aux[i];
+      if (R) {
+        const int t = R <= 1 ? 0 : 64 - __clzll((long long)(R - 1));
+        const int d = param - t;
+        out = (d >= 0 ? d / 2 : -((1 - d) / 2)) - (e - 5);
+      }
+    }
   }
-  s[i] = out;
+  j.s[i] = out;
 }
 
 __device__ __forceinline__ unsigned pack4(int r0, int r1, int r2, int r3) {
@@ -234,23 +242,6 @@ __global__ void __launch_bounds__(kThreads) prodmax_kernel(const int* __restrict
     }
   }
   if (rmax > 0) atomicMax(rowtop + i, (unsigned long long)rmax);
-}
-
-// sa = floor((b - t)/2) - (e - 5) with t the smallest integer such that 2^t >= top; 0 for an all-zero vector
-__global__ void __launch_bounds__(kThreads) shifts_prod_kernel(const unsigned long long* __restrict__ mx,
-                                                               const unsigned long long* __restrict__ top,
-                                                               int* __restrict__ s, int64_t count, int budget) {
-  int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
-  if (i >= count) return;
-  const unsigned long long b = mx[i], R = top[i];
-  int out = 0;
-  if (b && R) {
-    const int e = exponent_of_bits(b);
-    const int t = R <= 1 ? 0 : 64 - __clzll((long long)(R - 1));
-    const int d = budget - t;
-    out = (d >= 0 ? d / 2 : -((1 - d) / 2)) - (e - 5);
-  }
-  s[i] = out;
 }
 
 // Plane layout (shared with the GEMM kernel): blocks of 256 rows x 64 bytes of the inner dimension, each
@@ -395,14 +386,12 @@ struct Operand {
   unsigned long long* vmax;   // bit pattern of the largest magnitude per vector
   unsigned long long* vaux;   // per-vector integer norm bound, or largest element of the bound product
   unsigned long long* flag;   // set to 1 when the operand holds an infinity or a NaN
-  int64_t fill;               // entries to clear from vmax on (A's count includes the flag word behind it)
   int* shifts;
   int8_t* planes;
 };
 
 void launch_max(const Operand& o, hipStream_t st) {
   const dim3 thr(kThreads);
-  hipLaunchKernelGGL(fill_u64_kernel, dim3(blocks_of(o.fill, kThreads)), thr, 0, st, o.vmax, o.fill);
   if (o.strided)
     hipLaunchKernelGGL(rowmax_kernel, dim3(blocks_of(o.nvec, kThreads), blocks_of(o.k, kRowMaxKC)), thr, 0, st, o.X, o.ld,
                        o.nvec, o.k, o.vmax, o.flag);
@@ -413,7 +402,6 @@ void launch_max(const Operand& o, hipStream_t st) {
 
 void launch_norm(const Operand& o, hipStream_t st) {
   const dim3 thr(kThreads);
-  hipLaunchKernelGGL(fill_u64_kernel, dim3(blocks_of(o.nvec_pad, kThreads)), thr, 0, st, o.vaux, o.nvec_pad);
   if (o.strided)
     hipLaunchKernelGGL(rownorm_kernel, dim3(blocks_of(o.nvec, kThreads), blocks_of(o.k, kRowMaxKC)), thr, 0, st, o.X, o.ld,
                        o.nvec, o.k, o.vmax, o.vaux);
@@ -453,32 +441,42 @@ hipError_t oz2_launch_stage1(int transa, int transb, int64_t m, int64_t n, int64
                              char* ws, hipStream_t st) {
   // rows of op(A): strided in a stored m x k matrix, contiguous in a stored k x m matrix;
   // columns of op(B): contiguous in a stored k x n matrix, strided in a stored n x k matrix
-  // The flag words sit directly behind A's row maxima, so the fill that clears those (the first launch of the
-  // call) clears the flag as well; B's pass only ever sets it.
-  if (lay.off_flags != lay.off_rowmax + (size_t)lay.m_pad * 8) return hipErrorInvalidValue;
+  // Row maxima, flag words and column maxima are adjacent, and so are the two auxiliary vectors: one fill
+  // launch clears each group.
+  if (lay.off_flags != lay.off_rowmax + (size_t)lay.m_pad * 8 || lay.off_colmax != lay.off_flags + 256 ||
+      lay.off_colnorm != lay.off_rownorm + (size_t)lay.m_pad * 8)
+    return hipErrorInvalidValue;
   unsigned long long* flag = reinterpret_cast<unsigned long long*>(ws + lay.off_flags);
   const Operand ops[2] = {
       {A, lda, transa == 0, m, lay.m_pad, k, lay.k_pad, reinterpret_cast<unsigned long long*>(ws + lay.off_rowmax),
-       reinterpret_cast<unsigned long long*>(ws + lay.off_rownorm), flag, lay.m_pad + 32,
+       reinterpret_cast<unsigned long long*>(ws + lay.off_rownorm), flag,
        reinterpret_cast<int*>(ws + lay.off_sa), reinterpret_cast<int8_t*>(ws + lay.off_a)},
       {B, ldb, transb != 0, n, lay.n_pad, k, lay.k_pad, reinterpret_cast<unsigned long long*>(ws + lay.off_colmax),
-       reinterpret_cast<unsigned long long*>(ws + lay.off_colnorm), flag, lay.n_pad,
+       reinterpret_cast<unsigned long long*>(ws + lay.off_colnorm), flag,
        reinterpret_cast<int*>(ws + lay.off_sb), reinterpret_cast<int8_t*>(ws + lay.off_b)}};
   const dim3 thr(kThreads);
   const int nops = B ? 2 : 1;
+  const int64_t n_max = nops == 2 ? lay.m_pad + 32 + lay.n_pad : lay.m_pad + 32;
+  const int64_t n_aux = nops == 2 ? lay.m_pad + lay.n_pad : lay.m_pad;
+  auto fill = [&](unsigned long long* p, int64_t count) {
+    hipLaunchKernelGGL(fill_u64_kernel, dim3(blocks_of(count, kThreads)), thr, 0, st, p, count);
+  };
+  auto shifts = [&](int mode, int param) {
+    const ShiftJob ja = {ops[0].vmax, ops[0].vaux, ops[0].shifts, ops[0].nvec_pad};
+    const ShiftJob jb = {ops[1].vmax, ops[1].vaux, ops[1].shifts, nops == 2 ? ops[1].nvec_pad : 0};
+    hipLaunchKernelGGL(shifts_kernel, dim3(blocks_of(ja.count + jb.count, kThreads)), thr, 0, st, ja, jb, mode, param);
+  };
   Oz2ConvConsts conv = plan.conv;
   int xbits;  // |x'| < 2^xbits decides how deep the conversion kernels split an element
+  fill(ops[0].vmax, n_max);
+  for (int x = 0; x < nops; ++x) launch_max(ops[x], st);
   if (shift_mode == OZ2_SHIFT_INT8_PRODUCT) {
     // bound planes (in the slots of residue plane 0), their INT8 product (in the slot of product plane 0),
     // its row and column maxima, then the shifts.  In the symmetric case the product is A''A''^T and its
     // row maxima are its column maxima (those land in the unused column array).
-    for (int x = 0; x < nops; ++x) {
-      const Operand& o = ops[x];
-      launch_max(o, st);
-      hipLaunchKernelGGL(shifts_kernel, dim3(blocks_of(o.nvec_pad, kThreads)), thr, 0, st, o.vmax, o.shifts, o.nvec_pad, 6);
-      launch_convert(o, 2, conv, st);
-      hipLaunchKernelGGL(fill_u64_kernel, dim3(blocks_of(o.nvec_pad, kThreads)), thr, 0, st, o.vaux, o.nvec_pad);
-    }
+    shifts(0, 6);  // exponents 5 - e of the bounds
+    for (int x = 0; x < nops; ++x) launch_convert(ops[x], 2, conv, st);
+    fill(ops[0].vaux, n_aux);
     hipError_t e = oz2_launch_bound_gemm(lay, ws, B == nullptr, st);
     if (e != hipSuccess) return e;
     const int64_t row_blocks = lay.m_pad / kThreads;
@@ -486,28 +484,15 @@ hipError_t oz2_launch_stage1(int transa, int transb, int64_t m, int64_t n, int64
     if (nblk >= ((int64_t)1 << 31)) return hipErrorInvalidValue;
     hipLaunchKernelGGL(prodmax_kernel, dim3((unsigned)nblk), thr, 0, st, reinterpret_cast<const int*>(ws + lay.off_c),
                        lay.m_pad, m, n, row_blocks, ops[0].vaux, ops[1].vaux);
-    for (int x = 0; x < nops; ++x) {
-      const Operand& o = ops[x];
-      hipLaunchKernelGGL(shifts_prod_kernel, dim3(blocks_of(o.nvec_pad, kThreads)), thr, 0, st, o.vmax, o.vaux, o.shifts,
-                         o.nvec_pad, plan.budget2);
-    }
+    shifts(2, plan.budget2);
     xbits = plan.budget2 / 2 + 7;  // |x'| < 2^(e + 1 + sa) <= 2^(floor(b/2) + 6)
   } else if (shift_mode == OZ2_SHIFT_CAUCHY_SCHWARZ) {
-    for (int x = 0; x < nops; ++x) {
-      const Operand& o = ops[x];
-      launch_max(o, st);
-      launch_norm(o, st);
-      hipLaunchKernelGGL(shifts_cs_kernel, dim3(blocks_of(o.nvec_pad, kThreads)), thr, 0, st, o.vmax, o.vaux, o.shifts,
-                         o.nvec_pad, plan.beta);
-    }
+    fill(ops[0].vaux, n_aux);
+    for (int x = 0; x < nops; ++x) launch_norm(ops[x], st);
+    shifts(1, plan.beta);
     xbits = plan.beta + 1;
   } else {
-    for (int x = 0; x < nops; ++x) {
-      const Operand& o = ops[x];
-      launch_max(o, st);
-      hipLaunchKernelGGL(shifts_kernel, dim3(blocks_of(o.nvec_pad, kThreads)), thr, 0, st, o.vmax, o.shifts, o.nvec_pad,
-                         plan.kappa);
-    }
+    shifts(0, plan.kappa);
     xbits = plan.kappa;
   }
   conv.two_level = xbits > 75;
