@@ -35,6 +35,8 @@ def main():
                     help="0: shifts from maxima (Section 3, default); 1: Cauchy-Schwarz bound; 2: INT8-product bound (Section 4.1)")
     ap.add_argument("--product-format", type=int, default=-1,
                     help="0: INT32 product planes; 1: UINT8 residue planes (library default)")
+    ap.add_argument("--graph", action="store_true",
+                    help="time replays of one captured HIP graph of the call instead of eager calls (small sizes)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain device copy of A (known size) so that rocprofv3 byte counters can be scaled")
     args = ap.parse_args()
@@ -99,6 +101,19 @@ def main():
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
     oz.oz2_set_stage_events(None)
+    if args.graph:
+        # the stage times above come from the eager pass; the headline time from replays of one captured call
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=torch.cuda.Stream()):
+            oz.oz2_dgemm(m, n, k, dA.data_ptr(), m, dB.data_ptr(), k, dC.data_ptr(), m, N, torch.cuda.current_stream())
+        for _ in range(args.warmup):
+            graph.replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for s in range(args.steps):
+            graph.replay()
+        torch.cuda.synchronize()
+        wall = time.perf_counter() - t0
 
     stage_ms = np.array([[elapsed(e[i], e[i + 1]) for i in range(3)] for e in evs])
     avg = stage_ms.mean(axis=0)
@@ -135,7 +150,7 @@ def main():
         "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "int8", "data": "synthetic",
         "config": {"workload": "%s: m=%d n=%d k=%d phi=%g, %d moduli, seed %d" % (args.workload, m, n, k, phi, N, cfg["seed"]),
-                   "num_moduli": N, "entry_point": "oz2_dgemm", "shift_mode": args.shift_mode,
+                   "num_moduli": N, "entry_point": "oz2_dgemm" + (" (HIP graph replay)" if args.graph else ""), "shift_mode": args.shift_mode,
                    "product_format": "uint8 residues" if fmt == oz.OZ2_PRODUCT_RESIDUE_U8 else "int32", "host_input_generation_s": round(gen_s, 1)},
         "roofline": roofline, "stages": stages,
     }

@@ -603,3 +603,52 @@ def test_dsyrk_degenerate_and_nonfinite():
     assert L.oz2_dsyrk(b"L", b"T", n, k, 1.0, dA.data_ptr(), k - 1, 0.0, dC.data_ptr(), n, N, None) == -7
     assert L.oz2_dsyrk(b"L", b"N", n, k, 1.0, dA.data_ptr(), n, 0.0, dC.data_ptr(), n - 1, N, None) == -10
     del ws
+
+
+# ------------------------------------------------------------------ stream capture
+def test_hip_graph_replays_match_eager_calls():
+    # the whole call is kernel launches on the caller's stream (no allocation, no memset, no synchronisation),
+    # so it can be captured once and replayed; every replay is checked, with eager work and synchronisation
+    # in between, and with new input values in the captured buffers
+    m, n, k, N = 300, 260, 400, 14
+    rng = np.random.default_rng(41)
+    ws = oz.Workspace(m, n, k, N)
+    dA = torch.zeros((k, m), dtype=torch.float64, device="cuda").t()
+    dB = torch.zeros((n, k), dtype=torch.float64, device="cuda").t()
+    dC = torch.zeros((n, m), dtype=torch.float64, device="cuda").t()
+    dE = torch.zeros((n, m), dtype=torch.float64, device="cuda").t()
+
+    def load(seed):
+        r = np.random.default_rng(seed)
+        A = (r.random((m, k)) - 0.5) * np.exp(r.standard_normal((m, k)))
+        B = (r.random((k, n)) - 0.5) * np.exp(r.standard_normal((k, n)))
+        dA.copy_(_dev(A))
+        dB.copy_(_dev(B))
+        return A, B
+
+    load(0)
+    oz.oz2_dgemm(m, n, k, dA.data_ptr(), m, dB.data_ptr(), k, dE.data_ptr(), m, N)    # warm-up outside the capture
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    print("capturing oz2_dgemm", flush=True)
+    with torch.cuda.graph(graph, stream=side):
+        oz.oz2_dgemm(m, n, k, dA.data_ptr(), m, dB.data_ptr(), k, dC.data_ptr(), m, N, torch.cuda.current_stream())
+    for rep in range(4):
+        A, B = load(100 + rep)
+        if rep == 2:
+            A[5, 7] = np.nan            # the fallback decision is taken on the device: it replays too
+            dA.copy_(_dev(A))
+        oz.oz2_dgemm(m, n, k, dA.data_ptr(), m, dB.data_ptr(), k, dE.data_ptr(), m, N)    # eager
+        torch.cuda.synchronize()
+        dC.fill_(-1.0)
+        print("replay %d" % rep, flush=True)
+        graph.replay()
+        torch.cuda.synchronize()
+        got, eager = dC.cpu().numpy(), dE.cpu().numpy()
+        assert np.array_equal(got, eager, equal_nan=True)
+        if rep != 2:
+            assert np.array_equal(got, orc.dgemm(A, B, N).C)
+        else:
+            assert np.isnan(got[5, :]).all() and np.isfinite(np.delete(got, 5, axis=0)).all()
+    del graph, ws
