@@ -108,6 +108,18 @@ int oz2_dgemm_ex(char transa, char transb, int64_t m, int64_t n, int64_t k, doub
 int oz2_dsyrk(char uplo, char trans, int64_t n, int64_t k, double alpha, const double* A, int64_t lda, double beta,
               double* C, int64_t ldc, int num_moduli, void* stream);
 
+/* Triangular matrix product in BLAS form (Section 2.3, the TRMM shape), in place:
+ *   side 'L': B := alpha * op(A) * B,  A is m x m;   side 'R': B := alpha * B * op(A),  A is n x n;
+ * B is m x n (ldb >= max(1,m)), op(A) = A or A^T (transa), A is lower or upper triangular (uplo): only that
+ * triangle of the array is read, the rest counts as zero, and with diag 'U' the diagonal is not read and counts
+ * as one (diag 'N': it is read).  lda >= max(1, order of A).  The product is formed by Algorithm 1 on the
+ * triangular matrix so defined, exactly as oz2_dgemm_ex would on a full array holding those zeros; stage 1
+ * masks what is not stored and stage 2 skips the blocks of the inner dimension that are zero by structure
+ * (about half).  alpha == 0: B := 0, A is not read.  Workspace: oz2_workspace_bytes(m, n, order of A,
+ * num_moduli).  Argument codes are 1-based over this parameter list. */
+int oz2_dtrmm(char side, char uplo, char transa, char diag, int64_t m, int64_t n, double alpha, const double* A,
+              int64_t lda, double* B, int64_t ldb, int num_moduli, void* stream);
+
 /* The three device stages of oz2_dgemm as separate calls (same kernels, same workspace); running them
  * in order is identical to oz2_dgemm.  They exist so that each stage can be tested and timed alone.
  *   oz2_stage1_convert : Algorithm 1 lines 1-5 (shifts, truncation, INT8 residues of A and B)

@@ -227,6 +227,32 @@ def dsyrk(uplo, trans, alpha, A, beta, C, N, mode=0, check_nonfinite=True):
     return out
 
 
+def triangular(A, uplo, diag):
+    """The triangular matrix a BLAS routine sees in the array A: one triangle as stored, zeros elsewhere, ones
+    on the diagonal when it is declared unit.  What is not referenced may hold anything, NaNs included."""
+    A = np.asarray(A, dtype=np.float64)
+    n = A.shape[0]
+    ii, jj = np.meshgrid(np.arange(n), np.arange(n), indexing="ij")
+    keep = (ii >= jj) if uplo in "Ll" else (ii <= jj)
+    T = np.where(keep, A, 0.0)
+    if diag in "Uu":
+        T[np.arange(n), np.arange(n)] = 1.0
+    return np.asfortranarray(T)
+
+
+def dtrmm(side, uplo, transa, diag, alpha, A, B, N, mode=0, check_nonfinite=True):
+    """B := alpha * op(T) * B (side L) or alpha * B * op(T) (side R), T = triangular(A, uplo, diag), the product
+    formed by Algorithm 1 (or by the FP64 fallback) on the explicit triangular matrix.  Returns the new B."""
+    T = triangular(A, uplo, diag)
+    B = np.asfortranarray(B, dtype=np.float64)
+    zero = np.zeros(B.shape, order="F")
+    if alpha == 0.0:
+        return zero
+    if side in "Ll":
+        return dgemm_ex(transa, "N", alpha, T, B, 0.0, zero, N, mode=mode, check_nonfinite=check_nonfinite)
+    return dgemm_ex("N", transa, alpha, B, T, 0.0, zero, N, mode=mode, check_nonfinite=check_nonfinite)
+
+
 def exact(A, B, rows=None, cols=None):
     """binary128 reference: returns (C_ref, |A||B|) on the selected outputs, both rounded to double."""
     A = np.asfortranarray(A, dtype=np.float64)

@@ -8,7 +8,7 @@ _lib = None
 
 SYMBOLS = [
     "oz2_min_moduli", "oz2_max_moduli", "oz2_get_moduli", "oz2_workspace_bytes", "oz2_set_workspace",
-    "oz2_workspace_layout", "oz2_dgemm", "oz2_dgemm_ex", "oz2_dsyrk", "oz2_stage1_convert", "oz2_stage2_gemm", "oz2_stage3_crt",
+    "oz2_workspace_layout", "oz2_dgemm", "oz2_dgemm_ex", "oz2_dsyrk", "oz2_dtrmm", "oz2_stage1_convert", "oz2_stage2_gemm", "oz2_stage3_crt",
     "oz2_set_kblock", "oz2_set_shift_mode", "oz2_set_product_format", "oz2_set_nonfinite_check", "oz2_set_stage_events", "oz2_calibrate_mfma", "oz2_host_crt_element", "oz2_host_residues", "oz2_status_string",
 ]
 
@@ -35,6 +35,7 @@ def lib():
                                    ctypes.c_double, vp, i64, ci, vp]
         L.oz2_dsyrk.argtypes = [ctypes.c_char, ctypes.c_char, i64, i64, ctypes.c_double, vp, i64, ctypes.c_double, vp, i64,
                                 ci, vp]
+        L.oz2_dtrmm.argtypes = [ctypes.c_char] * 4 + [i64, i64, ctypes.c_double, vp, i64, vp, i64, ci, vp]
         L.oz2_stage1_convert.argtypes = [i64, i64, i64, vp, i64, vp, i64, ci, vp]
         L.oz2_stage2_gemm.argtypes = [i64, i64, i64, ci, vp]
         L.oz2_stage3_crt.argtypes = [i64, i64, i64, vp, i64, ci, vp]
@@ -143,6 +144,11 @@ def oz2_dgemm_ex(transa, transb, m, n, k, alpha, A_ptr, lda, B_ptr, ldb, beta, C
 def oz2_dsyrk(uplo, trans, n, k, alpha, A_ptr, lda, beta, C_ptr, ldc, num_moduli, stream=None):
     _check(lib().oz2_dsyrk(uplo.encode(), trans.encode(), n, k, float(alpha), A_ptr, lda, float(beta), C_ptr, ldc,
                            num_moduli, _stream_ptr(stream)), "oz2_dsyrk")
+
+
+def oz2_dtrmm(side, uplo, transa, diag, m, n, alpha, A_ptr, lda, B_ptr, ldb, num_moduli, stream=None):
+    _check(lib().oz2_dtrmm(side.encode(), uplo.encode(), transa.encode(), diag.encode(), m, n, float(alpha), A_ptr, lda,
+                           B_ptr, ldb, num_moduli, _stream_ptr(stream)), "oz2_dtrmm")
 
 
 def oz2_stage1_convert(m, n, k, A_ptr, lda, B_ptr, ldb, num_moduli, stream=None):

@@ -176,7 +176,7 @@ int oz2_stage1_convert(int64_t m, int64_t n, int64_t k, const double* A, int64_t
   Oz2Layout lay;
   int rc = prepare(s, m, n, k, num_moduli, &plan, &lay);
   if (rc) return rc;
-  hipError_t e = oz2_launch_stage1(0, 0, m, n, k, A, lda, B, ldb, *plan, s.shift_mode, lay, s.ws,
+  hipError_t e = oz2_launch_stage1(0, 0, m, n, k, A, lda, B, ldb, 0, 0, *plan, s.shift_mode, lay, s.ws,
                                    static_cast<hipStream_t>(stream));
   return e == hipSuccess ? OZ2_OK : OZ2_ERR_HIP;
 }
@@ -194,7 +194,7 @@ int oz2_stage2_gemm(int64_t m, int64_t n, int64_t k, int num_moduli, void* strea
   Oz2Layout lay;
   int rc = prepare(s, m, n, k, num_moduli, &plan, &lay);
   if (rc) return rc;
-  hipError_t e = oz2_launch_stage2(*plan, lay, s.ws, s.kblock, s.product_format, 0, static_cast<hipStream_t>(stream));
+  hipError_t e = oz2_launch_stage2(*plan, lay, s.ws, s.kblock, s.product_format, 0, OZ2_KRANGE_ALL, static_cast<hipStream_t>(stream));
   return e == hipSuccess ? OZ2_OK : OZ2_ERR_HIP;
 }
 
@@ -260,16 +260,17 @@ int oz2_dgemm_ex(char transa, char transb, int64_t m, int64_t n, int64_t k, doub
   if (rc) return rc;
   auto mark = [&](int i) { return !s.ev_on || hipEventRecord(s.ev[i], st) == hipSuccess; };
   if (!mark(0)) return OZ2_ERR_HIP;
-  if (oz2_launch_stage1(ta, tb, m, n, k, A, lda, B, ldb, *plan, s.shift_mode, lay, s.ws, st) != hipSuccess || !mark(1))
+  if (oz2_launch_stage1(ta, tb, m, n, k, A, lda, B, ldb, 0, 0, *plan, s.shift_mode, lay, s.ws, st) != hipSuccess || !mark(1))
     return OZ2_ERR_HIP;
-  if (oz2_launch_stage2(*plan, lay, s.ws, s.kblock, s.product_format, 0, st) != hipSuccess || !mark(2)) return OZ2_ERR_HIP;
+  if (oz2_launch_stage2(*plan, lay, s.ws, s.kblock, s.product_format, 0, OZ2_KRANGE_ALL, st) != hipSuccess || !mark(2))
+    return OZ2_ERR_HIP;
   if (oz2_launch_stage3(m, n, alpha, beta, C, ldc, *plan, lay, s.ws, s.product_format, s.nonfinite_check, 0, st) !=
           hipSuccess ||
       !mark(3))
     return OZ2_ERR_HIP;
   if (s.nonfinite_check &&
       oz2_launch_fallback(reinterpret_cast<const unsigned long long*>(s.ws + lay.off_flags), ta, tb, m, n, k, alpha, A, lda,
-                          B, ldb, beta, C, ldc, 0, st) != hipSuccess)
+                          B, ldb, beta, C, ldc, 0, 0, 0, st) != hipSuccess)
     return OZ2_ERR_HIP;
   return OZ2_OK;
 }
@@ -305,9 +306,11 @@ int oz2_dsyrk(char uplo, char trans, int64_t n, int64_t k, double alpha, const d
   if (!mark(0)) return OZ2_ERR_HIP;
   // op(A) op(A)^T: the columns of the second operand are the rows of the first, so A is converted once and
   // its planes serve as both operands
-  if (oz2_launch_stage1(ta, 0, n, n, k, A, lda, nullptr, 0, *plan, s.shift_mode, lay, s.ws, st) != hipSuccess || !mark(1))
+  if (oz2_launch_stage1(ta, 0, n, n, k, A, lda, nullptr, 0, 0, 0, *plan, s.shift_mode, lay, s.ws, st) != hipSuccess ||
+      !mark(1))
     return OZ2_ERR_HIP;
-  if (oz2_launch_stage2(*plan, lay, s.ws, s.kblock, s.product_format, tri, st) != hipSuccess || !mark(2)) return OZ2_ERR_HIP;
+  if (oz2_launch_stage2(*plan, lay, s.ws, s.kblock, s.product_format, tri, OZ2_KRANGE_ALL, st) != hipSuccess || !mark(2))
+    return OZ2_ERR_HIP;
   if (oz2_launch_stage3(n, n, alpha, beta, C, ldc, *plan, lay, s.ws, s.product_format, s.nonfinite_check, tri, st) !=
           hipSuccess ||
       !mark(3))
@@ -315,8 +318,70 @@ int oz2_dsyrk(char uplo, char trans, int64_t n, int64_t k, double alpha, const d
   // fallback: op(B) = op(A)^T is A read with the other orientation
   if (s.nonfinite_check &&
       oz2_launch_fallback(reinterpret_cast<const unsigned long long*>(s.ws + lay.off_flags), ta, !ta, n, n, k, alpha, A, lda,
-                          A, lda, beta, C, ldc, tri, st) != hipSuccess)
+                          A, lda, beta, C, ldc, tri, 0, 0, st) != hipSuccess)
     return OZ2_ERR_HIP;
+  return OZ2_OK;
+}
+
+int oz2_dtrmm(char side, char uplo, char transa, char diag, int64_t m, int64_t n, double alpha, const double* A,
+              int64_t lda, double* B, int64_t ldb, int num_moduli, void* stream) {
+  const int left = (side == 'L' || side == 'l') ? 1 : (side == 'R' || side == 'r') ? 0 : -1;
+  const int lower = (uplo == 'L' || uplo == 'l') ? 1 : (uplo == 'U' || uplo == 'u') ? 0 : -1;
+  const int ta = trans_code(transa);
+  const int unit = (diag == 'U' || diag == 'u') ? 1 : (diag == 'N' || diag == 'n') ? 0 : -1;
+  if (left < 0) return -1;
+  if (lower < 0) return -2;
+  if (ta < 0) return -3;
+  if (unit < 0) return -4;
+  if (m < 0) return -5;
+  if (n < 0) return -6;
+  const int64_t ka = left ? m : n;  // order of A = inner dimension of the product
+  if (!dims_ok(m, n, ka)) return -5;
+  if (lda < (ka > 1 ? ka : 1)) return -9;
+  if (ldb < (m > 1 ? m : 1)) return -11;
+  if (!n_ok(num_moduli)) return -12;
+  if (m == 0 || n == 0) return OZ2_OK;
+  if (!B) return -10;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  if (alpha == 0.0) return oz2_launch_scale_c(m, n, 0.0, B, ldb, 0, st) == hipSuccess ? OZ2_OK : OZ2_ERR_HIP;
+  if (!A) return -8;
+  State& s = state();
+  std::lock_guard<std::mutex> lock(s.mu);
+  const Oz2Plan* plan;
+  Oz2Layout lay;
+  int rc = prepare(s, m, n, ka, num_moduli, &plan, &lay);
+  if (rc) return rc;
+  const int tri = (lower ? 1 : 2) | (unit ? 4 : 0);    // structure of the stored A
+  const bool op_lower = (lower != 0) != (ta != 0);     // structure of op(A)
+  // the product X * Y with X = op(A), Y = B (left) or X = B, Y = op(A) (right)
+  const double* X = left ? A : B;
+  const double* Y = left ? B : A;
+  const int64_t ldx = left ? lda : ldb, ldy = left ? ldb : lda;
+  const int tx = left ? ta : 0, ty = left ? 0 : ta;
+  const int trix = left ? tri : 0, triy = left ? 0 : tri;
+  const int krange = left ? (op_lower ? OZ2_KRANGE_UPTO_ROW : OZ2_KRANGE_FROM_ROW)
+                          : (op_lower ? OZ2_KRANGE_FROM_COL : OZ2_KRANGE_UPTO_COL);
+  auto mark = [&](int i) { return !s.ev_on || hipEventRecord(s.ev[i], st) == hipSuccess; };
+  if (!mark(0)) return OZ2_ERR_HIP;
+  if (oz2_launch_stage1(tx, ty, m, n, ka, X, ldx, Y, ldy, trix, triy, *plan, s.shift_mode, lay, s.ws, st) != hipSuccess ||
+      !mark(1))
+    return OZ2_ERR_HIP;
+  if (oz2_launch_stage2(*plan, lay, s.ws, s.kblock, s.product_format, 0, krange, st) != hipSuccess || !mark(2))
+    return OZ2_ERR_HIP;
+  // B is overwritten: stage 1 has read all of it by now (stream order)
+  if (oz2_launch_stage3(m, n, alpha, 0.0, B, ldb, *plan, lay, s.ws, s.product_format, s.nonfinite_check, 0, st) !=
+          hipSuccess ||
+      !mark(3))
+    return OZ2_ERR_HIP;
+  if (s.nonfinite_check) {
+    // the FP64 fallback cannot work in place: it forms the product in the (then unused) product region of the
+    // workspace and a second conditional kernel copies it over B
+    const unsigned long long* flag = reinterpret_cast<const unsigned long long*>(s.ws + lay.off_flags);
+    double* tmp = reinterpret_cast<double*>(s.ws + lay.off_c);
+    if (oz2_launch_fallback(flag, tx, ty, m, n, ka, alpha, X, ldx, Y, ldy, 0.0, tmp, m, 0, trix, triy, st) != hipSuccess ||
+        oz2_launch_copy_if(flag, m, n, tmp, B, ldb, st) != hipSuccess)
+      return OZ2_ERR_HIP;
+  }
   return OZ2_OK;
 }
 

@@ -14,12 +14,29 @@ constexpr int kThreads = 256;
 constexpr int FT = 128;  // tile of C
 constexpr int FK = 8;    // inner-dimension step
 
+// element of a triangular operand: (r, c) = row and column in the stored array; tri & 3: 0 full, 1 lower,
+// 2 upper; tri & 4: unit diagonal; what is not stored counts as zero and is never propagated
+__device__ __forceinline__ double tri_value(double v, int64_t r, int64_t c, int tri) {
+  if (tri == 0) return v;
+  if (r == c) return (tri & 4) ? 1.0 : v;
+  const bool stored = (tri & 3) == 1 ? r > c : r < c;
+  return stored ? v : 0.0;
+}
+
+__global__ void __launch_bounds__(kThreads) copy_if_kernel(const unsigned long long* __restrict__ flag, int64_t m,
+                                                           const double* __restrict__ src, double* __restrict__ dst,
+                                                           int64_t ld) {
+  if (*flag == 0ull) return;
+  const int64_t i = (int64_t)blockIdx.y * kThreads + threadIdx.x, j = blockIdx.x;
+  if (i < m) dst[i + j * ld] = src[i + j * m];
+}
+
 __global__ void __launch_bounds__(kThreads) fp64_fallback_kernel(const unsigned long long* __restrict__ flag, int transa,
                                                                  int transb, int64_t m, int64_t n, int64_t k, double alpha,
                                                                  const double* __restrict__ A, int64_t lda,
                                                                  const double* __restrict__ B, int64_t ldb, double beta,
                                                                  double* __restrict__ C, int64_t ldc, int64_t tiles_m,
-                                                                 int triangle) {
+                                                                 int triangle, int tri_a, int tri_b) {
   if (*flag == 0ull) return;
   // symmetric update: tiles wholly outside the lower (1) / upper (2) triangle have nothing to write
   if ((triangle == 1 && (int64_t)(blockIdx.x % tiles_m) < (int64_t)(blockIdx.x / tiles_m)) ||
@@ -42,11 +59,14 @@ __global__ void __launch_bounds__(kThreads) fp64_fallback_kernel(const unsigned 
       int ii, ll;
       if (transa) { ll = e % FK; ii = e / FK; } else { ii = e % FT; ll = e / FT; }
       const int64_t i = i0 + ii, l = l0 + ll;
-      As[ll][ii] = (i < m && l < k) ? (transa ? A[l + i * lda] : A[i + l * lda]) : 0.0;
+      As[ll][ii] = (i < m && l < k) ? (transa ? tri_value(A[l + i * lda], l, i, tri_a) : tri_value(A[i + l * lda], i, l, tri_a))
+                                    : 0.0;
       int jj, lb;
       if (transb) { jj = e % FT; lb = e / FT; } else { lb = e % FK; jj = e / FK; }
       const int64_t j = j0 + jj, lq = l0 + lb;
-      Bs[lb][jj] = (j < n && lq < k) ? (transb ? B[j + lq * ldb] : B[lq + j * ldb]) : 0.0;
+      Bs[lb][jj] = (j < n && lq < k)
+                       ? (transb ? tri_value(B[j + lq * ldb], j, lq, tri_b) : tri_value(B[lq + j * ldb], lq, j, tri_b))
+                       : 0.0;
     }
     __syncthreads();
 #pragma unroll
@@ -82,10 +102,17 @@ __global__ void __launch_bounds__(kThreads) fp64_fallback_kernel(const unsigned 
 
 hipError_t oz2_launch_fallback(const unsigned long long* flag, int transa, int transb, int64_t m, int64_t n, int64_t k,
                                double alpha, const double* A, int64_t lda, const double* B, int64_t ldb, double beta,
-                               double* C, int64_t ldc, int triangle, hipStream_t st) {
+                               double* C, int64_t ldc, int triangle, int tri_a, int tri_b, hipStream_t st) {
   const int64_t tiles_m = (m + FT - 1) / FT, tiles_n = (n + FT - 1) / FT;
   if (tiles_m * tiles_n >= ((int64_t)1 << 31)) return hipErrorInvalidValue;
   hipLaunchKernelGGL(fp64_fallback_kernel, dim3((unsigned)(tiles_m * tiles_n)), dim3(kThreads), 0, st, flag, transa, transb, m,
-                     n, k, alpha, A, lda, B, ldb, beta, C, ldc, tiles_m, triangle);
+                     n, k, alpha, A, lda, B, ldb, beta, C, ldc, tiles_m, triangle, tri_a, tri_b);
+  return hipGetLastError();
+}
+
+hipError_t oz2_launch_copy_if(const unsigned long long* flag, int64_t m, int64_t n, const double* src, double* dst,
+                              int64_t ld, hipStream_t st) {
+  dim3 grid((unsigned)n, (unsigned)((m + kThreads - 1) / kThreads));
+  hipLaunchKernelGGL(copy_if_kernel, grid, dim3(kThreads), 0, st, flag, m, src, dst, ld);
   return hipGetLastError();
 }

@@ -64,12 +64,21 @@ void oz2_make_layout(int64_t m, int64_t n, int64_t k, int N, Oz2Layout* lay);
 
 // Kernel launchers.  Each returns hipSuccess or the launch error.
 hipError_t oz2_launch_stage1(int transa, int transb, int64_t m, int64_t n, int64_t k, const double* A, int64_t lda,
-                             const double* B, int64_t ldb, const Oz2Plan& plan, int shift_mode, const Oz2Layout& lay,
-                             char* ws, hipStream_t st);
+                             const double* B, int64_t ldb, int tri_a, int tri_b, const Oz2Plan& plan, int shift_mode,
+                             const Oz2Layout& lay, char* ws, hipStream_t st);
+// Inner-dimension range of a tile when one operand is triangular (TRMM shape), in units of diagonal blocks:
+//   UPTO_ROW / FROM_ROW: the first operand is lower / upper triangular (only l <= i / l >= i contribute);
+//   FROM_COL / UPTO_COL: the second operand is lower / upper triangular (only l >= j / l <= j contribute).
+#define OZ2_KRANGE_ALL 0
+#define OZ2_KRANGE_UPTO_ROW 1
+#define OZ2_KRANGE_FROM_ROW 2
+#define OZ2_KRANGE_FROM_COL 3
+#define OZ2_KRANGE_UPTO_COL 4
+
 // triangle: 0 = general product; 1 / 2 = symmetric product op(A) op(A)^T (B's planes are A's), only the tiles of
 // the lower / upper triangle are computed
 hipError_t oz2_launch_stage2(const Oz2Plan& plan, const Oz2Layout& lay, char* ws, int64_t kblock, int residue_u8,
-                             int triangle, hipStream_t st);
+                             int triangle, int krange, hipStream_t st);
 // P = A''B'' of the INT8-product shift mode: bound planes in the slots of residue plane 0 -> INT32 in the slot of
 // product plane 0.  Exact for k_pad * 64 * 64 < 2^31.
 hipError_t oz2_launch_bound_gemm(const Oz2Layout& lay, char* ws, bool symmetric, hipStream_t st);
@@ -78,9 +87,13 @@ hipError_t oz2_launch_stage3(int64_t m, int64_t n, double alpha, double beta, do
                              const Oz2Plan& plan, const Oz2Layout& lay, char* ws, int residue_u8, int check_flag,
                              int triangle, hipStream_t st);
 // C := alpha * op(A) * op(B) + beta * C in plain FP64, only if *flag != 0 (checked on the device)
+// tri_a / tri_b: triangular structure of the stored A / B (0 = full).  C must not overlap A or B.
 hipError_t oz2_launch_fallback(const unsigned long long* flag, int transa, int transb, int64_t m, int64_t n, int64_t k,
                                double alpha, const double* A, int64_t lda, const double* B, int64_t ldb, double beta,
-                               double* C, int64_t ldc, int triangle, hipStream_t st);
+                               double* C, int64_t ldc, int triangle, int tri_a, int tri_b, hipStream_t st);
+// dst(m x n, ld) := src(m x n, contiguous columns of length m), only if *flag != 0
+hipError_t oz2_launch_copy_if(const unsigned long long* flag, int64_t m, int64_t n, const double* src, double* dst,
+                              int64_t ld, hipStream_t st);
 hipError_t oz2_launch_scale_c(int64_t m, int64_t n, double beta, double* C, int64_t ldc, int triangle, hipStream_t st);
 
 hipError_t oz2_launch_mfma_calibration(int workgroups, int iters, int random_operands, int* sink, long long* clocks,

@@ -20,6 +20,16 @@ __global__ void __launch_bounds__(kThreads) fill_u64_kernel(unsigned long long* 
 // above it, every finite magnitude is below.
 constexpr unsigned long long kInfBits = 0x7ff0000000000000ull;
 
+// Triangular operands (TRMM shape): the array holds only one triangle; the rest is not referenced and counts
+// as zero, the diagonal as one when it is declared unit.  (r, c) = row and column of the element in the
+// stored array.  tri & 3: 0 = full matrix, 1 = lower (r >= c stored), 2 = upper (r <= c); tri & 4: unit diagonal.
+__device__ __forceinline__ double tri_value(double v, int64_t r, int64_t c, int tri) {
+  if (tri == 0) return v;
+  if (r == c) return (tri & 4) ? 1.0 : v;
+  const bool stored = (tri & 3) == 1 ? r > c : r < c;
+  return stored ? v : 0.0;
+}
+
 __device__ __forceinline__ unsigned long long abs_bits(double v) {
   return (unsigned long long)__double_as_longlong(v) & 0x7fffffffffffffffull;
 }
@@ -28,7 +38,7 @@ __device__ __forceinline__ unsigned long long abs_bits(double v) {
 constexpr int kRowMaxKC = 128;
 __global__ void __launch_bounds__(kThreads) rowmax_kernel(const double* __restrict__ A, int64_t lda, int64_t m,
                                                           int64_t k, unsigned long long* __restrict__ rowmax,
-                                                          unsigned long long* __restrict__ nonfinite) {
+                                                          unsigned long long* __restrict__ nonfinite, int tri) {
   int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
   if (i >= m) return;
   int64_t l0 = (int64_t)blockIdx.y * kRowMaxKC;
@@ -39,13 +49,13 @@ __global__ void __launch_bounds__(kThreads) rowmax_kernel(const double* __restri
   for (; l + 8 <= l1; l += 8) {
     unsigned long long v[8];
 #pragma unroll
-    for (int u = 0; u < 8; ++u) v[u] = abs_bits(p[(int64_t)u * lda]);
+    for (int u = 0; u < 8; ++u) v[u] = abs_bits(tri_value(p[(int64_t)u * lda], i, l + u, tri));
 #pragma unroll
     for (int u = 0; u < 8; ++u) mx = v[u] > mx ? v[u] : mx;
     p += 8 * lda;
   }
   for (; l < l1; ++l) {
-    unsigned long long v = abs_bits(*p);
+    unsigned long long v = abs_bits(tri_value(*p, i, l, tri));
     mx = v > mx ? v : mx;
     p += lda;
   }
@@ -57,7 +67,7 @@ __global__ void __launch_bounds__(kThreads) rowmax_kernel(const double* __restri
 constexpr int kColMaxKC = 4096;
 __global__ void __launch_bounds__(kThreads) colmax_kernel(const double* __restrict__ B, int64_t ldb, int64_t k,
                                                           unsigned long long* __restrict__ colmax,
-                                                          unsigned long long* __restrict__ nonfinite) {
+                                                          unsigned long long* __restrict__ nonfinite, int tri) {
   int64_t j = blockIdx.x;
   int64_t l0 = (int64_t)blockIdx.y * kColMaxKC;
   const double* p = B + j * ldb;
@@ -66,7 +76,7 @@ __global__ void __launch_bounds__(kThreads) colmax_kernel(const double* __restri
   for (int u = 0; u < kColMaxKC / kThreads; ++u) {
     int64_t l = l0 + (int64_t)u * kThreads + threadIdx.x;
     if (l < k) {
-      unsigned long long v = abs_bits(p[l]);
+      unsigned long long v = abs_bits(tri_value(p[l], l, j, tri));
       mx = v > mx ? v : mx;
     }
   }
@@ -102,7 +112,7 @@ __device__ __forceinline__ double scaled_ceil_sq(double v, int sc) {
 
 __global__ void __launch_bounds__(kThreads) rownorm_kernel(const double* __restrict__ A, int64_t lda, int64_t m,
                                                            int64_t k, const unsigned long long* __restrict__ rowmax,
-                                                           unsigned long long* __restrict__ rownorm) {
+                                                           unsigned long long* __restrict__ rownorm, int tri) {
   int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
   if (i >= m) return;
   const unsigned long long mb = rowmax[i];
@@ -116,13 +126,13 @@ __global__ void __launch_bounds__(kThreads) rownorm_kernel(const double* __restr
   for (; l + 8 <= l1; l += 8) {
     double v[8];
 #pragma unroll
-    for (int u = 0; u < 8; ++u) v[u] = p[(int64_t)u * lda];
+    for (int u = 0; u < 8; ++u) v[u] = tri_value(p[(int64_t)u * lda], i, l + u, tri);
 #pragma unroll
     for (int u = 0; u < 8; ++u) acc += scaled_ceil_sq(v[u], sc);
     p += 8 * lda;
   }
   for (; l < l1; ++l) {
-    acc += scaled_ceil_sq(*p, sc);
+    acc += scaled_ceil_sq(tri_value(*p, i, l, tri), sc);
     p += lda;
   }
   atomicAdd(rownorm + i, (unsigned long long)acc);
@@ -130,7 +140,7 @@ __global__ void __launch_bounds__(kThreads) rownorm_kernel(const double* __restr
 
 __global__ void __launch_bounds__(kThreads) colnorm_kernel(const double* __restrict__ B, int64_t ldb, int64_t k,
                                                            const unsigned long long* __restrict__ colmax,
-                                                           unsigned long long* __restrict__ colnorm) {
+                                                           unsigned long long* __restrict__ colnorm, int tri) {
   int64_t j = blockIdx.x;
   const unsigned long long mb = colmax[j];
   if (!mb) return;  // uniform over the block
@@ -141,7 +151,7 @@ __global__ void __launch_bounds__(kThreads) colnorm_kernel(const double* __restr
 #pragma unroll 4
   for (int u = 0; u < kColMaxKC / kThreads; ++u) {
     int64_t l = l0 + (int64_t)u * kThreads + threadIdx.x;
-    if (l < k) acc += scaled_ceil_sq(p[l], sc);
+    if (l < k) acc += scaled_ceil_sq(tri_value(p[l], l, j, tri), sc);
   }
   unsigned long long s = (unsigned long long)acc;
 #pragma unroll
@@ -263,7 +273,7 @@ template <int KIND>
 __global__ void __launch_bounds__(kThreads) convert_a_kernel(const double* __restrict__ A, int64_t lda, int64_t m,
                                                              int64_t k, int64_t m_pad, int64_t k_pad,
                                                              const int* __restrict__ sa, int8_t* __restrict__ planes,
-                                                             const Oz2ConvConsts cc) {
+                                                             const int tri, const Oz2ConvConsts cc) {
   __shared__ double tile[kConvARows * kConvAPitch];
   const int64_t r0 = (int64_t)blockIdx.x * kConvARows;  // < m_pad
   const int64_t kb = blockIdx.y;
@@ -275,7 +285,7 @@ __global__ void __launch_bounds__(kThreads) convert_a_kernel(const double* __res
     for (int c = 0; c < kBlkK / 4; ++c) {
       const int lc = c * 4 + wv;
       const int64_t l = kb * kBlkK + lc;
-      double v = (i < m && l < k) ? src[l * lda] : 0.0;
+      double v = (i < m && l < k) ? tri_value(src[l * lda], i, l, tri) : 0.0;
       tile[lane * kConvAPitch + lc] = v;
     }
   }
@@ -322,7 +332,7 @@ template <int KIND>
 __global__ void __launch_bounds__(kThreads) convert_b_kernel(const double* __restrict__ B, int64_t ldb, int64_t k,
                                                              int64_t n, int64_t n_pad, int64_t k_pad,
                                                              const int* __restrict__ sb, int8_t* __restrict__ planes,
-                                                             const Oz2ConvConsts cc) {
+                                                             const int tri, const Oz2ConvConsts cc) {
   __shared__ __attribute__((aligned(16))) double tile[kConvBCols * kConvBColPitch];
   const int64_t j0 = (int64_t)blockIdx.x * kConvBCols;  // < n_pad, multiple of 16
   const int64_t lbase = (int64_t)blockIdx.y * kConvBKC;
@@ -332,7 +342,7 @@ __global__ void __launch_bounds__(kThreads) convert_b_kernel(const double* __res
 #pragma unroll 4
     for (int c = 0; c < kConvBCols; ++c) {
       const int64_t j = j0 + c;
-      double v = (j < n && l < k) ? B[l + j * ldb] : 0.0;
+      double v = (j < n && l < k) ? tri_value(B[l + j * ldb], l, j, tri) : 0.0;
       tile[c * kConvBColPitch + slot] = v;
     }
   }
@@ -386,6 +396,7 @@ struct Operand {
   unsigned long long* vmax;   // bit pattern of the largest magnitude per vector
   unsigned long long* vaux;   // per-vector integer norm bound, or largest element of the bound product
   unsigned long long* flag;   // set to 1 when the operand holds an infinity or a NaN
+  int tri;                    // triangular structure of the stored array (see tri_value), 0 for a full matrix
   int* shifts;
   int8_t* planes;
 };
@@ -394,20 +405,20 @@ void launch_max(const Operand& o, hipStream_t st) {
   const dim3 thr(kThreads);
   if (o.strided)
     hipLaunchKernelGGL(rowmax_kernel, dim3(blocks_of(o.nvec, kThreads), blocks_of(o.k, kRowMaxKC)), thr, 0, st, o.X, o.ld,
-                       o.nvec, o.k, o.vmax, o.flag);
+                       o.nvec, o.k, o.vmax, o.flag, o.tri);
   else
     hipLaunchKernelGGL(colmax_kernel, dim3((unsigned)o.nvec, blocks_of(o.k, kColMaxKC)), thr, 0, st, o.X, o.ld, o.k, o.vmax,
-                       o.flag);
+                       o.flag, o.tri);
 }
 
 void launch_norm(const Operand& o, hipStream_t st) {
   const dim3 thr(kThreads);
   if (o.strided)
     hipLaunchKernelGGL(rownorm_kernel, dim3(blocks_of(o.nvec, kThreads), blocks_of(o.k, kRowMaxKC)), thr, 0, st, o.X, o.ld,
-                       o.nvec, o.k, o.vmax, o.vaux);
+                       o.nvec, o.k, o.vmax, o.vaux, o.tri);
   else
     hipLaunchKernelGGL(colnorm_kernel, dim3((unsigned)o.nvec, blocks_of(o.k, kColMaxKC)), thr, 0, st, o.X, o.ld, o.k, o.vmax,
-                       o.vaux);
+                       o.vaux, o.tri);
 }
 
 // kind 0 / 1: residue planes with the one- / two-level split; kind 2: the bound plane
@@ -418,10 +429,10 @@ void launch_convert(const Operand& o, int kind, const Oz2ConvConsts& conv, hipSt
 #define OZ2_CONV(KIND)                                                                                              \
   if (o.strided)                                                                                                    \
     hipLaunchKernelGGL(convert_a_kernel<KIND>, ga, thr, 0, st, o.X, o.ld, o.nvec, o.k, o.nvec_pad, o.k_pad, o.shifts, \
-                       o.planes, conv);                                                                             \
+                       o.planes, o.tri, conv);                                                                      \
   else                                                                                                              \
     hipLaunchKernelGGL(convert_b_kernel<KIND>, gb, thr, 0, st, o.X, o.ld, o.k, o.nvec, o.nvec_pad, o.k_pad, o.shifts, \
-                       o.planes, conv);
+                       o.planes, o.tri, conv);
   if (kind == 0) {
     OZ2_CONV(0)
   } else if (kind == 1) {
@@ -436,9 +447,10 @@ void launch_convert(const Operand& o, int kind, const Oz2ConvConsts& conv, hipSt
 
 // transa / transb: 0 = the operand is stored as op(X) (column-major), 1 = it is stored transposed.
 // B == nullptr: the symmetric product op(A) op(A)^T (n == m); only A's vectors, shifts and planes are produced.
+// tri_a / tri_b: triangular structure of the stored arrays (0 = full; see tri_value).
 hipError_t oz2_launch_stage1(int transa, int transb, int64_t m, int64_t n, int64_t k, const double* A, int64_t lda,
-                             const double* B, int64_t ldb, const Oz2Plan& plan, int shift_mode, const Oz2Layout& lay,
-                             char* ws, hipStream_t st) {
+                             const double* B, int64_t ldb, int tri_a, int tri_b, const Oz2Plan& plan, int shift_mode,
+                             const Oz2Layout& lay, char* ws, hipStream_t st) {
   // rows of op(A): strided in a stored m x k matrix, contiguous in a stored k x m matrix;
   // columns of op(B): contiguous in a stored k x n matrix, strided in a stored n x k matrix
   // Row maxima, flag words and column maxima are adjacent, and so are the two auxiliary vectors: one fill
@@ -449,10 +461,10 @@ hipError_t oz2_launch_stage1(int transa, int transb, int64_t m, int64_t n, int64
   unsigned long long* flag = reinterpret_cast<unsigned long long*>(ws + lay.off_flags);
   const Operand ops[2] = {
       {A, lda, transa == 0, m, lay.m_pad, k, lay.k_pad, reinterpret_cast<unsigned long long*>(ws + lay.off_rowmax),
-       reinterpret_cast<unsigned long long*>(ws + lay.off_rownorm), flag,
+       reinterpret_cast<unsigned long long*>(ws + lay.off_rownorm), flag, tri_a,
        reinterpret_cast<int*>(ws + lay.off_sa), reinterpret_cast<int8_t*>(ws + lay.off_a)},
       {B, ldb, transb != 0, n, lay.n_pad, k, lay.k_pad, reinterpret_cast<unsigned long long*>(ws + lay.off_colmax),
-       reinterpret_cast<unsigned long long*>(ws + lay.off_colnorm), flag,
+       reinterpret_cast<unsigned long long*>(ws + lay.off_colnorm), flag, tri_b,
        reinterpret_cast<int*>(ws + lay.off_sb), reinterpret_cast<int8_t*>(ws + lay.off_b)}};
   const dim3 thr(kThreads);
   const int nops = B ? 2 : 1;

@@ -62,6 +62,7 @@ struct GemmArgs {
   int ktiles;              // k_pad / BK
   int ktiles_per_block;    // k-tiles between modular reductions of the accumulators
   int triangle;            // 0: all tiles; 1: only tiles with tm >= tn (lower); 2: only tm <= tn (upper)
+  int krange;              // triangular operand: which k-tiles of a tile can be nonzero (see OZ2_KRANGE_*)
   float p[OZ2_MAX_N];
 };
 
@@ -138,9 +139,20 @@ __global__ void __launch_bounds__(kThreads) gemm_i8_kernel(const GemmArgs g) {
 
   // ---- global -> LDS copy: wave wv fills rows [64 wv, 64 wv + 64) of both tiles, 16 rows (1 KiB) per
   // load.  Lane l covers row (l >> 2) of the group and the chunk that the swizzle puts at position (l & 3).
+  // Triangular operand (TRMM shape): op(A)(i, l) vanishes for l > i (lower) or l < i (upper), so the tile only
+  // needs the k-tiles up to / from its diagonal block; which index (tm or tn) counts depends on the side.
+  int kt_begin = 0, kt_end = g.ktiles;
+  {
+    const int per = BM / BK;  // k-tiles per diagonal block
+    if (g.krange == OZ2_KRANGE_UPTO_ROW) kt_end = min(g.ktiles, (tm + 1) * per);
+    if (g.krange == OZ2_KRANGE_FROM_ROW) kt_begin = min(g.ktiles, tm * per);
+    if (g.krange == OZ2_KRANGE_UPTO_COL) kt_end = min(g.ktiles, (tn + 1) * per);
+    if (g.krange == OZ2_KRANGE_FROM_COL) kt_begin = min(g.ktiles, tn * per);
+  }
+  const int ktiles = kt_end - kt_begin;  // may be 0: the tile is then all zeros
   const size_t kp = (size_t)g.k_pad;
-  const int8_t* a_wave = g.a + ((size_t)t * g.m_pad + (size_t)tm * BM) * kp + wv * 64 * BK;
-  const int8_t* b_wave = g.b + ((size_t)t * g.n_pad + (size_t)tn * BN) * kp + wv * 64 * BK;
+  const int8_t* a_wave = g.a + ((size_t)t * g.m_pad + (size_t)tm * BM) * kp + wv * 64 * BK + (size_t)kt_begin * (BM * BK);
+  const int8_t* b_wave = g.b + ((size_t)t * g.n_pad + (size_t)tn * BN) * kp + wv * 64 * BK + (size_t)kt_begin * (BN * BK);
   const unsigned voff = (unsigned)((lane >> 2) * BK) + (((lane & 3) ^ (lane >> 4)) << 4);
   const unsigned lds_base = (unsigned)(size_t)(__attribute__((address_space(3))) char*)lds;
   const unsigned lds_wave = __builtin_amdgcn_readfirstlane(lds_base + wv * (64 * BK));
@@ -190,11 +202,11 @@ __global__ void __launch_bounds__(kThreads) gemm_i8_kernel(const GemmArgs g) {
   // ---- prologue: k-tiles 0 .. NS-2 in flight, tile 0 visible, its first fragments in registers
 #pragma unroll
   for (int pth = 0; pth < NS - 1; ++pth)
-    if (pth < g.ktiles) {
+    if (pth < ktiles) {
 #pragma unroll
       for (int q = 0; q < kLoads; ++q) gl(pth, pth, q);
     }
-  if (g.ktiles >= NS - 1)
+  if (ktiles >= NS - 1)
     wait_vmcnt<(NS - 2) * kLoads>();
   else
     wait_vmcnt<0>();
@@ -219,7 +231,7 @@ __global__ void __launch_bounds__(kThreads) gemm_i8_kernel(const GemmArgs g) {
     }
     // k-tile kt+1 must be complete in LDS for every wave before anyone reads it; passing this barrier
     // also means every wave has finished reading k-tile kt-1, whose stage is refilled below
-    if (more || kt + 2 < g.ktiles)
+    if (more || kt + 2 < ktiles)
       wait_vmcnt<(NS - 3) * kLoads>();
     else
       wait_vmcnt<0>();
@@ -237,13 +249,13 @@ __global__ void __launch_bounds__(kThreads) gemm_i8_kernel(const GemmArgs g) {
 
   const int p_int = (int)g.p[t];
   const float inv_pf = 1.0f / g.p[t];
-  const int last_full = g.ktiles - (NS - 1);  // k-tiles below this index still have a tile to prefetch
-  for (int kt0 = 0; kt0 < g.ktiles; kt0 += g.ktiles_per_block) {
-    const int kt1 = kt0 + g.ktiles_per_block < g.ktiles ? kt0 + g.ktiles_per_block : g.ktiles;
+  const int last_full = ktiles - (NS - 1);  // k-tiles below this index still have a tile to prefetch
+  for (int kt0 = 0; kt0 < ktiles; kt0 += g.ktiles_per_block) {
+    const int kt1 = kt0 + g.ktiles_per_block < ktiles ? kt0 + g.ktiles_per_block : ktiles;
     int kt = kt0;
     for (; kt < kt1 && kt < last_full; ++kt) body(kt, std::true_type{});
     for (; kt < kt1; ++kt) body(kt, std::false_type{});
-    if (kt1 < g.ktiles) {  // between k-blocks: bring the accumulators back near zero
+    if (kt1 < ktiles) {  // between k-blocks: bring the accumulators back near zero
 #pragma unroll
       for (int x = 0; x < 4; ++x)
 #pragma unroll
@@ -335,7 +347,7 @@ hipError_t set_lds_attributes() {
 // num_moduli planes of A' (off_a) times planes of B' (off_b) -> planes of C' (off_c)
 // b_is_a: the second operand's planes are the first operand's (symmetric product; m_pad == n_pad)
 hipError_t launch_gemm(const Oz2Layout& lay, char* ws, int num_moduli, const int* moduli, int64_t kblock, int residue_u8,
-                       int triangle, bool b_is_a, hipStream_t st) {
+                       int triangle, int krange, bool b_is_a, hipStream_t st) {
   hipError_t e = set_lds_attributes();
   if (e != hipSuccess) return e;
   GemmArgs g;
@@ -343,6 +355,7 @@ hipError_t launch_gemm(const Oz2Layout& lay, char* ws, int num_moduli, const int
   g.b = reinterpret_cast<const int8_t*>(ws + (b_is_a ? lay.off_a : lay.off_b));
   if (b_is_a && lay.m_pad != lay.n_pad) return hipErrorInvalidValue;
   g.triangle = triangle;
+  g.krange = krange;
   g.c = reinterpret_cast<int*>(ws + lay.off_c);
   g.m_pad = lay.m_pad;
   g.n_pad = lay.n_pad;
@@ -368,13 +381,13 @@ hipError_t launch_gemm(const Oz2Layout& lay, char* ws, int num_moduli, const int
 }  // namespace
 
 hipError_t oz2_launch_stage2(const Oz2Plan& plan, const Oz2Layout& lay, char* ws, int64_t kblock, int residue_u8,
-                             int triangle, hipStream_t st) {
-  return launch_gemm(lay, ws, plan.N, plan.moduli, kblock, residue_u8, triangle, triangle != 0, st);
+                             int triangle, int krange, hipStream_t st) {
+  return launch_gemm(lay, ws, plan.N, plan.moduli, kblock, residue_u8, triangle, krange, triangle != 0, st);
 }
 
 // One plain INT8 product with INT32 output and no modular reduction between k-blocks: the caller guarantees
 // k_pad * 64 * 64 < 2^31.
 hipError_t oz2_launch_bound_gemm(const Oz2Layout& lay, char* ws, bool symmetric, hipStream_t st) {
   const int one = 1;
-  return launch_gemm(lay, ws, 1, &one, lay.k_pad, 0, 0, symmetric, st);
+  return launch_gemm(lay, ws, 1, &one, lay.k_pad, 0, 0, OZ2_KRANGE_ALL, symmetric, st);
 }

@@ -652,3 +652,91 @@ def test_hip_graph_replays_match_eager_calls():
         else:
             assert np.isnan(got[5, :]).all() and np.isfinite(np.delete(got, 5, axis=0)).all()
     del graph, ws
+
+
+# ------------------------------------------------------------------ triangular product, in place
+def _garbage_outside(A, uplo, diag):
+    """NaN wherever the routine must not look."""
+    G = A.copy()
+    ka = A.shape[0]
+    ii, jj = np.meshgrid(np.arange(ka), np.arange(ka), indexing="ij")
+    G[(ii < jj) if uplo == "L" else (ii > jj)] = np.nan
+    if diag == "U":
+        G[np.arange(ka), np.arange(ka)] = np.nan
+    return np.asfortranarray(G)
+
+
+@pytest.mark.parametrize("side", ["L", "R"])
+@pytest.mark.parametrize("uplo", ["L", "U"])
+@pytest.mark.parametrize("transa", ["N", "T"])
+@pytest.mark.parametrize("diag,mode", [("N", 0), ("U", 0), ("N", 1), ("U", 2)])
+def test_dtrmm_matches_the_oracle_in_place(side, uplo, transa, diag, mode):
+    rng = np.random.default_rng(51)
+    m, n, N = 300, 520, 13          # order of A: 300 (two diagonal blocks) or 520 (three)
+    ka = m if side == "L" else n
+    A = (rng.random((ka, ka)) - 0.5) * np.exp(rng.standard_normal((ka, ka)))
+    B = np.asfortranarray((rng.random((m, n)) - 0.5) * np.exp(rng.standard_normal((m, n))))
+    B[4, :] = 0.0
+    G = _garbage_outside(A, uplo, diag)
+    ldb = m + 3
+    hB = np.full((ldb, n), 7.0, order="F")
+    hB[:m, :] = B
+    dA = _dev(G)
+    dB = torch.from_numpy(np.ascontiguousarray(hB.T)).cuda().t()
+    ws = oz.Workspace(m, n, ka, N)
+    oz.oz2_set_shift_mode(mode)
+    try:
+        print("dtrmm side=%s uplo=%s trans=%s diag=%s mode=%d" % (side, uplo, transa, diag, mode), flush=True)
+        oz.oz2_dtrmm(side, uplo, transa, diag, m, n, -1.25, dA.data_ptr(), ka, dB.data_ptr(), ldb, N)
+        torch.cuda.synchronize()
+    finally:
+        oz.oz2_set_shift_mode(0)
+    lay = oz.workspace_layout(m, n, ka, N)
+    assert int(ws.view(lay["flags"], 32, torch.int64).cpu().numpy()[0]) == 0     # the NaNs outside were never looked at
+    got = dB.cpu().numpy()
+    ref = orc.dtrmm(side, uplo, transa, diag, -1.25, G, B, N, mode=mode)
+    assert np.array_equal(got[:m, :], ref)
+    assert np.all(got[m:, :] == 7.0)            # the padding rows of B's array are untouched
+    del ws
+
+
+def test_dtrmm_degenerate_nonfinite_and_arguments():
+    rng = np.random.default_rng(52)
+    m, n, N = 90, 60, 9
+    A = np.asfortranarray(np.tril(rng.standard_normal((m, m))))
+    B = np.asfortranarray(rng.standard_normal((m, n)))
+    ws = oz.Workspace(m, n, m, N)
+    dA = _dev(A)
+    # alpha == 0: B := 0, A not read
+    dB = _dev(B).clone()
+    dN = torch.full((m, m), float("nan"), dtype=torch.float64, device="cuda")
+    oz.oz2_dtrmm("L", "L", "N", "N", m, n, 0.0, dN.data_ptr(), m, dB.data_ptr(), m, N)
+    torch.cuda.synchronize()
+    assert np.array_equal(dB.cpu().numpy(), np.zeros((m, n)))
+    # an infinity inside the triangle: FP64 fallback, in place through the workspace
+    A2 = A.copy()
+    A2[40, 3] = np.inf
+    B2 = B.copy()
+    B2[3, 5] = 0.0
+    dA2, dB = _dev(A2), _dev(B2).clone()
+    oz.oz2_dtrmm("L", "L", "N", "N", m, n, 2.0, dA2.data_ptr(), m, dB.data_ptr(), m, N)
+    torch.cuda.synchronize()
+    got = dB.cpu().numpy()
+    ref = orc.dtrmm("L", "L", "N", "N", 2.0, A2, B2, N)
+    assert np.array_equal(np.isnan(got), np.isnan(ref)) and np.isnan(ref[40, 5])
+    inf = np.isinf(ref)
+    assert np.array_equal(np.isinf(got), inf) and np.array_equal(got[inf], ref[inf]) and inf.sum() == n - 1
+    fin = np.isfinite(ref)
+    S = 2.0 * np.abs(np.nan_to_num(A2, posinf=0.0)) @ np.abs(B2)
+    assert np.all(np.abs(got[fin] - ref[fin]) <= 2 * (m + 2) * 2.0**-53 * S[fin])
+    # argument checks
+    L = oz.lib()
+    args = lambda **kw: [kw.get("side", b"L"), kw.get("uplo", b"L"), kw.get("trans", b"N"), kw.get("diag", b"N"),
+                         kw.get("m", m), kw.get("n", n), 1.0, dA.data_ptr(), kw.get("lda", m), dB.data_ptr(), kw.get("ldb", m),
+                         kw.get("N", N), None]
+    assert L.oz2_dtrmm(*args(side=b"X")) == -1 and L.oz2_dtrmm(*args(uplo=b"X")) == -2
+    assert L.oz2_dtrmm(*args(trans=b"X")) == -3 and L.oz2_dtrmm(*args(diag=b"X")) == -4
+    assert L.oz2_dtrmm(*args(m=-1)) == -5 and L.oz2_dtrmm(*args(n=-1)) == -6
+    assert L.oz2_dtrmm(*args(lda=m - 1)) == -9 and L.oz2_dtrmm(*args(ldb=m - 1)) == -11
+    assert L.oz2_dtrmm(*args(side=b"R", lda=n - 1)) == -9 and L.oz2_dtrmm(*args(N=1)) == -12
+    del ws

@@ -545,3 +545,40 @@ def test_symmetric_product_is_exactly_symmetric_and_touches_one_triangle(mode):
                         assert got[i, j] == float(Fraction(0.5) * Fraction(float(P.C[i, j])) + Fraction(t))
                     else:
                         assert got[i, j] == C0[i, j]
+
+
+# ------------------------------------------------------------------ Section 2.3: structured products (TRMM shape)
+def test_triangular_product_reads_one_triangle_and_is_exact_on_integers():
+    rng = np.random.default_rng(17)
+    m, n = 7, 5
+    for side in "LR":
+        ka = m if side == "L" else n
+        for uplo in "LU":
+            for transa in "NT":
+                for diag in "NU":
+                    A = rng.integers(-50, 50, (ka, ka)).astype(np.float64)
+                    B = rng.integers(-50, 50, (m, n)).astype(np.float64)
+                    # the triangle seen by the routine, as Python integers
+                    T = [[0] * ka for _ in range(ka)]
+                    for r in range(ka):
+                        for c in range(ka):
+                            if (r > c and uplo == "L") or (r < c and uplo == "U"):
+                                T[r][c] = int(A[r, c])
+                            elif r == c:
+                                T[r][c] = 1 if diag == "U" else int(A[r, c])
+                    if transa == "T":
+                        T = [[T[c][r] for c in range(ka)] for r in range(ka)]
+                    Bi = [[int(B[i, j]) for j in range(n)] for i in range(m)]
+                    if side == "L":
+                        want = [[-3 * sum(T[i][l] * Bi[l][j] for l in range(m)) for j in range(n)] for i in range(m)]
+                    else:
+                        want = [[-3 * sum(Bi[i][l] * T[l][j] for l in range(n)) for j in range(n)] for i in range(m)]
+                    # what is not referenced may hold anything
+                    G = A.copy()
+                    for r in range(ka):
+                        for c in range(ka):
+                            if (r < c and uplo == "L") or (r > c and uplo == "U") or (r == c and diag == "U"):
+                                G[r, c] = np.nan
+                    got = orc.dtrmm(side, uplo, transa, diag, -3.0, G, B, 10)
+                    assert got.tolist() == [[float(v) for v in row] for row in want]
+    assert np.array_equal(orc.dtrmm("L", "U", "N", "N", 0.0, np.full((m, m), np.nan), B, 10), np.zeros((m, n)))
