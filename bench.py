@@ -246,6 +246,20 @@ def main():
         syrk_t = (time.perf_counter() - t0) / 3
         out["dsyrk_lower_%d_moduli" % N] = {"ms_per_call": round(syrk_t * 1e3, 3),
                                             "TFLOPS_as_full_product": round(2.0 * m * m * k / syrk_t / 1e12, 2)}
+        # context: the triangular product B := A_lower * B in place (same sizes; half of the inner dimension
+        # is zero by structure)
+        if m == k:
+            dB2 = dB.clone()
+            oz.oz2_dtrmm("L", "L", "N", "N", m, n, 1.0, dA.data_ptr(), m, dB2.data_ptr(), k, N, stream)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(3):
+                oz.oz2_dtrmm("L", "L", "N", "N", m, n, 1.0, dA.data_ptr(), m, dB2.data_ptr(), k, N, stream)
+            torch.cuda.synchronize()
+            trmm_t = (time.perf_counter() - t0) / 3
+            out["dtrmm_left_lower_%d_moduli" % N] = {"ms_per_call": round(trmm_t * 1e3, 3),
+                                                     "TFLOPS_as_full_product": round(2.0 * m * n * k / trmm_t / 1e12, 2)}
+            del dB2
         del dC2, ws
         ws = oz.Workspace(m, n, k, N, device=dev)
 
