@@ -10,10 +10,12 @@
  *     they return without waiting for the GPU.
  *   - Return value: 0 success; -i = the i-th argument is invalid (1-based, LAPACK style);
  *     OZ2_ERR_WORKSPACE (1) workspace missing or too small; OZ2_ERR_BUDGET (2) the moduli product is
- *     too small for this inner dimension (kappa < 1); OZ2_ERR_HIP (3) a HIP call failed.
+ *     too small for this inner dimension (kappa < 1), or the inner dimension too long for the shift mode; OZ2_ERR_HIP (3) a HIP call failed.
  *     Nothing is printed and nothing throws across this boundary.
- *   - Inputs must be finite.  NaN, infinities and signed zeros are outside the method (Section 3, last
- *     paragraph); so are inputs whose scaled products leave the FP64 exponent range.
+ *   - The method covers finite inputs (Section 3.1, last paragraph).  Infinities and NaNs in A or B are detected
+ *     and handled by an FP64 fallback (oz2_set_nonfinite_check, on by default); signed zeros are not tracked
+ *     (an emulated zero is +0); results beyond the FP64 range become infinities as in FP64.
+ *   - One GPU: the library is used from one device per process (kernel attributes are set once).
  *   - The library keeps one workspace registration per process (oz2_set_workspace).  Calls that use it
  *     must not overlap in time on different streams.
  */
