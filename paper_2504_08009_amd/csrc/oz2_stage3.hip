@@ -37,8 +37,7 @@ struct PlaneLoad<true> {
   }
 };
 
-// One thread: R consecutive rows i of one column j.  Planes are read one ahead of the arithmetic so that
-// every wave keeps two loads in flight.
+// One thread: R consecutive rows i of one column j.
 template <int L, bool U8>
 __global__ void __launch_bounds__(kThreads) crt_kernel(const void* __restrict__ cplanes, int64_t m_pad, int64_t n_pad,
                                                        const int* __restrict__ sa, const int* __restrict__ sb,
@@ -67,17 +66,37 @@ __global__ void __launch_bounds__(kThreads) crt_kernel(const void* __restrict__ 
 #pragma unroll
     for (int l = 0; l < L; ++l) S[r][l] = 0.0;
 
-  Raw cur = src[0];
-  for (int t = 0; t < cc.N; ++t) {
-    const Raw c = cur;
-    if (t + 1 < cc.N) cur = src[(size_t)(t + 1) * stride];
-    double res[R];
-    PL::residues(c, cc.p[t], cc.inv_p[t], cc.half_inv_p[t], res);
+  // Planes are read a batch ahead of the arithmetic: kBatch loads per thread in flight keep enough bytes
+  // moving per CU to cover the memory latency (one load ahead does not).
+  constexpr int kBatch = 4;
+  const int N = cc.N;
+  Raw nxt[kBatch];
 #pragma unroll
-    for (int l = 0; l < L; ++l) {
-      const double w = cc.w[t][l];
+  for (int d = 0; d < kBatch; ++d) nxt[d] = src[(size_t)(d < N ? d : N - 1) * stride];
+  for (int t0 = 0; t0 < N; t0 += kBatch) {
+    Raw cur[kBatch];
 #pragma unroll
-      for (int r = 0; r < R; ++r) S[r][l] = fma(res[r], w, S[r][l]);
+    for (int d = 0; d < kBatch; ++d) cur[d] = nxt[d];
+    if (t0 + kBatch < N) {
+#pragma unroll
+      for (int d = 0; d < kBatch; ++d) {
+        const int t = t0 + kBatch + d;
+        nxt[d] = src[(size_t)(t < N ? t : N - 1) * stride];  // past the end: a harmless repeat of the last plane
+      }
+    }
+#pragma unroll
+    for (int d = 0; d < kBatch; ++d) {
+      const int t = t0 + d;
+      if (t < N) {
+        double res[R];
+        PL::residues(cur[d], cc.p[t], cc.inv_p[t], cc.half_inv_p[t], res);
+#pragma unroll
+        for (int l = 0; l < L; ++l) {
+          const double w = cc.w[t][l];
+#pragma unroll
+          for (int r = 0; r < R; ++r) S[r][l] = fma(res[r], w, S[r][l]);
+        }
+      }
     }
   }
   const int sbj = sb[j];

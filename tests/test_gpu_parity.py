@@ -109,6 +109,9 @@ def test_c1_all_stages(fmt):
     (33, 17, 50, 23, 4.0),        # kappa > 75: two-level split, 5 limbs
     (5, 3, 1, 26, 0.5),           # k = 1, largest moduli count
     (1, 1, 7, 2, 0.5),            # smallest everything
+    (5000, 1, 7, 12, 0.5),        # tall and thin: twenty row tiles, one column
+    (1, 3000, 2000, 15, 1.0),     # one row, twelve column tiles
+    (2100, 3, 5000, 16, 0.5),     # long inner dimension against a sliver of C
 ])
 @pytest.mark.parametrize("fmt", [0, 1])
 def test_ragged_shapes(m, n, k, N, phi, fmt):
