@@ -1,10 +1,15 @@
 // Stage 1 of Ozaki scheme II on gfx950: Algorithm 1 lines 1-5.
 //   1a  per-row maximum of |A| and per-column maximum of |B| (bit patterns, 64-bit atomic max)
-//   1a' shifts  sa_i = kappa - 1 - floor(log2 max_l |a_il|),  sb_j likewise  (Section 3, D and E)
+//   1a' shifts  sa_i = kappa - 1 - floor(log2 max_l |a_il|),  sb_j likewise  (Section 3, D and E); or, in the
+//       modes of Section 4.1, from an integer bound of the 2-norms (one more pass over A and B) or from the
+//       row / column maxima of an INT8 product of 6-bit upper bounds of |A| and |B| (bound planes, one GEMM
+//       launch, one pass over the product)
 //   1b  a' = trunc(a * 2^sa_i) and its symmetric residues modulo every p_t, written as INT8 planes in the
 //       blocked layout the GEMM reads (256 rows x 64 inner-dimension bytes per contiguous block), zero
 //       padded up to the GEMM tile sizes.
-// All three are bound by HBM traffic: 8 bytes read per element in 1a, 8 read + N written in 1b.
+// All are bound by HBM traffic: 8 bytes read per element in 1a, 8 read + N written in 1b.
+// Infinities and NaNs are noticed in 1a (their bit patterns are above every finite magnitude) and recorded in
+// a flag word of the workspace.  Triangular operands (TRMM shape) are masked while they are read.
 #include "oz2_math.h"
 
 namespace {

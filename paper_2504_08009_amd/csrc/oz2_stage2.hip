@@ -33,6 +33,10 @@
 // same time, so that panels re-read by several XCDs come from the shared last-level cache instead of HBM
 // (measured: same L2 miss count, higher clock under the power cap, +6 % throughput).  Otherwise each XCD
 // walks its own contiguous range of tiles in 8-tile-tall column groups.
+//
+// Structured products: for the symmetric product op(A) op(A)^T both operands are A's planes and the
+// workgroups of the other triangle of tiles return at once; for a triangular operand a tile walks only the
+// k-tiles up to or from its diagonal block.
 #include <type_traits>
 
 #include "oz2_internal.h"

@@ -2,7 +2,8 @@
 //   per output element: c''_t = c'_t mod p_t (line 7), Y = sum_t c''_t W_t on 40-bit FP64 limbs (line 9),
 //   X = Y mod M in the symmetric range (line 10), one rounding to FP64 and the exact power-of-two
 //   scaling by 2^-(sa_i + sb_j) (line 11).
-// Bound by HBM traffic: 4N (INT32 planes) or N (UINT8 residue planes) bytes read and 8 written per element.
+// 4N (INT32 planes) or N (UINT8 residue planes, line 7 already taken by the GEMM epilogue) bytes read and 8
+// written per element: bound by HBM traffic with INT32 planes, by FP64 instruction issue with UINT8 planes.
 #include "oz2_math.h"
 
 namespace {
