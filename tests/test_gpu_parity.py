@@ -444,10 +444,11 @@ def test_inner_dimension_beyond_int32_exactness():
     kap = orc.kappa(N, k)
     A[0, :] = 1.0 + 128.0 * 2.0 ** -(kap - 1)
     B[:, 0] = 1.0 + 128.0 * 2.0 ** -(kap - 1)
+    B[:, 1] = 1.0 + 127.0 * 2.0 ** -(kap - 1)      # residue +127: the most negative products, -128 * 127 each
     got, ref = check_against_oracle(A, B, N, products_exact=False)
     check_against_oracle(A, B, N, fmt=1)
-    # the exact products really exceed INT32 somewhere, so blocking was needed
-    assert np.max(np.abs(ref.Cprod)) > 2**31
+    # the exact products really exceed INT32 somewhere, on both sides, so blocking was needed
+    assert np.max(ref.Cprod) > 2**31 and np.min(ref.Cprod) < -2**31
 
 
 # ------------------------------------------------------------------ exceptional inputs: detection and FP64 fallback
