@@ -322,6 +322,28 @@ def test_planted_mistakes_are_caught_by_the_pins():
     assert rebuild(W, shifted) != r.X
 
 
+def test_hand_worked_example_three_moduli():
+    # A 2 x 2 x 2 product small enough to follow with pencil and paper (Algorithm 1 with the moduli 256, 255,
+    # 253: M = 16515840, kappa = 10 for k = 2).  Every number below follows from the definitions:
+    # e.g. 512 = trunc(1.0 * 2^9), 153 = trunc(0.3 * 2^9), 153 mod 256 = -103 (symmetric), 5253 = (-103)(-51),
+    # 5253 mod 256 = 133, and X = A'B' = [[512*358 + 153*(-563), 512*768], [-640*358, -640*768]].
+    A = np.array([[1.0, 0.3], [-2.5, 1e-3]])
+    B = np.array([[0.7, 3.0], [-1.1, 0.001]])
+    assert orc.moduli(3) == [256, 255, 253] and orc.kappa(3, 2) == 10
+    M, W = orc.crt_constants(3)
+    assert M == 16515840 and [int(w) for w in W] == [64515 * 171, 64768 * 127, 65280 * 211]
+    r = orc.dgemm(A, B, 3, want=("C", "shifts", "Ap", "Bp", "Ares", "Bres", "Cprod", "Cres", "X"))
+    assert r.sa.tolist() == [9, 8] and r.sb.tolist() == [9, 8]
+    assert r.Ap == [[512, 153], [-640, 0]] and r.Bp == [[358, 768], [-563, 0]]
+    assert r.Ares[0].tolist() == [[0, -103], [-128, 0]]                 # rows of A' modulo 256
+    assert r.Bres[0].tolist() == [[102, -51], [0, 0]]                   # columns of B' modulo 256
+    assert r.Cprod.tolist() == [[[5253, 0], [-13056, 0]], [[5612, 6], [12875, 375]], [[6330, 54], [12495, 1071]]]
+    assert r.Cres.tolist() == [[[133, 0], [0, 0]], [[2, 6], [125, 120]], [[5, 54], [98, 59]]]
+    assert r.X == [[97157, 393216], [-229120, -491520]]
+    assert r.X == [[512 * 358 + 153 * -563, 512 * 768], [-640 * 358, -640 * 768]]
+    assert r.C.tolist() == [[97157 / 2.0**18, 3.0], [-229120 / 2.0**17, -7.5]]
+
+
 # ------------------------------------------------------------------ Section 4.1: Cauchy-Schwarz shift selection
 @pytest.mark.parametrize("N,phi", [(4, 0.5), (10, 1.0), (16, 0.5), (20, 4.0), (26, 4.0)])
 def test_cauchy_schwarz_shifts_are_rigorous_and_maximal(N, phi):
