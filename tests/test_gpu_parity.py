@@ -744,3 +744,46 @@ def test_dtrmm_degenerate_nonfinite_and_arguments():
     assert L.oz2_dtrmm(*args(lda=m - 1)) == -9 and L.oz2_dtrmm(*args(ldb=m - 1)) == -11
     assert L.oz2_dtrmm(*args(side=b"R", lda=n - 1)) == -9 and L.oz2_dtrmm(*args(N=1)) == -12
     del ws
+
+
+# ------------------------------------------------------------------ structured products on the super-block tile order
+def test_dsyrk_and_dtrmm_at_4096_sampled():
+    # 16 x 16 tiles: the tile order that shares a super-block between the XCDs, with its triangle of tiles
+    # skipped (dsyrk) or its inner dimension cut at the diagonal block (dtrmm); outputs checked on sampled rows
+    # and columns, the diagonal blocks included
+    n = k = 4096
+    N = 15
+    A = inputs.block(250408003, 0, n, k, 1.0)
+    B = inputs.block(250408003, 1, k, n, 1.0)
+    rng = np.random.default_rng(8)
+    rows = np.unique(np.concatenate([[0, 255, 256, n - 1], rng.choice(n, 12, replace=False)]))
+    cols = np.unique(np.concatenate([[0, 255, 256, n - 1], rng.choice(n, 12, replace=False)]))
+    drows, dcols = torch.from_numpy(rows).cuda(), torch.from_numpy(cols).cuda()
+    dA = _dev(A)
+    ws = oz.Workspace(n, n, k, N)
+    # --- dsyrk, lower
+    dC = torch.zeros((n, n), dtype=torch.float64, device="cuda").t()
+    print("dsyrk n=k=4096", flush=True)
+    oz.oz2_dsyrk("L", "N", n, k, 1.0, dA.data_ptr(), n, 0.0, dC.data_ptr(), n, N)
+    torch.cuda.synchronize()
+    got = dC[drows][:, dcols].cpu().numpy()
+    ref = orc.dgemm(A, A.T, N, rows=rows, cols=cols).C
+    low = rows[:, None] >= cols[None, :]
+    assert np.array_equal(got[low], ref[low]) and np.all(got[~low] == 0.0)
+    # --- dtrmm, left, upper, transposed: op(A) = A^T is lower triangular
+    T = orc.triangular(A, "U", "N")
+    dB = _dev(B).clone()
+    print("dtrmm n=k=4096", flush=True)
+    oz.oz2_dtrmm("L", "U", "T", "N", n, n, 1.0, dA.data_ptr(), n, dB.data_ptr(), n, N)
+    torch.cuda.synchronize()
+    got = dB[drows][:, dcols].cpu().numpy()
+    ref = orc.dgemm(T.T, B, N, rows=rows, cols=cols).C
+    assert np.array_equal(got, ref)
+    # --- dtrmm, right, upper: the second operand is triangular
+    dB = _dev(B).clone()
+    oz.oz2_dtrmm("R", "U", "N", "N", n, n, 1.0, dA.data_ptr(), n, dB.data_ptr(), n, N)
+    torch.cuda.synchronize()
+    got = dB[drows][:, dcols].cpu().numpy()
+    ref = orc.dgemm(B, T, N, rows=rows, cols=cols).C
+    assert np.array_equal(got, ref)
+    del ws
