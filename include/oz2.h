@@ -52,6 +52,13 @@ int oz2_max_moduli(void);
  * even kappa = 0 breaks the bound.  k >= 1.  Returns 0 or a negative argument code. */
 int oz2_get_moduli(int num_moduli, int* moduli_out, int* kappa_out, int64_t k);
 
+/* Smallest number of moduli whose bit budget kappa (same definition as in oz2_get_moduli) reaches `bits` for
+ * inner dimension k: with it every entry of a row (column) keeps at least `bits` bits below the row's
+ * (column's) largest one under the default shift selection (Section 3.1 works this out for 53 bits: sixteen moduli
+ * cover the inner dimensions 1024, 4096 and 16384).  Returns that count, 0 if even oz2_max_moduli() does not reach it, -1 / -2 for k < 1 /
+ * bits < 1. */
+int oz2_moduli_for_bits(int64_t k, int bits);
+
 /* Workspace size in bytes for a problem, 0 on invalid arguments.  Holds the shift vectors, the INT8
  * residue planes of A and B and the INT32 product planes (Algorithm 1, lines 1-6). */
 size_t oz2_workspace_bytes(int64_t m, int64_t n, int64_t k, int num_moduli);

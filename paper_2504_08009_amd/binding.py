@@ -7,7 +7,7 @@ _LIB_PATH = os.path.join(_HERE, "liboz2.so")
 _lib = None
 
 SYMBOLS = [
-    "oz2_min_moduli", "oz2_max_moduli", "oz2_get_moduli", "oz2_workspace_bytes", "oz2_set_workspace",
+    "oz2_min_moduli", "oz2_moduli_for_bits", "oz2_max_moduli", "oz2_get_moduli", "oz2_workspace_bytes", "oz2_set_workspace",
     "oz2_workspace_layout", "oz2_dgemm", "oz2_dgemm_ex", "oz2_dsyrk", "oz2_dtrmm", "oz2_stage1_convert", "oz2_stage2_gemm", "oz2_stage3_crt",
     "oz2_set_kblock", "oz2_set_shift_mode", "oz2_set_product_format", "oz2_set_nonfinite_check", "oz2_set_stage_events", "oz2_calibrate_mfma", "oz2_host_crt_element", "oz2_host_residues", "oz2_status_string",
 ]
@@ -26,6 +26,7 @@ def lib():
         L = ctypes.CDLL(_LIB_PATH)
         i64, vp, ci = ctypes.c_int64, ctypes.c_void_p, ctypes.c_int
         L.oz2_get_moduli.argtypes = [ci, vp, vp, i64]
+        L.oz2_moduli_for_bits.argtypes = [i64, ci]
         L.oz2_workspace_bytes.restype = ctypes.c_size_t
         L.oz2_workspace_bytes.argtypes = [i64, i64, i64, ci]
         L.oz2_set_workspace.argtypes = [vp, ctypes.c_size_t]
@@ -76,6 +77,14 @@ def get_moduli(num_moduli, k=1):
 
 def workspace_bytes(m, n, k, num_moduli):
     return int(lib().oz2_workspace_bytes(m, n, k, num_moduli))
+
+
+def moduli_for_bits(k, bits=53):
+    """Smallest number of moduli whose bit budget reaches `bits` for inner dimension k (0: none does)."""
+    rc = lib().oz2_moduli_for_bits(int(k), int(bits))
+    if rc < 0:
+        raise Oz2Error("oz2_moduli_for_bits: invalid argument %d" % -rc)
+    return rc
 
 
 def workspace_layout(m, n, k, num_moduli):

@@ -76,6 +76,14 @@ int oz2_get_moduli(int num_moduli, int* moduli_out, int* kappa_out, int64_t k) {
   return OZ2_OK;
 }
 
+int oz2_moduli_for_bits(int64_t k, int bits) {
+  if (k < 1) return -1;
+  if (bits < 1) return -2;
+  for (int N = OZ2_MIN_N; N <= OZ2_MAX_N; ++N)
+    if (oz2_table_kappa(N, k) >= bits) return N;
+  return 0;
+}
+
 size_t oz2_workspace_bytes(int64_t m, int64_t n, int64_t k, int num_moduli) {
   if (m < 0 || n < 0 || k < 0 || !n_ok(num_moduli) || !dims_ok(m, n, k)) return 0;
   Oz2Layout lay;

@@ -37,6 +37,19 @@ def test_moduli_and_kappa_match_the_oracle():
             assert kap == orc.kappa(N, k)
 
 
+def test_moduli_for_bits_matches_the_papers_statement():
+    # Section 3.1: sixteen moduli give 53 bits for all of the inner dimensions 1024, 4096 and 16384, fifteen
+    # only for the first
+    assert [oz.moduli_for_bits(k, 53) for k in (1024, 4096, 16384)] == [15, 16, 16]
+    assert [orc.kappa(15, k) for k in (1024, 4096, 16384)] == [53, 52, 51]
+    assert [orc.kappa(16, k) for k in (1024, 4096, 16384)] == [57, 56, 55]
+    for k, bits in [(1, 1), (100, 24), (65536, 53), (10**6, 40)]:
+        N = oz.moduli_for_bits(k, bits)
+        assert orc.kappa(N, k) >= bits and (N == 2 or orc.kappa(N - 1, k) < bits)
+    assert oz.moduli_for_bits(16384, 200) == 0
+    assert oz.lib().oz2_moduli_for_bits(0, 53) == -1 and oz.lib().oz2_moduli_for_bits(5, 0) == -2
+
+
 def test_argument_validation_without_gpu():
     L = oz.lib()
     assert L.oz2_get_moduli(1, None, None, 5) == -1
