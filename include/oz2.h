@@ -7,7 +7,8 @@
  *   - A, B, C and the workspace are DEVICE pointers owned by the caller; the library never frees them.
  *     A and B are read-only, C is overwritten, A/B must not overlap C or the workspace.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls only enqueue work;
- *     they return without waiting for the GPU.
+ *     they return without waiting for the GPU, allocate nothing and record no memset, so a call can be captured
+ *     into a HIP graph (after oz2_init or one earlier call).
  *   - Return value: 0 success; -i = the i-th argument is invalid (1-based, LAPACK style);
  *     OZ2_ERR_WORKSPACE (1) workspace missing or too small; OZ2_ERR_BUDGET (2) the moduli product is
  *     too small for this inner dimension (kappa < 1), or the inner dimension too long for the shift mode; OZ2_ERR_HIP (3) a HIP call failed.
@@ -40,6 +41,11 @@ extern "C" {
 #define OZ2_SHIFT_MAX 0            /* shifts from row/column maxima: the simple bound of Section 3 */
 #define OZ2_SHIFT_CAUCHY_SCHWARZ 1 /* shifts from row/column 2-norms: Section 4.1, the "fast" variant */
 #define OZ2_SHIFT_INT8_PRODUCT 2   /* shifts from an INT8 product of upper bounds: Section 4.1, the "accu" variant */
+
+/* One-time set-up on the current device (kernel attributes, compute-unit count).  The first call that launches
+ * the GEMM does the same by itself; call this first when that call would otherwise be made under stream
+ * capture, where attributes cannot be set.  Returns 0 or OZ2_ERR_HIP. */
+int oz2_init(void);
 
 /* Smallest and largest supported number of moduli (Section 3.1: the table starts at s = 2). */
 int oz2_min_moduli(void);

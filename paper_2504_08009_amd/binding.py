@@ -7,7 +7,7 @@ _LIB_PATH = os.path.join(_HERE, "liboz2.so")
 _lib = None
 
 SYMBOLS = [
-    "oz2_min_moduli", "oz2_moduli_for_bits", "oz2_max_moduli", "oz2_get_moduli", "oz2_workspace_bytes", "oz2_set_workspace",
+    "oz2_init", "oz2_min_moduli", "oz2_moduli_for_bits", "oz2_max_moduli", "oz2_get_moduli", "oz2_workspace_bytes", "oz2_set_workspace",
     "oz2_workspace_layout", "oz2_dgemm", "oz2_dgemm_ex", "oz2_dsyrk", "oz2_dtrmm", "oz2_stage1_convert", "oz2_stage2_gemm", "oz2_stage3_crt",
     "oz2_set_kblock", "oz2_set_shift_mode", "oz2_set_product_format", "oz2_set_nonfinite_check", "oz2_set_stage_events", "oz2_calibrate_mfma", "oz2_host_crt_element", "oz2_host_residues", "oz2_status_string",
 ]
@@ -77,6 +77,10 @@ def get_moduli(num_moduli, k=1):
 
 def workspace_bytes(m, n, k, num_moduli):
     return int(lib().oz2_workspace_bytes(m, n, k, num_moduli))
+
+
+def oz2_init():
+    _check(lib().oz2_init(), "oz2_init")
 
 
 def moduli_for_bits(k, bits=53):

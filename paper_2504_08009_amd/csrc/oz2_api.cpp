@@ -65,6 +65,12 @@ int prepare(State& s, int64_t m, int64_t n, int64_t k, int N, const Oz2Plan** pl
 
 extern "C" {
 
+int oz2_init(void) {
+  State& s = state();
+  std::lock_guard<std::mutex> lock(s.mu);
+  return oz2_gemm_setup() == hipSuccess ? OZ2_OK : OZ2_ERR_HIP;
+}
+
 int oz2_min_moduli(void) { return OZ2_MIN_N; }
 int oz2_max_moduli(void) { return OZ2_MAX_N; }
 

@@ -66,6 +66,10 @@ void oz2_make_layout(int64_t m, int64_t n, int64_t k, int N, Oz2Layout* lay);
 hipError_t oz2_launch_stage1(int transa, int transb, int64_t m, int64_t n, int64_t k, const double* A, int64_t lda,
                              const double* B, int64_t ldb, int tri_a, int tri_b, const Oz2Plan& plan, int shift_mode,
                              const Oz2Layout& lay, char* ws, hipStream_t st);
+// One-time device set-up of the GEMM kernels (function attributes, compute-unit count); also done lazily by the
+// first launch.
+hipError_t oz2_gemm_setup();
+
 // Inner-dimension range of a tile when one operand is triangular (TRMM shape), in units of diagonal blocks:
 //   UPTO_ROW / FROM_ROW: the first operand is lower / upper triangular (only l <= i / l >= i contribute);
 //   FROM_COL / UPTO_COL: the second operand is lower / upper triangular (only l >= j / l <= j contribute).

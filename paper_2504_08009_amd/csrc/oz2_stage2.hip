@@ -401,23 +401,29 @@ __global__ void __launch_bounds__(kThreads) gemm_i8_kernel(const GemmArgs g) {
 
 namespace {
 
-hipError_t set_lds_attributes() {
-  static bool attr_set = false;
-  if (attr_set) return hipSuccess;
+// Once per process: the kernels' dynamic LDS limit and the number of compute units (a multiple of 8, one
+// workgroup slot each).  Callers hold the library's lock.
+int g_cus = 0;
+hipError_t gemm_setup() {
+  if (g_cus) return hipSuccess;
   hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_i8_kernel<false>),
                                      hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
   if (e == hipSuccess)
     e = hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_i8_kernel<true>),
                             hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
-  if (e == hipSuccess) attr_set = true;
-  return e;
+  if (e != hipSuccess) return e;
+  int dev = 0, n = 0;
+  if ((e = hipGetDevice(&dev)) != hipSuccess) return e;
+  if ((e = hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev)) != hipSuccess) return e;
+  g_cus = n / 8 * 8 < 8 ? 8 : n / 8 * 8;
+  return hipSuccess;
 }
 
 // num_moduli planes of A' (off_a) times planes of B' (off_b) -> planes of C' (off_c)
 // b_is_a: the second operand's planes are the first operand's (symmetric product; m_pad == n_pad)
 hipError_t launch_gemm(const Oz2Layout& lay, char* ws, int num_moduli, const int* moduli, int64_t kblock, int residue_u8,
                        int triangle, int krange, bool b_is_a, hipStream_t st) {
-  hipError_t e = set_lds_attributes();
+  hipError_t e = gemm_setup();
   if (e != hipSuccess) return e;
   GemmArgs g;
   g.a = reinterpret_cast<const int8_t*>(ws + lay.off_a);
@@ -445,15 +451,7 @@ hipError_t launch_gemm(const Oz2Layout& lay, char* ws, int num_moduli, const int
   // unequal length (or none): there the hardware's dynamic placement of one workgroup per index balances better.
   unsigned grid = (unsigned)(g.chunk * 8);
   if (triangle == 0 && krange == OZ2_KRANGE_ALL) {
-    static int cus = 0;
-    if (cus == 0) {
-      int dev = 0, n = 0;
-      if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess)
-        return hipErrorInvalidDevice;
-      cus = n / 8 * 8;
-      if (cus < 8) cus = 8;
-    }
-    if (grid > (unsigned)cus) grid = (unsigned)cus;
+    if (grid > (unsigned)g_cus) grid = (unsigned)g_cus;
   }
   if (residue_u8)
     hipLaunchKernelGGL(gemm_i8_kernel<true>, dim3(grid), dim3(kThreads), kLdsBytes, st, g);
@@ -463,6 +461,8 @@ hipError_t launch_gemm(const Oz2Layout& lay, char* ws, int num_moduli, const int
 }
 
 }  // namespace
+
+hipError_t oz2_gemm_setup() { return gemm_setup(); }
 
 hipError_t oz2_launch_stage2(const Oz2Plan& plan, const Oz2Layout& lay, char* ws, int64_t kblock, int residue_u8,
                              int triangle, int krange, hipStream_t st) {

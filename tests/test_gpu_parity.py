@@ -631,7 +631,7 @@ def test_hip_graph_replays_match_eager_calls():
         return A, B
 
     load(0)
-    oz.oz2_dgemm(m, n, k, dA.data_ptr(), m, dB.data_ptr(), k, dE.data_ptr(), m, N)    # warm-up outside the capture
+    oz.oz2_init()            # kernel attributes cannot be set under capture
     torch.cuda.synchronize()
     graph = torch.cuda.CUDAGraph()
     side = torch.cuda.Stream()
