@@ -132,8 +132,12 @@ __device__ __forceinline__ Tile decode_tile(const GemmArgs& g, int slot, int wv)
     const int sbs_m = g.tiles_m >> 4, sbs_n = g.tiles_n >> 4;
     t = sb / (sbs_m * sbs_n);
     const int sr = sb - t * (sbs_m * sbs_n);
-    tm = (sr % sbs_m) * 16 + (x & 1) * 8 + (within & 7);
-    tn = (sr / sbs_m) * 16 + (x >> 1) * 4 + (within >> 3);
+    // Structured products: the eight sub-blocks of a super-block hold different amounts of work (tiles beyond
+    // the diagonal are skipped, tiles of a triangular operand differ in length), so the sub-block an XCD takes
+    // rotates with the super-block and the modulus; over eight moduli every XCD has had every position.
+    const int xp = (g.triangle | g.krange) ? ((x + sr + t) & 7) : x;
+    tm = (sr % sbs_m) * 16 + (xp & 1) * 8 + (within & 7);
+    tn = (sr / sbs_m) * 16 + (xp >> 1) * 4 + (within >> 3);
     if (t >= g.num_moduli) return T;
   } else {
     const int item = (slot & 7) * g.chunk + (slot >> 3);
