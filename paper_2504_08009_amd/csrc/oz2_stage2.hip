@@ -136,8 +136,14 @@ __device__ __forceinline__ Tile decode_tile(const GemmArgs& g, int slot, int wv)
     // the diagonal are skipped, tiles of a triangular operand differ in length), so the sub-block an XCD takes
     // rotates with the super-block and the modulus; over eight moduli every XCD has had every position.
     const int xp = (g.triangle | g.krange) ? ((x + sr + t) & 7) : x;
-    tm = (sr % sbs_m) * 16 + (xp & 1) * 8 + (within & 7);
-    tn = (sr / sbs_m) * 16 + (xp >> 1) * 4 + (within >> 3);
+    // super-block coordinates; with a triangular operand the super-blocks with the longest tiles go first
+    // (measured at 16384: 32.0 -> 30.1 ms for the product with a lower triangular first operand)
+    int sm = sr % sbs_m, sn = sr / sbs_m;
+    if (g.krange == OZ2_KRANGE_UPTO_ROW) { sm = sbs_m - 1 - sr / sbs_n; sn = sr % sbs_n; }
+    if (g.krange == OZ2_KRANGE_FROM_ROW) { sm = sr / sbs_n; sn = sr % sbs_n; }
+    if (g.krange == OZ2_KRANGE_UPTO_COL) { sn = sbs_n - 1 - sr / sbs_m; }
+    tm = sm * 16 + (xp & 1) * 8 + (within & 7);
+    tn = sn * 16 + (xp >> 1) * 4 + (within >> 3);
     if (t >= g.num_moduli) return T;
   } else {
     const int item = (slot & 7) * g.chunk + (slot >> 3);
