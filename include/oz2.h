@@ -179,6 +179,18 @@ int oz2_set_product_format(int format);
  * Returns 0 or -1. */
 int oz2_set_shift_mode(int mode);
 
+/* Unequal bit budgets for oz2_dgemm / oz2_dgemm_ex and the staged calls (Section 3: "if the precisions of the
+ * matrices A and B differ ... we assume k_A < k_B"), for all later calls.  delta moves that many bits of budget
+ * from op(A) to op(B) (negative: the other way); 0 (default) is the equal split k_A = k_B of the paper.  For
+ * delta != 0 and the default shift mode: k_A = kappa - delta, k_B = S - k_A with S = max{S : k 2^S <= M/2 - 1},
+ * so op(B) also receives the odd bit of S when there is one; in the Cauchy-Schwarz mode the two bounds become
+ * 2^(beta - delta) and 2^(b - beta + delta), b = max{b : 2^b <= M/2 - 1}; in the INT8-product mode sa is lowered
+ * and sb raised by delta.  Useful when one operand needs fewer bits than the other (e.g. single-precision
+ * values of similar magnitude in A: 25 bits suffice) -- fewer moduli then reach a given accuracy.  A call whose
+ * budget on either side would fall below 1 bit returns OZ2_ERR_BUDGET.  oz2_dsyrk and oz2_dtrmm always use
+ * the equal split.  |delta| <= 100.  Returns 0 or -1. */
+int oz2_set_bit_split(int delta);
+
 /* Optional timing hooks for oz2_dgemm: four caller-owned hipEvent_t handles (as void*), recorded on the
  * call's stream before stage 1 and after stages 1, 2 and 3 of every later oz2_dgemm call.  The kernels and
  * their order do not change.  events == NULL switches the hooks off.  Returns 0. */

@@ -41,8 +41,9 @@ def lib():
         _lib.oz2o_axpby.argtypes = [ctypes.c_int64, ctypes.c_double, ctypes.c_void_p, ctypes.c_double, ctypes.c_void_p]
         _lib.oz2o_shifts.argtypes = [ctypes.c_int, ctypes.c_int64, ctypes.c_int64, ctypes.c_void_p,
                                      ctypes.c_int64, ctypes.c_int, ctypes.c_void_p]
+        _lib.oz2o_kappa_sum.argtypes = [ctypes.c_int, ctypes.c_void_p, ctypes.c_int64]
         _lib.oz2o_dgemm_sub.argtypes = ([ctypes.c_int64] * 3 + [ctypes.c_void_p, ctypes.c_int64, ctypes.c_void_p,
-                                        ctypes.c_int64, ctypes.c_int, ctypes.c_int, ctypes.c_void_p, ctypes.c_int64,
+                                        ctypes.c_int64, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_void_p, ctypes.c_int64,
                                         ctypes.c_void_p, ctypes.c_int64, ctypes.c_void_p] + [ctypes.c_void_p] * 13)
         _lib.oz2o_exact_sub.argtypes = ([ctypes.c_int64] * 3 + [ctypes.c_void_p, ctypes.c_int64, ctypes.c_void_p,
                                         ctypes.c_int64, ctypes.c_int64, ctypes.c_void_p, ctypes.c_int64,
@@ -81,6 +82,12 @@ def kappa(N, k, mods=None):
     return int(lib().oz2o_kappa(int(N), _ptr(mods), int(k)))
 
 
+def kappa_sum(N, k, mods=None):
+    """Largest S = k_A + k_B with k * 2^S <= M/2 - 1 (Section 3, first budget equation)."""
+    mods = np.asarray(moduli(N) if mods is None else mods, dtype=np.int32)
+    return lib().oz2o_kappa_sum(int(N), _ptr(mods), int(k))
+
+
 def beta(N, mods=None):
     mods = np.asarray(moduli(N) if mods is None else mods, dtype=np.int32)
     return int(lib().oz2o_beta(int(N), _ptr(mods)))
@@ -115,12 +122,13 @@ class Result(dict):
     __getattr__ = dict.__getitem__
 
 
-def dgemm(A, B, N, mods=None, rows=None, cols=None, want=("C",), mode=0):
+def dgemm(A, B, N, mods=None, rows=None, cols=None, want=("C",), mode=0, delta=0):
     """Run Algorithm 1 on the CPU.  mode 0: shifts from the row/column maxima (Section 3); mode 1: shifts
     from the Cauchy-Schwarz bound (Section 4.1, "fast"); mode 2: shifts from the INT8 product of 6-bit upper
     bounds (Section 4.1, "accu"; the row and column maxima of that product always run over the whole of A and B,
     so A and B must be the full operands even when rows / cols select a subset).  A (m x k), B (k x n): numpy float64, any layout (copied to
-    column-major).  rows / cols: optional index lists selecting the outputs to compute.
+    column-major).  delta: bits of budget moved from A to B (0: the equal split of the paper).
+    rows / cols: optional index lists selecting the outputs to compute.
     want: any of "C", "shifts", "Ap", "Bp", "Ares", "Bres", "Cprod", "Cres", "X".
     Ap/Bp/X come back as nested Python-int lists (tiny inputs only)."""
     A = np.asfortranarray(A, dtype=np.float64)
@@ -147,7 +155,7 @@ def dgemm(A, B, N, mods=None, rows=None, cols=None, want=("C",), mode=0):
     cres = np.zeros((N, nJ, nI), dtype=np.uint8) if "Cres" in w else None
     xs = np.zeros((nJ, nI), dtype=np.uint8) if "X" in w else None
     xm = np.zeros((nJ, nI, WORDS), dtype=np.uint32) if "X" in w else None
-    rc = lib().oz2o_dgemm_sub(m, n, k, _ptr(A), max(1, m), _ptr(B), max(1, k), int(N), int(mode), _ptr(mods_a),
+    rc = lib().oz2o_dgemm_sub(m, n, k, _ptr(A), max(1, m), _ptr(B), max(1, k), int(N), int(mode), int(delta), _ptr(mods_a),
                               nI, _ptr(I), nJ, _ptr(J), _ptr(C), _ptr(sa), _ptr(sb), _ptr(aps), _ptr(apm),
                               _ptr(bps), _ptr(bpm), _ptr(ares), _ptr(bres), _ptr(cprod), _ptr(cres),
                               _ptr(xs), _ptr(xm))

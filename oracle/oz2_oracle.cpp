@@ -35,6 +35,13 @@
 // Since P_ij <= min(R_i, C_j) <= sqrt(R_i C_j) <= 2^((t_i+t_j)/2), this gives
 //   (|A'||B'|)_ij <= 2^(sa_i+sb_j) 2^(e_i-5) P_ij 2^(f_j-5) <= 2^b <= M/2 - 1.
 // The maxima R_i and C_j run over ALL columns and rows, also when only a subset of outputs is asked for.
+// Unequal bit budgets (Section 3: "if the precisions of A and B differ ... k_A < k_B"): an integer delta moves
+// delta bits of budget from A to B.  delta = 0 is the paper's equal split in every mode.  For delta != 0:
+//   mode 0: k_A = kappa - delta, k_B = S - k_A with S = max{S : k 2^S <= M/2 - 1} (first budget equation; S is
+//           2 kappa or 2 kappa + 1, so B also gets the odd bit);
+//   mode 1: 2^sa_i nu_i <= 2^(beta - delta), 2^sb_j nu_j <= 2^(b - beta + delta), b = max{b : 2^b <= M/2 - 1};
+//   mode 2: sa_i is lowered and sb_j raised by delta.
+// In every case the product of the two bounds is unchanged or smaller than M/2 - 1 allows.
 // The moduli are the greedy descending pairwise-coprime sequence starting at 256 (Section 3.1 asks for
 // the largest possible pairwise-coprime values not above 256); a caller may pass any other list, e.g. the
 // sixteen values the paper prints.
@@ -250,6 +257,24 @@ int kappa_of(const BigU& M, int64_t k) {
   return kappa;
 }
 
+// Section 3, first bit-budget equation: the largest S = k_A + k_B with k * 2^S <= M/2 - 1 (-1 if none).
+int kappa_sum_of(const BigU& M, int64_t k) {
+  BigU half = shr1(M);
+  if (is_zero(half)) return -1;
+  BigU lim = sub(half, BigU(1));
+  BigU v((uint64_t)k);
+  if (cmp(v, lim) > 0) return -1;
+  int S = 0;
+  for (;;) {
+    if (bit_length(v) + 1 >= 32 * WORDS - 1) break;
+    BigU nxt = shl1(v);
+    if (cmp(nxt, lim) > 0) break;
+    v = nxt;
+    ++S;
+  }
+  return S;
+}
+
 // ---------------------------------------------------------------------------------------------
 // FP64 decomposition: |x| = mant * 2^ex exactly, mant < 2^53 (mant = 0 for x = 0).
 // ---------------------------------------------------------------------------------------------
@@ -426,6 +451,12 @@ int oz2o_log2_budget(int N, const int* moduli) {
   return log2_budget(product(N, moduli));
 }
 
+// S = k_A + k_B of the first bit-budget equation of Section 3: largest S with k * 2^S <= M/2 - 1 (-1 if none).
+int oz2o_kappa_sum(int N, const int* moduli, int64_t k) {
+  if (N < 1 || N > 28 || k < 1) return -1;
+  return kappa_sum_of(product(N, moduli), k);
+}
+
 // beta of the Cauchy-Schwarz variant for a moduli list: largest beta with 4^beta <= M/2 - 1.
 int oz2o_beta(int N, const int* moduli) {
   if (N < 1 || N > 28) return -1;
@@ -486,7 +517,8 @@ int oz2o_shifts(int which, int64_t rows, int64_t cols, const double* X, int64_t 
 //   X_sign[r + c*nI], X_mag[(r + c*nI)*WORDS + w]   the integer X
 // Returns 0, or a negative code for bad arguments, or 2 when kappa < 1.
 int oz2o_dgemm_sub(int64_t m, int64_t n, int64_t k, const double* A, int64_t lda, const double* B, int64_t ldb,
-                   int N, int mode, const int* moduli_in, int64_t nI, const int64_t* I, int64_t nJ, const int64_t* J,
+                   int N, int mode, int delta, const int* moduli_in, int64_t nI, const int64_t* I, int64_t nJ,
+                   const int64_t* J,
                    double* C_out, int32_t* sa_out, int32_t* sb_out, uint8_t* Ap_sign, uint32_t* Ap_mag,
                    uint8_t* Bp_sign, uint32_t* Bp_mag, int8_t* Ares, int8_t* Bres, int64_t* Cprod, uint8_t* Cres,
                    uint8_t* X_sign, uint32_t* X_mag) {
@@ -520,6 +552,13 @@ int oz2o_dgemm_sub(int64_t m, int64_t n, int64_t k, const double* A, int64_t lda
   if (mode == 1 && (beta < 1 || beta > 120)) return 2;
   const int budget = log2_budget(M);
   if (mode == 2 && (budget < 2 || budget > 240)) return 2;
+  // per-operand budgets (delta == 0: the equal split)
+  const int kappa_a = kappa - delta;
+  const int kappa_b = delta == 0 ? kappa : kappa_sum_of(M, k) - kappa_a;
+  const int beta_a = beta - delta;
+  const int beta_b = delta == 0 ? beta : budget - beta_a;
+  if (mode == 0 && (kappa_a < 1 || kappa_b < 1 || kappa_a > 120 || kappa_b > 120)) return 2;
+  if (mode == 1 && (beta_a < 1 || beta_b < 1 || beta_a > 120 || beta_b > 120)) return 2;
 
   // line 1: shifts
   std::vector<int32_t> sa(nI), sb(nJ);
@@ -550,7 +589,7 @@ int oz2o_dgemm_sub(int64_t m, int64_t n, int64_t k, const double* A, int64_t lda
         for (int64_t l = 0; l < k; ++l) acc += (uint64_t)a2[(size_t)i * k + l] * b2[(size_t)j * k + l];
         if (acc > R) R = acc;
       }
-      sa[r] = R == 0 ? 0 : floor_div2(budget - ceil_log2_u64(R)) - (ea[i] - 5);
+      sa[r] = R == 0 ? 0 : floor_div2(budget - ceil_log2_u64(R)) - delta - (ea[i] - 5);
     }
 #pragma omp parallel for schedule(static)
     for (int64_t c = 0; c < nJ; ++c) {
@@ -561,7 +600,7 @@ int oz2o_dgemm_sub(int64_t m, int64_t n, int64_t k, const double* A, int64_t lda
         for (int64_t l = 0; l < k; ++l) acc += (uint64_t)a2[(size_t)i * k + l] * b2[(size_t)j * k + l];
         if (acc > Cm) Cm = acc;
       }
-      sb[c] = Cm == 0 ? 0 : floor_div2(budget - ceil_log2_u64(Cm)) - (fb[j] - 5);
+      sb[c] = Cm == 0 ? 0 : floor_div2(budget - ceil_log2_u64(Cm)) + delta - (fb[j] - 5);
     }
   }
 #pragma omp parallel for schedule(static)
@@ -569,24 +608,24 @@ int oz2o_dgemm_sub(int64_t m, int64_t n, int64_t k, const double* A, int64_t lda
     if (mode == 2) continue;
     int64_t i = I ? I[r] : r;
     if (mode == 1) {
-      sa[r] = fast_shift(A + i, k, lda, beta);
+      sa[r] = fast_shift(A + i, k, lda, beta_a);
       continue;
     }
     double mx = 0.0;
     for (int64_t l = 0; l < k; ++l) mx = std::fmax(mx, std::fabs(A[i + l * lda]));
-    sa[r] = mx == 0.0 ? 0 : kappa - 1 - ilog2_abs(mx);
+    sa[r] = mx == 0.0 ? 0 : kappa_a - 1 - ilog2_abs(mx);
   }
 #pragma omp parallel for schedule(static)
   for (int64_t c = 0; c < nJ; ++c) {
     if (mode == 2) continue;
     int64_t j = J ? J[c] : c;
     if (mode == 1) {
-      sb[c] = fast_shift(B + j * ldb, k, 1, beta);
+      sb[c] = fast_shift(B + j * ldb, k, 1, beta_b);
       continue;
     }
     double mx = 0.0;
     for (int64_t l = 0; l < k; ++l) mx = std::fmax(mx, std::fabs(B[l + j * ldb]));
-    sb[c] = mx == 0.0 ? 0 : kappa - 1 - ilog2_abs(mx);
+    sb[c] = mx == 0.0 ? 0 : kappa_b - 1 - ilog2_abs(mx);
   }
   if (sa_out) std::memcpy(sa_out, sa.data(), sizeof(int32_t) * nI);
   if (sb_out) std::memcpy(sb_out, sb.data(), sizeof(int32_t) * nJ);

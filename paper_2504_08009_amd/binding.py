@@ -9,7 +9,7 @@ _lib = None
 SYMBOLS = [
     "oz2_init", "oz2_min_moduli", "oz2_moduli_for_bits", "oz2_max_moduli", "oz2_get_moduli", "oz2_workspace_bytes", "oz2_set_workspace",
     "oz2_workspace_layout", "oz2_dgemm", "oz2_dgemm_ex", "oz2_dsyrk", "oz2_dtrmm", "oz2_stage1_convert", "oz2_stage2_gemm", "oz2_stage3_crt",
-    "oz2_set_kblock", "oz2_set_shift_mode", "oz2_set_product_format", "oz2_set_nonfinite_check", "oz2_set_stage_events", "oz2_calibrate_mfma", "oz2_host_crt_element", "oz2_host_residues", "oz2_status_string",
+    "oz2_set_kblock", "oz2_set_shift_mode", "oz2_set_product_format", "oz2_set_bit_split", "oz2_set_nonfinite_check", "oz2_set_stage_events", "oz2_calibrate_mfma", "oz2_host_crt_element", "oz2_host_residues", "oz2_status_string",
 ]
 
 
@@ -44,6 +44,7 @@ def lib():
         L.oz2_set_shift_mode.argtypes = [ci]
         L.oz2_set_product_format.argtypes = [ci]
         L.oz2_set_nonfinite_check.argtypes = [ci]
+        L.oz2_set_bit_split.argtypes = [ci]
         L.oz2_set_stage_events.argtypes = [vp]
         L.oz2_calibrate_mfma.argtypes = [ci, ci, ci, vp, vp, vp]
         L.oz2_host_crt_element.argtypes = [ci, vp, vp]
@@ -122,6 +123,11 @@ OZ2_PRODUCT_INT32, OZ2_PRODUCT_RESIDUE_U8 = 0, 1
 def oz2_set_product_format(fmt):
     """0: INT32 products in the C planes; 1 (default): UINT8 residues written by the GEMM epilogue."""
     _check(lib().oz2_set_product_format(int(fmt)), "oz2_set_product_format")
+
+
+def oz2_set_bit_split(delta):
+    """Bits of budget moved from op(A) to op(B) (0: the equal split)."""
+    _check(lib().oz2_set_bit_split(int(delta)), "oz2_set_bit_split")
 
 
 def oz2_set_nonfinite_check(on):

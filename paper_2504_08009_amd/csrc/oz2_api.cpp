@@ -13,6 +13,7 @@ struct State {
   int64_t kblock = 65536;
   int shift_mode = 0;
   int nonfinite_check = 1;
+  int bit_split = 0;
   int product_format = OZ2_PRODUCT_RESIDUE_U8;
   hipEvent_t ev[4] = {nullptr, nullptr, nullptr, nullptr};
   bool ev_on = false;
@@ -54,6 +55,15 @@ int prepare(State& s, int64_t m, int64_t n, int64_t k, int N, const Oz2Plan** pl
   if (rc == 2 && (s.shift_mode == OZ2_SHIFT_MAX || (*plan)->beta < 1)) return OZ2_ERR_BUDGET;
   if (rc == 2) rc = 0;
   if (rc != 0) return -10;
+  // unequal budgets must leave at least one bit and at most 110 on each side
+  if (s.bit_split != 0) {
+    const Oz2Plan& p = **plan;
+    int a, b;
+    if (s.shift_mode == OZ2_SHIFT_MAX) { a = p.kappa - s.bit_split; b = p.kappa_sum - a; }
+    else if (s.shift_mode == OZ2_SHIFT_CAUCHY_SCHWARZ) { a = p.beta - s.bit_split; b = p.budget2 - a; }
+    else { a = p.budget2 / 2 - s.bit_split; b = p.budget2 / 2 + s.bit_split; }
+    if (a < 1 || b < 1 || a > 110 || b > 110) return OZ2_ERR_BUDGET;
+  }
   // the INT8 product of the 6-bit bounds must stay below 2^31
   if (s.shift_mode == OZ2_SHIFT_INT8_PRODUCT && (k + 63) / 64 * 64 >= ((int64_t)1 << 19)) return OZ2_ERR_BUDGET;
   oz2_make_layout(m, n, k, N, lay);
@@ -156,6 +166,14 @@ int oz2_set_nonfinite_check(int on) {
   return OZ2_OK;
 }
 
+int oz2_set_bit_split(int delta) {
+  if (delta < -100 || delta > 100) return -1;
+  State& s = state();
+  std::lock_guard<std::mutex> lock(s.mu);
+  s.bit_split = delta;
+  return OZ2_OK;
+}
+
 int oz2_set_product_format(int format) {
   if (format != OZ2_PRODUCT_INT32 && format != OZ2_PRODUCT_RESIDUE_U8) return -1;
   State& s = state();
@@ -190,7 +208,7 @@ int oz2_stage1_convert(int64_t m, int64_t n, int64_t k, const double* A, int64_t
   Oz2Layout lay;
   int rc = prepare(s, m, n, k, num_moduli, &plan, &lay);
   if (rc) return rc;
-  hipError_t e = oz2_launch_stage1(0, 0, m, n, k, A, lda, B, ldb, 0, 0, *plan, s.shift_mode, lay, s.ws,
+  hipError_t e = oz2_launch_stage1(0, 0, m, n, k, A, lda, B, ldb, 0, 0, *plan, s.shift_mode, s.bit_split, lay, s.ws,
                                    static_cast<hipStream_t>(stream));
   return e == hipSuccess ? OZ2_OK : OZ2_ERR_HIP;
 }
@@ -274,7 +292,9 @@ int oz2_dgemm_ex(char transa, char transb, int64_t m, int64_t n, int64_t k, doub
   if (rc) return rc;
   auto mark = [&](int i) { return !s.ev_on || hipEventRecord(s.ev[i], st) == hipSuccess; };
   if (!mark(0)) return OZ2_ERR_HIP;
-  if (oz2_launch_stage1(ta, tb, m, n, k, A, lda, B, ldb, 0, 0, *plan, s.shift_mode, lay, s.ws, st) != hipSuccess || !mark(1))
+  if (oz2_launch_stage1(ta, tb, m, n, k, A, lda, B, ldb, 0, 0, *plan, s.shift_mode, s.bit_split, lay, s.ws, st) !=
+          hipSuccess ||
+      !mark(1))
     return OZ2_ERR_HIP;
   if (oz2_launch_stage2(*plan, lay, s.ws, s.kblock, s.product_format, 0, OZ2_KRANGE_ALL, st) != hipSuccess || !mark(2))
     return OZ2_ERR_HIP;
@@ -320,7 +340,7 @@ int oz2_dsyrk(char uplo, char trans, int64_t n, int64_t k, double alpha, const d
   if (!mark(0)) return OZ2_ERR_HIP;
   // op(A) op(A)^T: the columns of the second operand are the rows of the first, so A is converted once and
   // its planes serve as both operands
-  if (oz2_launch_stage1(ta, 0, n, n, k, A, lda, nullptr, 0, 0, 0, *plan, s.shift_mode, lay, s.ws, st) != hipSuccess ||
+  if (oz2_launch_stage1(ta, 0, n, n, k, A, lda, nullptr, 0, 0, 0, *plan, s.shift_mode, 0, lay, s.ws, st) != hipSuccess ||
       !mark(1))
     return OZ2_ERR_HIP;
   if (oz2_launch_stage2(*plan, lay, s.ws, s.kblock, s.product_format, tri, OZ2_KRANGE_ALL, st) != hipSuccess || !mark(2))
@@ -377,7 +397,7 @@ int oz2_dtrmm(char side, char uplo, char transa, char diag, int64_t m, int64_t n
                           : (op_lower ? OZ2_KRANGE_FROM_COL : OZ2_KRANGE_UPTO_COL);
   auto mark = [&](int i) { return !s.ev_on || hipEventRecord(s.ev[i], st) == hipSuccess; };
   if (!mark(0)) return OZ2_ERR_HIP;
-  if (oz2_launch_stage1(tx, ty, m, n, ka, X, ldx, Y, ldy, trix, triy, *plan, s.shift_mode, lay, s.ws, st) != hipSuccess ||
+  if (oz2_launch_stage1(tx, ty, m, n, ka, X, ldx, Y, ldy, trix, triy, *plan, s.shift_mode, 0, lay, s.ws, st) != hipSuccess ||
       !mark(1))
     return OZ2_ERR_HIP;
   if (oz2_launch_stage2(*plan, lay, s.ws, s.kblock, s.product_format, 0, krange, st) != hipSuccess || !mark(2))
@@ -453,7 +473,7 @@ const char* oz2_status_string(int status) {
   switch (status) {
     case OZ2_OK: return "success";
     case OZ2_ERR_WORKSPACE: return "workspace not registered or too small";
-    case OZ2_ERR_BUDGET: return "moduli product too small for this inner dimension (kappa < 1)";
+    case OZ2_ERR_BUDGET: return "bit budget: moduli product too small for this inner dimension, or a bit split or shift mode it cannot serve";
     case OZ2_ERR_HIP: return "HIP call failed";
     default: return status < 0 ? "invalid argument" : "unknown status";
   }

@@ -130,6 +130,18 @@ int oz2_table_kappa(int N, int64_t k) {
   return (bits - 1) / 2;  // largest kappa with 4^kappa <= floor((M/2-1)/k)
 }
 
+// largest S with k * 2^S <= M/2 - 1 (-1 if there is none): k_A + k_B of Section 3
+int oz2_table_kappa_sum(int N, int64_t k) {
+  if (N < 1 || N > kTableLen || k < 1) return -1;
+  int tab[kTableLen];
+  build_table(tab);
+  Wide lim = product_of(tab, N);
+  wide_divmod(lim, 2);
+  wide_sub_one(lim);
+  wide_divmod(lim, (uint64_t)k);  // floor((M/2-1)/k)
+  return wide_bits(lim) - 1;
+}
+
 // largest b with 2^b <= M/2 - 1 (-1 if there is none); the largest beta with 4^beta <= M/2 - 1 is floor(b/2)
 static int table_budget2(const int* moduli, int N) {
   Wide lim = product_of(moduli, N);
@@ -144,6 +156,7 @@ int oz2_build_plan(int N, int64_t k, Oz2Plan* plan) {
   plan->N = N;
   oz2_table_moduli(N, plan->moduli);
   plan->kappa = oz2_table_kappa(N, k);
+  plan->kappa_sum = oz2_table_kappa_sum(N, k);
   plan->budget2 = table_budget2(plan->moduli, N);
   plan->beta = plan->budget2 < 0 ? -1 : plan->budget2 / 2;
 

@@ -46,6 +46,7 @@ struct Oz2Plan {
   int kappa;
   int beta;     // largest beta with 4^beta <= M/2 - 1 (Cauchy-Schwarz shift mode)
   int budget2;  // largest b with 2^b <= M/2 - 1 (INT8-product shift mode)
+  int kappa_sum;  // largest S with k * 2^S <= M/2 - 1 (Section 3, first budget equation); 2 kappa or 2 kappa + 1
   int moduli[OZ2_MAX_N];
   Oz2ConvConsts conv;
   Oz2CrtConsts crt;
@@ -55,6 +56,7 @@ struct Oz2Plan {
 int oz2_build_plan(int N, int64_t k, Oz2Plan* plan);
 int oz2_table_moduli(int N, int* out);
 int oz2_table_kappa(int N, int64_t k);
+int oz2_table_kappa_sum(int N, int64_t k);
 
 struct Oz2Layout {
   int64_t m_pad, n_pad, k_pad;
@@ -65,7 +67,7 @@ void oz2_make_layout(int64_t m, int64_t n, int64_t k, int N, Oz2Layout* lay);
 // Kernel launchers.  Each returns hipSuccess or the launch error.
 hipError_t oz2_launch_stage1(int transa, int transb, int64_t m, int64_t n, int64_t k, const double* A, int64_t lda,
                              const double* B, int64_t ldb, int tri_a, int tri_b, const Oz2Plan& plan, int shift_mode,
-                             const Oz2Layout& lay, char* ws, hipStream_t st);
+                             int bit_split, const Oz2Layout& lay, char* ws, hipStream_t st);
 // One-time device set-up of the GEMM kernels (function attributes, compute-unit count); also done lazily by the
 // first launch.
 hipError_t oz2_gemm_setup();

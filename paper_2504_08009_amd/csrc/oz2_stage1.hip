@@ -178,19 +178,24 @@ __global__ void __launch_bounds__(kThreads) colnorm_kernel(const double* __restr
 //   mode 2 (INT8 product):    floor((b2 - t)/2) - (e - 5), t = min{t : 2^t >= v}, v = largest element of the bound
 //                             product in the vector's row / column      (param = b2)
 // An all-zero vector gets shift 0.
+// With unequal bit budgets (Section 3: k_A != k_B when the operands differ in precision) each operand has its
+// own param (modes 0, 1) or an offset added at the end (mode 2).
 struct ShiftJob {
   const unsigned long long* mx;
   const unsigned long long* aux;
   int* s;
   int64_t count;
+  int param;
+  int offset;
 };
-__global__ void __launch_bounds__(kThreads) shifts_kernel(const ShiftJob ja, const ShiftJob jb, int mode, int param) {
+__global__ void __launch_bounds__(kThreads) shifts_kernel(const ShiftJob ja, const ShiftJob jb, int mode) {
   int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
   const bool first = i < ja.count;
   const ShiftJob& j = first ? ja : jb;
   if (!first) i -= ja.count;
   if (i >= j.count) return;
   const unsigned long long b = j.mx[i];
+  const int param = j.param;
   int out = 0;
   if (b) {
     const int e = exponent_of_bits(b);
@@ -205,7 +210,7 @@ __global__ void __launch_bounds__(kThreads) shifts_kernel(const ShiftJob ja, con
       if (R) {
         const int t = R <= 1 ? 0 : 64 - __clzll((long long)(R - 1));
         const int d = param - t;
-        out = (d >= 0 ? d / 2 : -((1 - d) / 2)) - (e - 5);
+        out = (d >= 0 ? d / 2 : -((1 - d) / 2)) + j.offset - (e - 5);
       }
     }
   }
@@ -455,7 +460,7 @@ void launch_convert(const Operand& o, int kind, const Oz2ConvConsts& conv, hipSt
 // tri_a / tri_b: triangular structure of the stored arrays (0 = full; see tri_value).
 hipError_t oz2_launch_stage1(int transa, int transb, int64_t m, int64_t n, int64_t k, const double* A, int64_t lda,
                              const double* B, int64_t ldb, int tri_a, int tri_b, const Oz2Plan& plan, int shift_mode,
-                             const Oz2Layout& lay, char* ws, hipStream_t st) {
+                             int bit_split, const Oz2Layout& lay, char* ws, hipStream_t st) {
   // rows of op(A): strided in a stored m x k matrix, contiguous in a stored k x m matrix;
   // columns of op(B): contiguous in a stored k x n matrix, strided in a stored n x k matrix
   // Row maxima, flag words and column maxima are adjacent, and so are the two auxiliary vectors: one fill
@@ -478,20 +483,23 @@ hipError_t oz2_launch_stage1(int transa, int transb, int64_t m, int64_t n, int64
   auto fill = [&](unsigned long long* p, int64_t count) {
     hipLaunchKernelGGL(fill_u64_kernel, dim3(blocks_of(count, kThreads)), thr, 0, st, p, count);
   };
-  auto shifts = [&](int mode, int param) {
-    const ShiftJob ja = {ops[0].vmax, ops[0].vaux, ops[0].shifts, ops[0].nvec_pad};
-    const ShiftJob jb = {ops[1].vmax, ops[1].vaux, ops[1].shifts, nops == 2 ? ops[1].nvec_pad : 0};
-    hipLaunchKernelGGL(shifts_kernel, dim3(blocks_of(ja.count + jb.count, kThreads)), thr, 0, st, ja, jb, mode, param);
+  auto shifts = [&](int mode, int param_a, int param_b, int off_a, int off_b) {
+    const ShiftJob ja = {ops[0].vmax, ops[0].vaux, ops[0].shifts, ops[0].nvec_pad, param_a, off_a};
+    const ShiftJob jb = {ops[1].vmax, ops[1].vaux, ops[1].shifts, nops == 2 ? ops[1].nvec_pad : 0, param_b, off_b};
+    hipLaunchKernelGGL(shifts_kernel, dim3(blocks_of(ja.count + jb.count, kThreads)), thr, 0, st, ja, jb, mode);
   };
   Oz2ConvConsts conv = plan.conv;
-  int xbits;  // |x'| < 2^xbits decides how deep the conversion kernels split an element
+  // Budgets per operand: bit_split moves that many bits from the first operand to the second, which also gets
+  // the odd bit of the sum (bit_split == 0: the equal split; the symmetric product always uses it).
+  const int d = bit_split;
+  int xbits[2];  // |x'| < 2^xbits decides how deep the conversion kernels split an element
   fill(ops[0].vmax, n_max);
   for (int x = 0; x < nops; ++x) launch_max(ops[x], st);
   if (shift_mode == OZ2_SHIFT_INT8_PRODUCT) {
     // bound planes (in the slots of residue plane 0), their INT8 product (in the slot of product plane 0),
     // its row and column maxima, then the shifts.  In the symmetric case the product is A''A''^T and its
     // row maxima are its column maxima (those land in the unused column array).
-    shifts(0, 6);  // exponents 5 - e of the bounds
+    shifts(0, 6, 6, 0, 0);  // exponents 5 - e of the bounds
     for (int x = 0; x < nops; ++x) launch_convert(ops[x], 2, conv, st);
     fill(ops[0].vaux, n_aux);
     hipError_t e = oz2_launch_bound_gemm(lay, ws, B == nullptr, st);
@@ -501,19 +509,26 @@ hipError_t oz2_launch_stage1(int transa, int transb, int64_t m, int64_t n, int64
     if (nblk >= ((int64_t)1 << 31)) return hipErrorInvalidValue;
     hipLaunchKernelGGL(prodmax_kernel, dim3((unsigned)nblk), thr, 0, st, reinterpret_cast<const int*>(ws + lay.off_c),
                        lay.m_pad, m, n, row_blocks, ops[0].vaux, ops[1].vaux);
-    shifts(2, plan.budget2);
-    xbits = plan.budget2 / 2 + 7;  // |x'| < 2^(e + 1 + sa) <= 2^(floor(b/2) + 6)
+    shifts(2, plan.budget2, plan.budget2, -d, d);
+    xbits[0] = plan.budget2 / 2 + 7 - d;  // |x'| < 2^(e + 1 + sa) <= 2^(floor(b/2) + 6 -+ d)
+    xbits[1] = plan.budget2 / 2 + 7 + d;
   } else if (shift_mode == OZ2_SHIFT_CAUCHY_SCHWARZ) {
     fill(ops[0].vaux, n_aux);
     for (int x = 0; x < nops; ++x) launch_norm(ops[x], st);
-    shifts(1, plan.beta);
-    xbits = plan.beta + 1;
+    const int beta_a = plan.beta - d, beta_b = d == 0 ? plan.beta : plan.budget2 - beta_a;
+    shifts(1, beta_a, beta_b, 0, 0);
+    xbits[0] = beta_a + 1;
+    xbits[1] = beta_b + 1;
   } else {
-    shifts(0, plan.kappa);
-    xbits = plan.kappa;
+    const int kappa_a = plan.kappa - d, kappa_b = d == 0 ? plan.kappa : plan.kappa_sum - kappa_a;
+    shifts(0, kappa_a, kappa_b, 0, 0);
+    xbits[0] = kappa_a;
+    xbits[1] = kappa_b;
   }
-  conv.two_level = xbits > 75;
-  for (int x = 0; x < nops; ++x) launch_convert(ops[x], conv.two_level ? 1 : 0, conv, st);
+  for (int x = 0; x < nops; ++x) {
+    conv.two_level = xbits[x] > 75;
+    launch_convert(ops[x], conv.two_level ? 1 : 0, conv, st);
+  }
   return hipGetLastError();
 }
 

@@ -19,7 +19,7 @@ def _dev(x):
     return torch.from_numpy(np.ascontiguousarray(x.T)).cuda().t()
 
 
-def run_stages(A, B, N, kblock=None, mode=0, fmt=0):
+def run_stages(A, B, N, kblock=None, mode=0, fmt=0, delta=0):
     m, k = A.shape
     _, n = B.shape
     ws = oz.Workspace(m, n, k, N)
@@ -30,8 +30,9 @@ def run_stages(A, B, N, kblock=None, mode=0, fmt=0):
         oz.oz2_set_kblock(kblock)
     oz.oz2_set_shift_mode(mode)
     oz.oz2_set_product_format(fmt)
+    oz.oz2_set_bit_split(delta)
     try:
-        print("stage1 m=%d n=%d k=%d N=%d mode=%d fmt=%d" % (m, n, k, N, mode, fmt), flush=True)
+        print("stage1 m=%d n=%d k=%d N=%d mode=%d fmt=%d delta=%d" % (m, n, k, N, mode, fmt, delta), flush=True)
         oz.oz2_stage1_convert(m, n, k, dA.data_ptr(), m, dB.data_ptr(), k, N)
         torch.cuda.synchronize()
         print("stage2", flush=True)
@@ -43,6 +44,7 @@ def run_stages(A, B, N, kblock=None, mode=0, fmt=0):
     finally:
         oz.oz2_set_shift_mode(0)
         oz.oz2_set_product_format(1)
+        oz.oz2_set_bit_split(0)
         if kblock is not None:
             oz.oz2_set_kblock(65536)
     mp, np_, kp = lay["m_pad"], lay["n_pad"], lay["k_pad"]
@@ -64,13 +66,13 @@ def run_stages(A, B, N, kblock=None, mode=0, fmt=0):
     return out
 
 
-def check_against_oracle(A, B, N, kblock=None, products_exact=True, mode=0, fmt=0):
+def check_against_oracle(A, B, N, kblock=None, products_exact=True, mode=0, fmt=0, delta=0):
     """fmt 0: INT32 product planes (compared with the exact products); fmt 1: UINT8 residue planes written by
     the GEMM epilogue (compared with the oracle's residues of line 7)."""
     m, k = A.shape
     _, n = B.shape
-    got = run_stages(A, B, N, kblock, mode, fmt)
-    ref = orc.dgemm(A, B, N, want=("C", "shifts", "Ares", "Bres", "Cprod", "Cres"), mode=mode)
+    got = run_stages(A, B, N, kblock, mode, fmt, delta)
+    ref = orc.dgemm(A, B, N, want=("C", "shifts", "Ares", "Bres", "Cprod", "Cres"), mode=mode, delta=delta)
     assert np.array_equal(got["sa"][:m], ref.sa), "row shifts"
     assert np.array_equal(got["sb"][:n], ref.sb), "column shifts"
     assert np.array_equal(got["Ap"][:, :m, :k], ref.Ares), "A residue planes"
@@ -786,4 +788,33 @@ def test_dsyrk_and_dtrmm_at_4096_sampled():
     got = dB[drows][:, dcols].cpu().numpy()
     ref = orc.dgemm(B, T, N, rows=rows, cols=cols).C
     assert np.array_equal(got, ref)
+    del ws
+
+
+# ------------------------------------------------------------------ unequal bit budgets
+@pytest.mark.parametrize("mode", [0, 1, 2])
+@pytest.mark.parametrize("N,delta", [(12, 8), (12, -5), (15, 1), (26, 8)])
+def test_unequal_bit_budgets_all_stages(mode, N, delta):
+    rng = np.random.default_rng(61 + N)
+    m, n, k = 300, 200, 333
+    A = (rng.random((m, k)) - 0.5) * np.exp(rng.standard_normal((m, k)))
+    B = (rng.random((k, n)) - 0.5) * np.exp(rng.standard_normal((k, n)))
+    A[3, :] = 0.0
+    check_against_oracle(A, B, N, mode=mode, delta=delta)
+
+
+def test_bit_split_out_of_budget_is_refused():
+    m = n = k = 64
+    ws = oz.Workspace(m, n, k, 4)
+    dX = torch.zeros((64, 64), dtype=torch.float64, device="cuda")
+    kap = orc.kappa(4, k)
+    oz.oz2_set_bit_split(kap)           # k_A = 0
+    try:
+        assert oz.lib().oz2_stage1_convert(m, n, k, dX.data_ptr(), m, dX.data_ptr(), k, 4, None) == 2
+        oz.oz2_set_bit_split(kap - 1)   # k_A = 1
+        assert oz.lib().oz2_stage1_convert(m, n, k, dX.data_ptr(), m, dX.data_ptr(), k, 4, None) == 0
+        torch.cuda.synchronize()
+    finally:
+        oz.oz2_set_bit_split(0)
+    assert oz.lib().oz2_set_bit_split(101) == -1
     del ws

@@ -604,3 +604,59 @@ def test_triangular_product_reads_one_triangle_and_is_exact_on_integers():
                     got = orc.dtrmm(side, uplo, transa, diag, -3.0, G, B, 10)
                     assert got.tolist() == [[float(v) for v in row] for row in want]
     assert np.array_equal(orc.dtrmm("L", "U", "N", "N", 0.0, np.full((m, m), np.nan), B, 10), np.zeros((m, n)))
+
+
+# ------------------------------------------------------------------ Section 3: unequal bit budgets k_A != k_B
+@pytest.mark.parametrize("N,k,delta", [(8, 9, 3), (8, 9, -5), (13, 9, 7), (14, 1024, 10), (5, 3, 1)])
+def test_unequal_bit_budgets_keep_the_premise_and_use_the_whole_sum(N, k, delta):
+    m, n = 5, 4
+    A, B = _tiny(900 + N, m, n, k, 1.0)
+    mods = orc.moduli(N)
+    M = math.prod(mods)
+    S, kap = orc.kappa_sum(N, k), orc.kappa(N, k)
+    assert k * 2**S <= M // 2 - 1 < k * 2 ** (S + 1) and S in (2 * kap, 2 * kap + 1)
+    ka, kb = kap - delta, S - (kap - delta)
+    r = orc.dgemm(A, B, N, delta=delta, want=("C", "shifts", "Ap", "Bp", "X"))
+    for i in range(m):
+        assert 2 ** (ka - 1) <= max(abs(v) for v in r.Ap[i]) < 2**ka
+    for j in range(n):
+        assert 2 ** (kb - 1) <= max(abs(r.Bp[l][j]) for l in range(k)) < 2**kb
+    for i in range(m):
+        for j in range(n):
+            assert sum(abs(r.Ap[i][l]) * abs(r.Bp[l][j]) for l in range(k)) <= M // 2 - 1
+            ex = sum(r.Ap[i][l] * r.Bp[l][j] for l in range(k))
+            assert r.X[i][j] == ex
+            assert r.C[i, j] == float(Fraction(ex) / Fraction(2) ** (int(r.sa[i]) + int(r.sb[j])))
+    # the other two shift selections: the premise holds for the same delta
+    for mode in (1, 2):
+        q = orc.dgemm(A, B, N, mode=mode, delta=delta, want=("shifts", "Ap", "Bp", "X"))
+        z = orc.dgemm(A, B, N, mode=mode, want=("shifts",))
+        assert np.array_equal(q.sa, z.sa - delta) and np.all(q.sb >= z.sb + delta) and np.all(q.sb <= z.sb + delta + 1)
+        for i in range(m):
+            for j in range(n):
+                assert sum(abs(q.Ap[i][l]) * abs(q.Bp[l][j]) for l in range(k)) <= M // 2 - 1
+                assert q.X[i][j] == sum(q.Ap[i][l] * q.Bp[l][j] for l in range(k))
+
+
+def test_unequal_bit_budgets_serve_operands_of_different_precision():
+    # A holds single-precision values within one binade per row (24 significant bits, no spread), B full doubles:
+    # A needs 25 bits of budget and no more, so moving the rest to B gives with 12 moduli the accuracy that the
+    # equal split only reaches with more moduli.  (With a wide spread inside the rows of A the truncation of its
+    # small entries costs 2^-k_A of the row maximum whatever their own precision, and the equal split is best.)
+    m, n, k = 64, 48, 256
+    rng = np.random.default_rng(5)
+    A = (np.where(rng.random((m, k)) < 0.5, -1.0, 1.0) * (0.5 + 0.5 * rng.random((m, k)))).astype(np.float32).astype(np.float64)
+    B = (rng.random((k, n)) - 0.5) * np.exp(0.5 * rng.standard_normal((k, n)))
+    Cx, S = orc.exact(A, B)
+    err = lambda C: np.max(np.abs(C - Cx) / S)
+    kap = orc.kappa(12, k)
+    assert kap - 8 >= 25
+    e_equal = err(orc.dgemm(A, B, 12).C)
+    e_split = err(orc.dgemm(A, B, 12, delta=8).C)
+    e_more = err(orc.dgemm(A, B, 14).C)
+    assert e_split < e_equal / 50 and e_split < 4 * e_more
+    # A is not truncated at all with this budget
+    r = orc.dgemm(A[:4], B[:, :3], 12, delta=8, want=("shifts", "Ap"))
+    for i in range(4):
+        for l in range(k):
+            assert Fraction(r.Ap[i][l]) == Fraction(float(A[i, l])) * Fraction(2) ** int(r.sa[i])
