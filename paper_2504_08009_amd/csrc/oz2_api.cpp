@@ -226,7 +226,7 @@ int oz2_stage2_gemm(int64_t m, int64_t n, int64_t k, int num_moduli, void* strea
   Oz2Layout lay;
   int rc = prepare(s, m, n, k, num_moduli, &plan, &lay);
   if (rc) return rc;
-  hipError_t e = oz2_launch_stage2(*plan, lay, s.ws, s.kblock, s.product_format, 0, OZ2_KRANGE_ALL, static_cast<hipStream_t>(stream));
+  hipError_t e = oz2_launch_stage2(*plan, lay, s.ws, s.kblock, s.product_format, 0, OZ2_KRANGE_ALL, 0, static_cast<hipStream_t>(stream));
   return e == hipSuccess ? OZ2_OK : OZ2_ERR_HIP;
 }
 
@@ -296,7 +296,8 @@ int oz2_dgemm_ex(char transa, char transb, int64_t m, int64_t n, int64_t k, doub
           hipSuccess ||
       !mark(1))
     return OZ2_ERR_HIP;
-  if (oz2_launch_stage2(*plan, lay, s.ws, s.kblock, s.product_format, 0, OZ2_KRANGE_ALL, st) != hipSuccess || !mark(2))
+  if (oz2_launch_stage2(*plan, lay, s.ws, s.kblock, s.product_format, 0, OZ2_KRANGE_ALL, s.nonfinite_check, st) != hipSuccess ||
+      !mark(2))
     return OZ2_ERR_HIP;
   if (oz2_launch_stage3(m, n, alpha, beta, C, ldc, *plan, lay, s.ws, s.product_format, s.nonfinite_check, 0, st) !=
           hipSuccess ||
@@ -343,7 +344,8 @@ int oz2_dsyrk(char uplo, char trans, int64_t n, int64_t k, double alpha, const d
   if (oz2_launch_stage1(ta, 0, n, n, k, A, lda, nullptr, 0, 0, 0, *plan, s.shift_mode, 0, lay, s.ws, st) != hipSuccess ||
       !mark(1))
     return OZ2_ERR_HIP;
-  if (oz2_launch_stage2(*plan, lay, s.ws, s.kblock, s.product_format, tri, OZ2_KRANGE_ALL, st) != hipSuccess || !mark(2))
+  if (oz2_launch_stage2(*plan, lay, s.ws, s.kblock, s.product_format, tri, OZ2_KRANGE_ALL, s.nonfinite_check, st) != hipSuccess ||
+      !mark(2))
     return OZ2_ERR_HIP;
   if (oz2_launch_stage3(n, n, alpha, beta, C, ldc, *plan, lay, s.ws, s.product_format, s.nonfinite_check, tri, st) !=
           hipSuccess ||
@@ -400,7 +402,7 @@ int oz2_dtrmm(char side, char uplo, char transa, char diag, int64_t m, int64_t n
   if (oz2_launch_stage1(tx, ty, m, n, ka, X, ldx, Y, ldy, trix, triy, *plan, s.shift_mode, 0, lay, s.ws, st) != hipSuccess ||
       !mark(1))
     return OZ2_ERR_HIP;
-  if (oz2_launch_stage2(*plan, lay, s.ws, s.kblock, s.product_format, 0, krange, st) != hipSuccess || !mark(2))
+  if (oz2_launch_stage2(*plan, lay, s.ws, s.kblock, s.product_format, 0, krange, s.nonfinite_check, st) != hipSuccess || !mark(2))
     return OZ2_ERR_HIP;
   // B is overwritten: stage 1 has read all of it by now (stream order)
   if (oz2_launch_stage3(m, n, alpha, 0.0, B, ldb, *plan, lay, s.ws, s.product_format, s.nonfinite_check, 0, st) !=

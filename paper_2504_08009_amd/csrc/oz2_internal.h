@@ -81,10 +81,11 @@ hipError_t oz2_gemm_setup();
 #define OZ2_KRANGE_FROM_COL 3
 #define OZ2_KRANGE_UPTO_COL 4
 
+// check_flag != 0: return at once on the device when stage 1 found a non-finite input.
 // triangle: 0 = general product; 1 / 2 = symmetric product op(A) op(A)^T (B's planes are A's), only the tiles of
 // the lower / upper triangle are computed
 hipError_t oz2_launch_stage2(const Oz2Plan& plan, const Oz2Layout& lay, char* ws, int64_t kblock, int residue_u8,
-                             int triangle, int krange, hipStream_t st);
+                             int triangle, int krange, int check_flag, hipStream_t st);
 // P = A''B'' of the INT8-product shift mode: bound planes in the slots of residue plane 0 -> INT32 in the slot of
 // product plane 0.  Exact for k_pad * 64 * 64 < 2^31.
 hipError_t oz2_launch_bound_gemm(const Oz2Layout& lay, char* ws, bool symmetric, hipStream_t st);

@@ -71,6 +71,7 @@ struct GemmArgs {
   int ktiles_per_block;    // k-tiles between modular reductions of the accumulators
   int triangle;            // 0: all tiles; 1: only tiles with tm >= tn (lower); 2: only tm <= tn (upper)
   int krange;              // triangular operand: which k-tiles of a tile can be nonzero (see OZ2_KRANGE_*)
+  const unsigned long long* skip_flag;  // if not null and nonzero on the device: the products are not needed
   float p[OZ2_MAX_N];
 };
 
@@ -185,6 +186,9 @@ __device__ __forceinline__ Tile decode_tile(const GemmArgs& g, int slot, int wv)
 template <bool RESIDUE_U8>
 __global__ void __launch_bounds__(kThreads) gemm_i8_kernel(const GemmArgs g) {
   extern __shared__ __attribute__((aligned(1024))) char lds[];
+
+  // stage 1 found an infinity or a NaN: the FP64 fallback forms C, these products would be thrown away
+  if (g.skip_flag != nullptr && *g.skip_flag != 0ull) return;
 
   const int lane = threadIdx.x & 63;
   const int wv = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -432,7 +436,7 @@ hipError_t gemm_setup() {
 // num_moduli planes of A' (off_a) times planes of B' (off_b) -> planes of C' (off_c)
 // b_is_a: the second operand's planes are the first operand's (symmetric product; m_pad == n_pad)
 hipError_t launch_gemm(const Oz2Layout& lay, char* ws, int num_moduli, const int* moduli, int64_t kblock, int residue_u8,
-                       int triangle, int krange, bool b_is_a, hipStream_t st) {
+                       int triangle, int krange, bool b_is_a, bool check_flag, hipStream_t st) {
   hipError_t e = gemm_setup();
   if (e != hipSuccess) return e;
   GemmArgs g;
@@ -441,6 +445,7 @@ hipError_t launch_gemm(const Oz2Layout& lay, char* ws, int num_moduli, const int
   if (b_is_a && lay.m_pad != lay.n_pad) return hipErrorInvalidValue;
   g.triangle = triangle;
   g.krange = krange;
+  g.skip_flag = check_flag ? reinterpret_cast<const unsigned long long*>(ws + lay.off_flags) : nullptr;
   g.c = reinterpret_cast<int*>(ws + lay.off_c);
   g.m_pad = lay.m_pad;
   g.n_pad = lay.n_pad;
@@ -475,13 +480,13 @@ hipError_t launch_gemm(const Oz2Layout& lay, char* ws, int num_moduli, const int
 hipError_t oz2_gemm_setup() { return gemm_setup(); }
 
 hipError_t oz2_launch_stage2(const Oz2Plan& plan, const Oz2Layout& lay, char* ws, int64_t kblock, int residue_u8,
-                             int triangle, int krange, hipStream_t st) {
-  return launch_gemm(lay, ws, plan.N, plan.moduli, kblock, residue_u8, triangle, krange, triangle != 0, st);
+                             int triangle, int krange, int check_flag, hipStream_t st) {
+  return launch_gemm(lay, ws, plan.N, plan.moduli, kblock, residue_u8, triangle, krange, triangle != 0, check_flag != 0, st);
 }
 
 // One plain INT8 product with INT32 output and no modular reduction between k-blocks: the caller guarantees
 // k_pad * 64 * 64 < 2^31.
 hipError_t oz2_launch_bound_gemm(const Oz2Layout& lay, char* ws, bool symmetric, hipStream_t st) {
   const int one = 1;
-  return launch_gemm(lay, ws, 1, &one, lay.k_pad, 0, 0, OZ2_KRANGE_ALL, symmetric, st);
+  return launch_gemm(lay, ws, 1, &one, lay.k_pad, 0, 0, OZ2_KRANGE_ALL, symmetric, false, st);
 }
