@@ -67,11 +67,11 @@ def main():
     dA = torch.from_numpy(A.T).to(dev).t()   # A is column-major: A.T is a C-contiguous view
     dB = torch.from_numpy(B.T).to(dev).t()
     dC = torch.empty((n, m), dtype=torch.float64, device=dev).t()
-    ws = oz.Workspace(m, n, k, N, device=dev)
-    stream = torch.cuda.current_stream()
-    oz.oz2_set_shift_mode(args.shift_mode)
     fmt = args.product_format if args.product_format >= 0 else oz.OZ2_PRODUCT_RESIDUE_U8
     oz.oz2_set_product_format(fmt)
+    ws = oz.Workspace(m, n, k, N, device=dev, product_format=fmt)
+    stream = torch.cuda.current_stream()
+    oz.oz2_set_shift_mode(args.shift_mode)
 
     hip = ctypes.CDLL("libamdhip64.so")
     def new_event():
@@ -151,7 +151,8 @@ def main():
         "dtype": "int8", "data": "synthetic",
         "config": {"workload": "%s: m=%d n=%d k=%d phi=%g, %d moduli, seed %d" % (args.workload, m, n, k, phi, N, cfg["seed"]),
                    "num_moduli": N, "entry_point": "oz2_dgemm" + (" (HIP graph replay)" if args.graph else ""), "shift_mode": args.shift_mode,
-                   "product_format": "uint8 residues" if fmt == oz.OZ2_PRODUCT_RESIDUE_U8 else "int32", "host_input_generation_s": round(gen_s, 1)},
+                   "product_format": "uint8 residues" if fmt == oz.OZ2_PRODUCT_RESIDUE_U8 else "int32",
+                   "workspace_GiB": round(ws.nbytes / 2**30, 2), "host_input_generation_s": round(gen_s, 1)},
         "roofline": roofline, "stages": stages,
     }
 
@@ -196,7 +197,7 @@ def main():
         per_n = {}
         for Nx in (14, 15, 17, 18):
             del ws
-            ws = oz.Workspace(m, n, k, Nx, device=dev)
+            ws = oz.Workspace(m, n, k, Nx, device=dev, product_format=fmt)
             oz.oz2_dgemm(m, n, k, dA.data_ptr(), m, dB.data_ptr(), k, dC.data_ptr(), m, Nx, stream)
             torch.cuda.synchronize()
             t0 = time.perf_counter()
@@ -207,7 +208,7 @@ def main():
         per_n[str(N)] = round(tflops, 2)
         out["emulated_TFLOPS_per_num_moduli"] = dict(sorted(per_n.items()))
         del ws
-        ws = oz.Workspace(m, n, k, N, device=dev)
+        ws = oz.Workspace(m, n, k, N, device=dev, product_format=fmt)
         oz.oz2_dgemm(m, n, k, dA.data_ptr(), m, dB.data_ptr(), k, dC.data_ptr(), m, N, stream)
         torch.cuda.synchronize()
 
@@ -215,7 +216,7 @@ def main():
     # workload with 14 moduli in those modes
     if args.workload == "c4" and not args.no_context and args.shift_mode == 0 and not args.no_cpu_baseline and not args.mnk:
         del ws
-        ws = oz.Workspace(m, n, k, 14, device=dev)
+        ws = oz.Workspace(m, n, k, 14, device=dev, product_format=fmt)
         dC2 = torch.empty((n, m), dtype=torch.float64, device=dev).t()
         for mode, label in ((1, "cauchy_schwarz_mode_14_moduli"), (2, "int8_product_mode_14_moduli")):
             oz.oz2_set_shift_mode(mode)
@@ -235,7 +236,7 @@ def main():
         del ws
         # context: the symmetric rank-k update A A^T of the same A (half the conversion, about half the tiles);
         # TFLOPS counted with the flops of the full product so that it compares with the lines above
-        ws = oz.Workspace(m, m, k, N, device=dev)
+        ws = oz.Workspace(m, m, k, N, device=dev, product_format=fmt)
         dC2 = torch.zeros((m, m), dtype=torch.float64, device=dev).t()
         oz.oz2_dsyrk("L", "N", m, k, 1.0, dA.data_ptr(), m, 0.0, dC2.data_ptr(), m, N, stream)
         torch.cuda.synchronize()
@@ -261,7 +262,7 @@ def main():
                                                      "TFLOPS_as_full_product": round(2.0 * m * n * k / trmm_t / 1e12, 2)}
             del dB2
         del dC2, ws
-        ws = oz.Workspace(m, n, k, N, device=dev)
+        ws = oz.Workspace(m, n, k, N, device=dev, product_format=fmt)
 
     if args.calibrate_copy:
         tmp = torch.empty_like(dA)

@@ -66,14 +66,19 @@ int oz2_get_moduli(int num_moduli, int* moduli_out, int* kappa_out, int64_t k);
 int oz2_moduli_for_bits(int64_t k, int bits);
 
 /* Workspace size in bytes for a problem, 0 on invalid arguments.  Holds the shift vectors, the INT8
- * residue planes of A and B and the INT32 product planes (Algorithm 1, lines 1-6). */
+ * residue planes of A and B and the product planes (Algorithm 1, lines 1-7).  oz2_workspace_bytes is enough
+ * for either product format (it is the INT32 size); oz2_workspace_bytes_for gives the exact size for one
+ * format -- with OZ2_PRODUCT_RESIDUE_U8, the default, about half as much at large sizes (12 instead of 24 GiB at
+ * m = n = k = 16384 with 16 moduli).  Calls check the registered size against the format in force. */
 size_t oz2_workspace_bytes(int64_t m, int64_t n, int64_t k, int num_moduli);
+size_t oz2_workspace_bytes_for(int64_t m, int64_t n, int64_t k, int num_moduli, int product_format);
 
 /* Register a caller-owned device buffer (256-byte aligned) as the workspace for later calls.
  * NULL/0 unregisters.  Returns 0 or -1 (bad alignment or NULL with nonzero size). */
 int oz2_set_workspace(void* dev_ptr, size_t bytes);
 
-/* Where each intermediate lives inside the workspace, so that a test can read every stage's output.
+/* Where each intermediate lives inside the workspace for the product format in force, so that a test can read
+ * every stage's output.
  * offsets[0..9] (bytes from the workspace start):
  *   0 rowmax  : m_pad uint64, bit pattern of max_l |a_il| per row of A
  *   1 colmax  : n_pad uint64, same per column of B
@@ -86,7 +91,7 @@ int oz2_set_workspace(void* dev_ptr, size_t bytes);
  *               index j of B in the place of i and n_pad in the place of m_pad
  *   6 C planes: num_moduli x n_pad x m_pad, plane t element (i,j) at index ((t*n_pad)+j)*m_pad + i; the
  *               elements are int32 products (OZ2_PRODUCT_INT32) or uint8 residues in [0, p_t)
- *               (OZ2_PRODUCT_RESIDUE_U8, the planes then fill the first quarter of the region)
+ *               (OZ2_PRODUCT_RESIDUE_U8); the region holds at least 8 bytes per element of one plane
  *   7 rownorm : m_pad uint64, integer norm bound S_i of A's rows (Cauchy-Schwarz shift mode only)
  *   8 colnorm : n_pad uint64, same per column of B
  *   9 flags   : 32 uint64; word 0 is 1 after a stage 1 that found an infinity or a NaN in A or B, else 0

@@ -7,7 +7,7 @@ _LIB_PATH = os.path.join(_HERE, "liboz2.so")
 _lib = None
 
 SYMBOLS = [
-    "oz2_init", "oz2_min_moduli", "oz2_moduli_for_bits", "oz2_max_moduli", "oz2_get_moduli", "oz2_workspace_bytes", "oz2_set_workspace",
+    "oz2_init", "oz2_min_moduli", "oz2_moduli_for_bits", "oz2_max_moduli", "oz2_get_moduli", "oz2_workspace_bytes", "oz2_workspace_bytes_for", "oz2_set_workspace",
     "oz2_workspace_layout", "oz2_dgemm", "oz2_dgemm_ex", "oz2_dsyrk", "oz2_dtrmm", "oz2_stage1_convert", "oz2_stage2_gemm", "oz2_stage3_crt",
     "oz2_set_kblock", "oz2_set_shift_mode", "oz2_set_product_format", "oz2_set_bit_split", "oz2_set_nonfinite_check", "oz2_set_stage_events", "oz2_calibrate_mfma", "oz2_host_crt_element", "oz2_host_residues", "oz2_status_string",
 ]
@@ -29,6 +29,8 @@ def lib():
         L.oz2_moduli_for_bits.argtypes = [i64, ci]
         L.oz2_workspace_bytes.restype = ctypes.c_size_t
         L.oz2_workspace_bytes.argtypes = [i64, i64, i64, ci]
+        L.oz2_workspace_bytes_for.restype = ctypes.c_size_t
+        L.oz2_workspace_bytes_for.argtypes = [i64, i64, i64, ci, ci]
         L.oz2_set_workspace.argtypes = [vp, ctypes.c_size_t]
         L.oz2_workspace_layout.argtypes = [i64, i64, i64, ci, vp, vp]
         L.oz2_dgemm.argtypes = [i64, i64, i64, vp, i64, vp, i64, vp, i64, ci, vp]
@@ -76,8 +78,11 @@ def get_moduli(num_moduli, k=1):
     return list(mods), kap.value
 
 
-def workspace_bytes(m, n, k, num_moduli):
-    return int(lib().oz2_workspace_bytes(m, n, k, num_moduli))
+def workspace_bytes(m, n, k, num_moduli, product_format=None):
+    """Bytes that serve either product format (None), or exactly one of them."""
+    if product_format is None:
+        return int(lib().oz2_workspace_bytes(m, n, k, num_moduli))
+    return int(lib().oz2_workspace_bytes_for(m, n, k, num_moduli, int(product_format)))
 
 
 def oz2_init():
@@ -204,9 +209,9 @@ def host_residues(num_moduli, kappa, a, shift):
 class Workspace:
     """A torch-owned device buffer registered with the library (device memory only; no arithmetic)."""
 
-    def __init__(self, m, n, k, num_moduli, device="cuda:0"):
+    def __init__(self, m, n, k, num_moduli, device="cuda:0", product_format=None):
         import torch
-        self.nbytes = workspace_bytes(m, n, k, num_moduli)
+        self.nbytes = workspace_bytes(m, n, k, num_moduli, product_format)
         if self.nbytes == 0:
             raise Oz2Error("invalid problem for a workspace")
         self.buf = torch.empty(self.nbytes + 256, dtype=torch.uint8, device=device)

@@ -66,7 +66,7 @@ int prepare(State& s, int64_t m, int64_t n, int64_t k, int N, const Oz2Plan** pl
   }
   // the INT8 product of the 6-bit bounds must stay below 2^31
   if (s.shift_mode == OZ2_SHIFT_INT8_PRODUCT && (k + 63) / 64 * 64 >= ((int64_t)1 << 19)) return OZ2_ERR_BUDGET;
-  oz2_make_layout(m, n, k, N, lay);
+  oz2_make_layout(m, n, k, N, s.product_format == OZ2_PRODUCT_INT32 ? 4 : 1, lay);
   if (!s.ws || s.ws_bytes < lay->total) return OZ2_ERR_WORKSPACE;
   return OZ2_OK;
 }
@@ -100,11 +100,16 @@ int oz2_moduli_for_bits(int64_t k, int bits) {
   return 0;
 }
 
-size_t oz2_workspace_bytes(int64_t m, int64_t n, int64_t k, int num_moduli) {
+size_t oz2_workspace_bytes_for(int64_t m, int64_t n, int64_t k, int num_moduli, int product_format) {
   if (m < 0 || n < 0 || k < 0 || !n_ok(num_moduli) || !dims_ok(m, n, k)) return 0;
+  if (product_format != OZ2_PRODUCT_INT32 && product_format != OZ2_PRODUCT_RESIDUE_U8) return 0;
   Oz2Layout lay;
-  oz2_make_layout(m, n, k, num_moduli, &lay);
+  oz2_make_layout(m, n, k, num_moduli, product_format == OZ2_PRODUCT_INT32 ? 4 : 1, &lay);
   return lay.total;
+}
+
+size_t oz2_workspace_bytes(int64_t m, int64_t n, int64_t k, int num_moduli) {
+  return oz2_workspace_bytes_for(m, n, k, num_moduli, OZ2_PRODUCT_INT32);
 }
 
 int oz2_set_workspace(void* dev_ptr, size_t bytes) {
@@ -125,7 +130,11 @@ int oz2_workspace_layout(int64_t m, int64_t n, int64_t k, int num_moduli, size_t
   if (!offsets) return -5;
   if (!dims) return -6;
   Oz2Layout lay;
-  oz2_make_layout(m, n, k, num_moduli, &lay);
+  {
+    State& s = state();
+    std::lock_guard<std::mutex> lock(s.mu);
+    oz2_make_layout(m, n, k, num_moduli, s.product_format == OZ2_PRODUCT_INT32 ? 4 : 1, &lay);
+  }
   offsets[0] = lay.off_rowmax;
   offsets[1] = lay.off_colmax;
   offsets[2] = lay.off_sa;

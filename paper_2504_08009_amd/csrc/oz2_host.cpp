@@ -208,7 +208,10 @@ int oz2_build_plan(int N, int64_t k, Oz2Plan* plan) {
   return plan->kappa < 1 ? 2 : 0;  // 2: the simple bound of Section 3 leaves no bits for this k
 }
 
-void oz2_make_layout(int64_t m, int64_t n, int64_t k, int N, Oz2Layout* lay) {
+// c_elem_bytes: 4 for INT32 product planes, 1 for UINT8 residue planes.  The product region always holds at least
+// 8 bytes per element of the padded m x n grid: the INT32 product of the INT8-product shift mode and the FP64
+// staging buffer of the in-place triangular product live there.
+void oz2_make_layout(int64_t m, int64_t n, int64_t k, int N, int c_elem_bytes, Oz2Layout* lay) {
   auto up = [](int64_t v, int64_t a) { return (v + a - 1) / a * a; };
   auto up256 = [](size_t v) { return (v + 255) / 256 * 256; };
   lay->m_pad = up(m > 0 ? m : 1, OZ2_TILE_M);
@@ -230,7 +233,10 @@ void oz2_make_layout(int64_t m, int64_t n, int64_t k, int N, Oz2Layout* lay) {
   lay->off_b = off;
   off = up256(off + (size_t)N * lay->n_pad * lay->k_pad);
   lay->off_c = off;
-  off = up256(off + (size_t)N * lay->n_pad * lay->m_pad * 4);
+  {
+    const size_t per_elem = (size_t)N * c_elem_bytes > 8 ? (size_t)N * c_elem_bytes : 8;
+    off = up256(off + per_elem * lay->n_pad * lay->m_pad);
+  }
   lay->off_rownorm = off;
   off = up256(off + (size_t)lay->m_pad * 8);
   lay->off_colnorm = off;

@@ -62,7 +62,7 @@ struct Oz2Layout {
   int64_t m_pad, n_pad, k_pad;
   size_t off_rowmax, off_colmax, off_sa, off_sb, off_a, off_b, off_c, off_rownorm, off_colnorm, off_flags, total;
 };
-void oz2_make_layout(int64_t m, int64_t n, int64_t k, int N, Oz2Layout* lay);
+void oz2_make_layout(int64_t m, int64_t n, int64_t k, int N, int c_elem_bytes, Oz2Layout* lay);
 
 // Kernel launchers.  Each returns hipSuccess or the launch error.
 hipError_t oz2_launch_stage1(int transa, int transb, int64_t m, int64_t n, int64_t k, const double* A, int64_t lda,

@@ -85,18 +85,28 @@ def test_argument_validation_without_gpu():
 
 
 def test_workspace_layout_is_consistent():
-    for (m, n, k, N) in [(1, 1, 1, 2), (300, 200, 100, 3), (256, 256, 64, 14), (16384, 16384, 16384, 16)]:
-        lay = oz.workspace_layout(m, n, k, N)
-        mp, npad, kp = lay["m_pad"], lay["n_pad"], lay["k_pad"]
-        assert mp % 256 == 0 and npad % 256 == 0 and kp % 64 == 0
-        assert mp >= m and npad >= n and kp >= k and mp - m < 256 and kp - k < 64
-        order = ["rowmax", "flags", "colmax", "sa", "sb", "a_planes", "b_planes", "c_planes", "rownorm", "colnorm"]
-        sizes = [8 * mp, 256, 8 * npad, 4 * mp, 4 * npad, N * mp * kp, N * npad * kp, 4 * N * npad * mp, 8 * mp, 8 * npad]
-        for a, b, sz in zip(order, order[1:], sizes):
-            assert lay[a] % 256 == 0 and lay[a] + sz <= lay[b]
-        assert lay["flags"] == lay["rowmax"] + 8 * mp      # cleared by the same fill as the row maxima
-        assert lay["colnorm"] + sizes[-1] <= oz.workspace_bytes(m, n, k, N)
+    for fmt, bpe in ((oz.OZ2_PRODUCT_RESIDUE_U8, 1), (oz.OZ2_PRODUCT_INT32, 4)):
+        oz.oz2_set_product_format(fmt)
+        try:
+            for (m, n, k, N) in [(1, 1, 1, 2), (300, 200, 100, 3), (256, 256, 64, 14), (16384, 16384, 16384, 16)]:
+                lay = oz.workspace_layout(m, n, k, N)
+                mp, npad, kp = lay["m_pad"], lay["n_pad"], lay["k_pad"]
+                assert mp % 256 == 0 and npad % 256 == 0 and kp % 64 == 0
+                assert mp >= m and npad >= n and kp >= k and mp - m < 256 and kp - k < 64
+                order = ["rowmax", "flags", "colmax", "sa", "sb", "a_planes", "b_planes", "c_planes", "rownorm", "colnorm"]
+                # the product region: N planes of the format in force, and never less than 8 bytes per element
+                sizes = [8 * mp, 256, 8 * npad, 4 * mp, 4 * npad, N * mp * kp, N * npad * kp, max(bpe * N, 8) * npad * mp,
+                         8 * mp, 8 * npad]
+                for a, b, sz in zip(order, order[1:], sizes):
+                    assert lay[a] % 256 == 0 and lay[a] + sz <= lay[b]
+                assert lay["flags"] == lay["rowmax"] + 8 * mp      # cleared by the same fill as the row maxima
+                exact = oz.workspace_bytes(m, n, k, N, fmt)
+                assert lay["colnorm"] + sizes[-1] <= exact <= oz.workspace_bytes(m, n, k, N)
+        finally:
+            oz.oz2_set_product_format(oz.OZ2_PRODUCT_RESIDUE_U8)
     assert oz.workspace_bytes(16384, 16384, 16384, 16) < 25 * 2**30
+    assert oz.workspace_bytes(16384, 16384, 16384, 16, oz.OZ2_PRODUCT_RESIDUE_U8) < 13 * 2**30
+    assert oz.workspace_bytes(4, 4, 4, 4, 7) == 0
 
 
 # ----------------------------------------------------------------------------------------------
