@@ -10,6 +10,8 @@
 // All are bound by HBM traffic: 8 bytes read per element in 1a, 8 read + N written in 1b.
 // Infinities and NaNs are noticed in 1a (their bit patterns are above every finite magnitude) and recorded in
 // a flag word of the workspace.  Triangular operands (TRMM shape) are masked while they are read.
+// The maxima of both operands share one launch and so do their conversions (small problems are bound by the
+// number of launches); a block picks its operand and its kernel body by its index.
 #include "oz2_math.h"
 
 namespace {
@@ -41,12 +43,13 @@ __device__ __forceinline__ unsigned long long abs_bits(double v) {
 
 // A is m x k column-major: lanes run along rows (coalesced), each block covers 256 rows x KC columns.
 constexpr int kRowMaxKC = 128;
-__global__ void __launch_bounds__(kThreads) rowmax_kernel(const double* __restrict__ A, int64_t lda, int64_t m,
-                                                          int64_t k, unsigned long long* __restrict__ rowmax,
-                                                          unsigned long long* __restrict__ nonfinite, int tri) {
-  int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+__device__ __forceinline__ void strided_max(const double* __restrict__ A, int64_t lda, int64_t m, int64_t k,
+                                            unsigned long long* __restrict__ rowmax,
+                                            unsigned long long* __restrict__ nonfinite, int tri, unsigned bx,
+                                            unsigned by) {
+  int64_t i = (int64_t)bx * kThreads + threadIdx.x;
   if (i >= m) return;
-  int64_t l0 = (int64_t)blockIdx.y * kRowMaxKC;
+  int64_t l0 = (int64_t)by * kRowMaxKC;
   int64_t l1 = l0 + kRowMaxKC < k ? l0 + kRowMaxKC : k;
   const double* p = A + i + l0 * lda;
   unsigned long long mx = 0ull;
@@ -70,11 +73,11 @@ __global__ void __launch_bounds__(kThreads) rowmax_kernel(const double* __restri
 
 // B is k x n column-major: one block per (column, chunk of KC rows); lanes run down the column.
 constexpr int kColMaxKC = 4096;
-__global__ void __launch_bounds__(kThreads) colmax_kernel(const double* __restrict__ B, int64_t ldb, int64_t k,
-                                                          unsigned long long* __restrict__ colmax,
-                                                          unsigned long long* __restrict__ nonfinite, int tri) {
-  int64_t j = blockIdx.x;
-  int64_t l0 = (int64_t)blockIdx.y * kColMaxKC;
+__device__ __forceinline__ void contig_max(const double* __restrict__ B, int64_t ldb, int64_t k,
+                                           unsigned long long* __restrict__ colmax,
+                                           unsigned long long* __restrict__ nonfinite, int tri, unsigned bx, unsigned by) {
+  int64_t j = bx;
+  int64_t l0 = (int64_t)by * kColMaxKC;
   const double* p = B + j * ldb;
   unsigned long long mx = 0ull;
 #pragma unroll 4
@@ -99,6 +102,28 @@ __global__ void __launch_bounds__(kThreads) colmax_kernel(const double* __restri
     if (mx) atomicMax(colmax + j, mx);
     if (mx >= kInfBits) *nonfinite = 1ull;
   }
+}
+
+// Both operands of a call in one launch: a block belongs to the first job or to the second by its index.
+// strided: the vectors are rows of a column-major array (lanes along the vectors); otherwise they are its
+// columns (lanes along the inner dimension).  gx: extent of the job's first (fast) block coordinate.
+struct MaxJob {
+  const double* X;
+  int64_t ld, nvec, k;
+  unsigned long long* vmax;
+  int tri, strided;
+  unsigned gx, nblk;
+};
+__global__ void __launch_bounds__(kThreads) operand_max_kernel(const MaxJob ja, const MaxJob jb,
+                                                               unsigned long long* __restrict__ nonfinite) {
+  const bool first = blockIdx.x < ja.nblk;
+  const MaxJob& j = first ? ja : jb;
+  const unsigned id = first ? blockIdx.x : blockIdx.x - ja.nblk;
+  const unsigned bx = id % j.gx, by = id / j.gx;
+  if (j.strided)
+    strided_max(j.X, j.ld, j.nvec, j.k, j.vmax, nonfinite, j.tri, bx, by);
+  else
+    contig_max(j.X, j.ld, j.k, j.vmax, nonfinite, j.tri, bx, by);
 }
 
 // ---- Cauchy-Schwarz shift mode (Section 4.1): integer upper bound of the 2-norm.
@@ -280,13 +305,12 @@ constexpr int kConvAPitch = 65;  // doubles per row in LDS
 // KIND 0 / 1: residues of trunc(a 2^shift) with the one- / two-level split; KIND 2: the single plane of 6-bit
 // upper bounds ceil(|a| 2^shift) of Section 4.1 (written where plane 0 goes).
 template <int KIND>
-__global__ void __launch_bounds__(kThreads) convert_a_kernel(const double* __restrict__ A, int64_t lda, int64_t m,
-                                                             int64_t k, int64_t m_pad, int64_t k_pad,
-                                                             const int* __restrict__ sa, int8_t* __restrict__ planes,
-                                                             const int tri, const Oz2ConvConsts cc) {
-  __shared__ double tile[kConvARows * kConvAPitch];
-  const int64_t r0 = (int64_t)blockIdx.x * kConvARows;  // < m_pad
-  const int64_t kb = blockIdx.y;
+__device__ __forceinline__ void convert_strided(const double* __restrict__ A, int64_t lda, int64_t m, int64_t k,
+                                                int64_t m_pad, int64_t k_pad, const int* __restrict__ sa,
+                                                int8_t* __restrict__ planes, const int tri, const Oz2ConvConsts& cc,
+                                                double* tile, unsigned bx, unsigned by) {
+  const int64_t r0 = (int64_t)bx * kConvARows;  // < m_pad
+  const int64_t kb = by;
   const int wv = threadIdx.x >> 6, lane = threadIdx.x & 63;
   {
     const int64_t i = r0 + lane;
@@ -339,13 +363,12 @@ constexpr int kConvBKC = 256;
 constexpr int kConvBGroup = 18;     // doubles per 16-element group in LDS (144 bytes)
 constexpr int kConvBColPitch = 296; // doubles per column in LDS: 16 groups + 8 (2368 bytes = 64 mod 256)
 template <int KIND>
-__global__ void __launch_bounds__(kThreads) convert_b_kernel(const double* __restrict__ B, int64_t ldb, int64_t k,
-                                                             int64_t n, int64_t n_pad, int64_t k_pad,
-                                                             const int* __restrict__ sb, int8_t* __restrict__ planes,
-                                                             const int tri, const Oz2ConvConsts cc) {
-  __shared__ __attribute__((aligned(16))) double tile[kConvBCols * kConvBColPitch];
-  const int64_t j0 = (int64_t)blockIdx.x * kConvBCols;  // < n_pad, multiple of 16
-  const int64_t lbase = (int64_t)blockIdx.y * kConvBKC;
+__device__ __forceinline__ void convert_contig(const double* __restrict__ B, int64_t ldb, int64_t k, int64_t n,
+                                               int64_t n_pad, int64_t k_pad, const int* __restrict__ sb,
+                                               int8_t* __restrict__ planes, const int tri, const Oz2ConvConsts& cc,
+                                               double* tile, unsigned bx, unsigned by) {
+  const int64_t j0 = (int64_t)bx * kConvBCols;  // < n_pad, multiple of 16
+  const int64_t lbase = (int64_t)by * kConvBKC;
   {
     const int64_t l = lbase + threadIdx.x;
     const int slot = (threadIdx.x >> 4) * kConvBGroup + (threadIdx.x & 15);
@@ -389,6 +412,38 @@ __global__ void __launch_bounds__(kThreads) convert_b_kernel(const double* __res
   }
 }
 
+// Both operands of a call in one launch (see operand_max_kernel).  KA / KB: what is written for the first /
+// second job (0, 1: residue planes with the one- / two-level split; 2: the bound plane).
+struct ConvJob {
+  const double* X;
+  int64_t ld, nvec, k, nvec_pad, k_pad;
+  const int* shifts;
+  int8_t* planes;
+  int tri, strided;
+  unsigned gx, nblk;
+};
+constexpr int kConvTileDoubles =
+    kConvARows * kConvAPitch > kConvBCols * kConvBColPitch ? kConvARows * kConvAPitch : kConvBCols * kConvBColPitch;
+template <int KA, int KB>
+__global__ void __launch_bounds__(kThreads) operand_convert_kernel(const ConvJob ja, const ConvJob jb,
+                                                                   const Oz2ConvConsts cc) {
+  __shared__ __attribute__((aligned(16))) double tile[kConvTileDoubles];
+  if (blockIdx.x < ja.nblk) {
+    const unsigned bx = blockIdx.x % ja.gx, by = blockIdx.x / ja.gx;
+    if (ja.strided)
+      convert_strided<KA>(ja.X, ja.ld, ja.nvec, ja.k, ja.nvec_pad, ja.k_pad, ja.shifts, ja.planes, ja.tri, cc, tile, bx, by);
+    else
+      convert_contig<KA>(ja.X, ja.ld, ja.k, ja.nvec, ja.nvec_pad, ja.k_pad, ja.shifts, ja.planes, ja.tri, cc, tile, bx, by);
+  } else {
+    const unsigned id = blockIdx.x - ja.nblk;
+    const unsigned bx = id % jb.gx, by = id / jb.gx;
+    if (jb.strided)
+      convert_strided<KB>(jb.X, jb.ld, jb.nvec, jb.k, jb.nvec_pad, jb.k_pad, jb.shifts, jb.planes, jb.tri, cc, tile, bx, by);
+    else
+      convert_contig<KB>(jb.X, jb.ld, jb.k, jb.nvec, jb.nvec_pad, jb.k_pad, jb.shifts, jb.planes, jb.tri, cc, tile, bx, by);
+  }
+}
+
 }  // namespace
 
 namespace {
@@ -411,14 +466,21 @@ struct Operand {
   int8_t* planes;
 };
 
-void launch_max(const Operand& o, hipStream_t st) {
-  const dim3 thr(kThreads);
-  if (o.strided)
-    hipLaunchKernelGGL(rowmax_kernel, dim3(blocks_of(o.nvec, kThreads), blocks_of(o.k, kRowMaxKC)), thr, 0, st, o.X, o.ld,
-                       o.nvec, o.k, o.vmax, o.flag, o.tri);
-  else
-    hipLaunchKernelGGL(colmax_kernel, dim3((unsigned)o.nvec, blocks_of(o.k, kColMaxKC)), thr, 0, st, o.X, o.ld, o.k, o.vmax,
-                       o.flag, o.tri);
+// maxima of one or two operands in one launch
+hipError_t launch_max(const Operand* ops, int nops, hipStream_t st) {
+  MaxJob job[2] = {};
+  int64_t total = 0;
+  for (int x = 0; x < nops; ++x) {
+    const Operand& o = ops[x];
+    const int64_t gx = o.strided ? blocks_of(o.nvec, kThreads) : o.nvec;
+    const int64_t gy = o.strided ? blocks_of(o.k, kRowMaxKC) : blocks_of(o.k, kColMaxKC);
+    total += gx * gy;
+    if (total >= ((int64_t)1 << 31)) return hipErrorInvalidValue;
+    job[x] = {o.X, o.ld, o.nvec, o.k, o.vmax, o.tri, o.strided ? 1 : 0, (unsigned)gx, (unsigned)(gx * gy)};
+  }
+  if (nops == 1) job[1] = job[0], job[1].nblk = 0;
+  hipLaunchKernelGGL(operand_max_kernel, dim3((unsigned)total), dim3(kThreads), 0, st, job[0], job[1], ops[0].flag);
+  return hipSuccess;
 }
 
 void launch_norm(const Operand& o, hipStream_t st) {
@@ -431,26 +493,36 @@ void launch_norm(const Operand& o, hipStream_t st) {
                        o.vaux, o.tri);
 }
 
-// kind 0 / 1: residue planes with the one- / two-level split; kind 2: the bound plane
-void launch_convert(const Operand& o, int kind, const Oz2ConvConsts& conv, hipStream_t st) {
-  const dim3 thr(kThreads);
-  const dim3 ga((unsigned)(o.nvec_pad / kConvARows), (unsigned)(o.k_pad / kBlkK));
-  const dim3 gb((unsigned)(o.nvec_pad / kConvBCols), blocks_of(o.k_pad, kConvBKC));
-#define OZ2_CONV(KIND)                                                                                              \
-  if (o.strided)                                                                                                    \
-    hipLaunchKernelGGL(convert_a_kernel<KIND>, ga, thr, 0, st, o.X, o.ld, o.nvec, o.k, o.nvec_pad, o.k_pad, o.shifts, \
-                       o.planes, o.tri, conv);                                                                      \
-  else                                                                                                              \
-    hipLaunchKernelGGL(convert_b_kernel<KIND>, gb, thr, 0, st, o.X, o.ld, o.k, o.nvec, o.nvec_pad, o.k_pad, o.shifts, \
-                       o.planes, o.tri, conv);
-  if (kind == 0) {
-    OZ2_CONV(0)
-  } else if (kind == 1) {
-    OZ2_CONV(1)
-  } else {
-    OZ2_CONV(2)
+// planes of one or two operands in one launch; kind 0 / 1: residue planes with the one- / two-level split,
+// kind 2: the bound plane
+hipError_t launch_convert(const Operand* ops, int nops, const int* kind, const Oz2ConvConsts& conv, hipStream_t st) {
+  ConvJob job[2] = {};
+  int64_t total = 0;
+  for (int x = 0; x < nops; ++x) {
+    const Operand& o = ops[x];
+    const int64_t gx = o.strided ? o.nvec_pad / kConvARows : o.nvec_pad / kConvBCols;
+    const int64_t gy = o.strided ? o.k_pad / kBlkK : blocks_of(o.k_pad, kConvBKC);
+    total += gx * gy;
+    if (total >= ((int64_t)1 << 31)) return hipErrorInvalidValue;
+    job[x] = {o.X, o.ld, o.nvec, o.k, o.nvec_pad, o.k_pad, o.shifts, o.planes, o.tri, o.strided ? 1 : 0, (unsigned)gx,
+              (unsigned)(gx * gy)};
   }
+  const int ka = kind[0], kb = nops == 2 ? kind[1] : kind[0];
+  if (nops == 1) job[1] = job[0], job[1].nblk = 0;
+  const dim3 grid((unsigned)total), thr(kThreads);
+#define OZ2_CONV(KA, KB) hipLaunchKernelGGL((operand_convert_kernel<KA, KB>), grid, thr, 0, st, job[0], job[1], conv)
+  if (ka == 2)
+    OZ2_CONV(2, 2);
+  else if (ka == 0 && kb == 0)
+    OZ2_CONV(0, 0);
+  else if (ka == 0)
+    OZ2_CONV(0, 1);
+  else if (kb == 0)
+    OZ2_CONV(1, 0);
+  else
+    OZ2_CONV(1, 1);
 #undef OZ2_CONV
+  return hipSuccess;
 }
 
 }  // namespace
@@ -494,13 +566,16 @@ hipError_t oz2_launch_stage1(int transa, int transb, int64_t m, int64_t n, int64
   const int d = bit_split;
   int xbits[2];  // |x'| < 2^xbits decides how deep the conversion kernels split an element
   fill(ops[0].vmax, n_max);
-  for (int x = 0; x < nops; ++x) launch_max(ops[x], st);
+  if (hipError_t e = launch_max(ops, nops, st); e != hipSuccess) return e;
   if (shift_mode == OZ2_SHIFT_INT8_PRODUCT) {
     // bound planes (in the slots of residue plane 0), their INT8 product (in the slot of product plane 0),
     // its row and column maxima, then the shifts.  In the symmetric case the product is A''A''^T and its
     // row maxima are its column maxima (those land in the unused column array).
     shifts(0, 6, 6, 0, 0);  // exponents 5 - e of the bounds
-    for (int x = 0; x < nops; ++x) launch_convert(ops[x], 2, conv, st);
+    {
+      const int bound[2] = {2, 2};
+      if (hipError_t e = launch_convert(ops, nops, bound, conv, st); e != hipSuccess) return e;
+    }
     fill(ops[0].vaux, n_aux);
     hipError_t e = oz2_launch_bound_gemm(lay, ws, B == nullptr, st);
     if (e != hipSuccess) return e;
@@ -525,10 +600,8 @@ hipError_t oz2_launch_stage1(int transa, int transb, int64_t m, int64_t n, int64
     xbits[0] = kappa_a;
     xbits[1] = kappa_b;
   }
-  for (int x = 0; x < nops; ++x) {
-    conv.two_level = xbits[x] > 75;
-    launch_convert(ops[x], conv.two_level ? 1 : 0, conv, st);
-  }
+  const int kinds[2] = {xbits[0] > 75 ? 1 : 0, xbits[1] > 75 ? 1 : 0};
+  if (hipError_t e = launch_convert(ops, nops, kinds, conv, st); e != hipSuccess) return e;
   return hipGetLastError();
 }
 
