@@ -132,7 +132,7 @@ def main():
         # HBM-side bytes per launch from the rocprofv3 counter runs summarised in
         # profiles/c4_oz2_dgemm_counters.md: FETCH_SIZE x 2.0 (copy-kernel scale) + WRITE_SIZE, in GiB, for the
         # UINT8 and the INT32 product format
-        fetch_gib, write_gib, min_gib = (53.425, 8.095, 12) if fmt == oz.OZ2_PRODUCT_RESIDUE_U8 else (54.186, 19.125, 24)
+        fetch_gib, write_gib, min_gib = (48.658, 8.051, 12) if fmt == oz.OZ2_PRODUCT_RESIDUE_U8 else (54.186, 19.125, 24)
         roofline["traffic"] = round((fetch_gib * 2.0 + write_gib) * 2**30)
         roofline["traffic_unit"] = "bytes per launch (L2 misses + write-backs; algorithmic minimum %d GiB)" % min_gib
     stages = {
