@@ -485,12 +485,16 @@ hipError_t launch_gemm(const Oz2Layout& lay, char* ws, int num_moduli, const int
   g.full_rounds = 0;
   if (triangle == 0 && krange == OZ2_KRANGE_ALL) {
     if (grid > (unsigned)g_cus) grid = (unsigned)g_cus;
-    // Large general products: the workgroups of an XCD start the tiles of a round together, which keeps them
+    // General products: the workgroups of an XCD start the tiles of a round together, which keeps them
     // on the same k-tiles of their shared panels (measured: L2 misses 48.7 GiB per launch every time instead of
     // 50-54 GiB, and 83 GiB in some runs).  The counters are words 8..15 of the flag words that stage 1 clears.
-    if (g.superblock && num_moduli > 1) {
+    if (num_moduli > 1) {
       g.xcd_sync = reinterpret_cast<unsigned long long*>(ws + lay.off_flags) + 8;
-      g.full_rounds = (g.chunk * 8) / (int)grid;
+      // rounds in which each of the grid / 8 workgroup slots of every XCD has a tile: all of them in the
+      // super-block order (its work count is a multiple of 256); otherwise XCD 7 runs out first
+      const int per_xcd = (int)grid / 8;
+      const int last = g.total - 7 * g.chunk;  // work items of XCD 7
+      g.full_rounds = g.superblock ? (g.chunk * 8) / (int)grid : (last > 0 ? last / per_xcd : 0);
     }
   }
   if (residue_u8)
