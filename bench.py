@@ -35,6 +35,8 @@ def main():
                     help="0: shifts from maxima (Section 3, default); 1: Cauchy-Schwarz bound; 2: INT8-product bound (Section 4.1)")
     ap.add_argument("--product-format", type=int, default=-1,
                     help="0: INT32 product planes; 1: UINT8 residue planes (library default)")
+    ap.add_argument("--gemm-algorithm", type=int, default=-1,
+                    help="-1: library default (Strassen form of the INT8 products for large sizes); 0: classical; 1: Strassen form")
     ap.add_argument("--graph", action="store_true",
                     help="time replays of one captured HIP graph of the call instead of eager calls (small sizes)")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -69,9 +71,11 @@ def main():
     dC = torch.empty((n, m), dtype=torch.float64, device=dev).t()
     fmt = args.product_format if args.product_format >= 0 else oz.OZ2_PRODUCT_RESIDUE_U8
     oz.oz2_set_product_format(fmt)
-    ws = oz.Workspace(m, n, k, N, device=dev, product_format=fmt)
-    stream = torch.cuda.current_stream()
+    oz.oz2_set_gemm_algorithm(args.gemm_algorithm)
     oz.oz2_set_shift_mode(args.shift_mode)
+    ws = oz.Workspace(m, n, k, N, device=dev, product_format=fmt)
+    strassen = oz.oz2_gemm_algorithm_for(m, n, k, N) == oz.OZ2_GEMM_STRASSEN
+    stream = torch.cuda.current_stream()
 
     hip = ctypes.CDLL("libamdhip64.so")
     def new_event():
@@ -122,13 +126,25 @@ def main():
 
     # dominant kernel: the INT8 GEMM of stage 2 (one launch per step)
     gemm_ms = float(avg[1])
-    gemm_tops = 2.0 * m * n * k * N / (gemm_ms * 1e-3) / 1e12
-    s1_bytes = (16 + N) * (m * k + k * n) + 4 * (m + n)
-    s3_bytes = ((1 if fmt == oz.OZ2_PRODUCT_RESIDUE_U8 else 4) * N + 8) * m * n + 4 * (m + n)
+    # INT8 operations the launch executes: 2 m n k per modulus as printed in Algorithm 1 line 6; in the Strassen
+    # form seven products of half the (padded) size per modulus, 7/8 of that
+    if strassen:
+        up = lambda v, a: (v + a - 1) // a * a
+        mh, nh, kh = up((m + 1) // 2, 256), up((n + 1) // 2, 256), up((k + 1) // 2, 64)
+        gemm_ops = 7 * 2.0 * mh * nh * kh * N
+    else:
+        gemm_ops = 2.0 * m * n * k * N
+    gemm_tops = gemm_ops / (gemm_ms * 1e-3) / 1e12
+    planes = 1.75 if strassen else 1.0   # plane bytes of the conversion and CRT passes relative to the classical form
+    s1_bytes = (16 + planes * N) * (m * k + k * n) + 4 * (m + n)
+    s3_bytes = ((1 if fmt == oz.OZ2_PRODUCT_RESIDUE_U8 else 4) * planes * N + 8) * m * n + 4 * (m + n)
     roofline = {"bound": "mfma", "kernel": "gemm_i8_kernel", "achieved": round(gemm_tops, 2),
                 "peak": INT8_MFMA_PEAK_TOPS, "unit": "TOP/s", "frac": round(gemm_tops / INT8_MFMA_PEAK_TOPS, 4),
                 "traffic": None, "avg_launch_ms": round(gemm_ms, 4)}
-    if args.workload == "c4" and N == 16 and not args.mnk and args.shift_mode == 0:
+    if strassen:
+        roofline["note"] = ("achieved counts the INT8 operations executed (7 half-size products per modulus); "
+                            "the classical count 2mnkN over the same time is %.2f TOP/s" % (2.0 * m * n * k * N / (gemm_ms * 1e-3) / 1e12))
+    if args.workload == "c4" and N == 16 and not args.mnk and args.shift_mode == 0 and not strassen:
         # HBM-side bytes per launch from the rocprofv3 counter runs summarised in
         # profiles/c4_oz2_dgemm_counters.md: FETCH_SIZE x 2.0 (copy-kernel scale) + WRITE_SIZE, in GiB, for the
         # UINT8 and the INT32 product format
@@ -152,6 +168,7 @@ def main():
         "config": {"workload": "%s: m=%d n=%d k=%d phi=%g, %d moduli, seed %d" % (args.workload, m, n, k, phi, N, cfg["seed"]),
                    "num_moduli": N, "entry_point": "oz2_dgemm" + (" (HIP graph replay)" if args.graph else ""), "shift_mode": args.shift_mode,
                    "product_format": "uint8 residues" if fmt == oz.OZ2_PRODUCT_RESIDUE_U8 else "int32",
+                   "gemm_algorithm": "strassen (one level, in the residue rings)" if strassen else "classical",
                    "workspace_GiB": round(ws.nbytes / 2**30, 2), "host_input_generation_s": round(gen_s, 1)},
         "roofline": roofline, "stages": stages,
     }

@@ -38,6 +38,10 @@ extern "C" {
 #define OZ2_PRODUCT_INT32 0      /* stage 2 writes the INT32 products C'_t (Algorithm 1 line 6) */
 #define OZ2_PRODUCT_RESIDUE_U8 1 /* stage 2 writes C''_t = C'_t mod p_t as UINT8 (lines 6 and 7 together); default */
 
+#define OZ2_GEMM_AUTO (-1)    /* Strassen form for large general products when the workspace allows it; default */
+#define OZ2_GEMM_CLASSICAL 0  /* Algorithm 1 line 6 as printed: one INT8 product of the full size per modulus */
+#define OZ2_GEMM_STRASSEN 1   /* one level of Strassen's recursion inside every residue ring: 7 products of half size */
+
 #define OZ2_SHIFT_MAX 0            /* shifts from row/column maxima: the simple bound of Section 3 */
 #define OZ2_SHIFT_CAUCHY_SCHWARZ 1 /* shifts from row/column 2-norms: Section 4.1, the "fast" variant */
 #define OZ2_SHIFT_INT8_PRODUCT 2   /* shifts from an INT8 product of upper bounds: Section 4.1, the "accu" variant */
@@ -168,6 +172,30 @@ int oz2_set_nonfinite_check(int on);
  * for k < 2^17; with k-blocking a value congruent to the product modulo p_t) and stage 3 takes line 7.
  * The final C is identical in both formats.  Returns 0 or -1. */
 int oz2_set_product_format(int format);
+
+/* How oz2_dgemm / oz2_dgemm_ex form the products of Algorithm 1 line 6, for all later calls.  Line 6 is only used
+ * modulo p_t (line 7), and the residues form a ring, so Strassen's identities hold in it exactly: with A'_t, B'_t
+ * split into 2 x 2 blocks, seven INT8 products of half the size in each dimension, of block sums and differences
+ * reduced modulo p_t again (they still fit INT8), give the four blocks of C''_t.  7/8 of the matrix-core work for
+ * 7/4 of the plane bytes in stages 1 and 3; C''_t, and therefore C, is the same as in the classical form, bit
+ * for bit.  The form needs UINT8 residue planes (OZ2_PRODUCT_RESIDUE_U8) and applies to the general product only:
+ * oz2_dsyrk, oz2_dtrmm and the staged entry points always take the classical form.
+ *   OZ2_GEMM_AUTO (default): Strassen form when m and n are at least 8192 and k at least 12288 (below, the extra
+ *     bytes cost more than the products save) and the registered workspace holds oz2_workspace_bytes_strassen;
+ *     else classical.
+ *   OZ2_GEMM_CLASSICAL: never.   OZ2_GEMM_STRASSEN: whenever the form applies, at any size (a workspace below
+ *     oz2_workspace_bytes_strassen then gives OZ2_ERR_WORKSPACE).
+ * oz2_gemm_algorithm_for tells which form a general product of that shape would take under the settings and the
+ * workspace in force (OZ2_GEMM_CLASSICAL or OZ2_GEMM_STRASSEN, or a negative argument code).
+ * oz2_workspace_bytes_strassen: bytes the Strassen form needs (0 on invalid arguments): m, n rounded up to 512 and
+ * k to 128, seven planes of a quarter of that area per modulus and operand (21 GiB at m = n = k = 16384 with 16
+ * moduli).  oz2_workspace_bytes_preferred: bytes with which a general product of that shape takes the form the
+ * settings in force prefer (the Strassen size where that form would be chosen, else the size for the product
+ * format in force).  Returns of the setter: 0 or -1. */
+int oz2_set_gemm_algorithm(int algorithm);
+int oz2_gemm_algorithm_for(int64_t m, int64_t n, int64_t k, int num_moduli);
+size_t oz2_workspace_bytes_strassen(int64_t m, int64_t n, int64_t k, int num_moduli);
+size_t oz2_workspace_bytes_preferred(int64_t m, int64_t n, int64_t k, int num_moduli);
 
 /* How Algorithm 1 line 1 picks the shifts, for all later calls (default OZ2_SHIFT_MAX).
  *   OZ2_SHIFT_MAX: sa_i = kappa - 1 - floor(log2 max_l |a_il|) with the bit budget kappa of Section 3.

@@ -9,6 +9,7 @@ _lib = None
 SYMBOLS = [
     "oz2_init", "oz2_min_moduli", "oz2_moduli_for_bits", "oz2_max_moduli", "oz2_get_moduli", "oz2_workspace_bytes", "oz2_workspace_bytes_for", "oz2_set_workspace",
     "oz2_workspace_layout", "oz2_dgemm", "oz2_dgemm_ex", "oz2_dsyrk", "oz2_dtrmm", "oz2_stage1_convert", "oz2_stage2_gemm", "oz2_stage3_crt",
+    "oz2_set_gemm_algorithm", "oz2_gemm_algorithm_for", "oz2_workspace_bytes_strassen", "oz2_workspace_bytes_preferred",
     "oz2_set_kblock", "oz2_set_shift_mode", "oz2_set_product_format", "oz2_set_bit_split", "oz2_set_nonfinite_check", "oz2_set_stage_events", "oz2_calibrate_mfma", "oz2_host_crt_element", "oz2_host_residues", "oz2_status_string",
 ]
 
@@ -31,6 +32,12 @@ def lib():
         L.oz2_workspace_bytes.argtypes = [i64, i64, i64, ci]
         L.oz2_workspace_bytes_for.restype = ctypes.c_size_t
         L.oz2_workspace_bytes_for.argtypes = [i64, i64, i64, ci, ci]
+        L.oz2_workspace_bytes_strassen.restype = ctypes.c_size_t
+        L.oz2_workspace_bytes_strassen.argtypes = [i64, i64, i64, ci]
+        L.oz2_workspace_bytes_preferred.restype = ctypes.c_size_t
+        L.oz2_workspace_bytes_preferred.argtypes = [i64, i64, i64, ci]
+        L.oz2_set_gemm_algorithm.argtypes = [ci]
+        L.oz2_gemm_algorithm_for.argtypes = [i64, i64, i64, ci]
         L.oz2_set_workspace.argtypes = [vp, ctypes.c_size_t]
         L.oz2_workspace_layout.argtypes = [i64, i64, i64, ci, vp, vp]
         L.oz2_dgemm.argtypes = [i64, i64, i64, vp, i64, vp, i64, vp, i64, ci, vp]
@@ -83,6 +90,32 @@ def workspace_bytes(m, n, k, num_moduli, product_format=None):
     if product_format is None:
         return int(lib().oz2_workspace_bytes(m, n, k, num_moduli))
     return int(lib().oz2_workspace_bytes_for(m, n, k, num_moduli, int(product_format)))
+
+
+def workspace_bytes_strassen(m, n, k, num_moduli):
+    """Bytes the Strassen form of the products needs."""
+    return int(lib().oz2_workspace_bytes_strassen(m, n, k, num_moduli))
+
+
+def workspace_bytes_preferred(m, n, k, num_moduli):
+    """Bytes with which a general product takes the form the settings in force prefer."""
+    return int(lib().oz2_workspace_bytes_preferred(m, n, k, num_moduli))
+
+
+OZ2_GEMM_AUTO, OZ2_GEMM_CLASSICAL, OZ2_GEMM_STRASSEN = -1, 0, 1
+
+
+def oz2_set_gemm_algorithm(algorithm):
+    """-1 (default): Strassen form for large general products; 0: never; 1: whenever it applies."""
+    _check(lib().oz2_set_gemm_algorithm(int(algorithm)), "oz2_set_gemm_algorithm")
+
+
+def oz2_gemm_algorithm_for(m, n, k, num_moduli):
+    """Form (0 classical, 1 Strassen) a general product of this shape takes under the settings and workspace in force."""
+    rc = lib().oz2_gemm_algorithm_for(m, n, k, num_moduli)
+    if rc < 0:
+        raise Oz2Error("oz2_gemm_algorithm_for: invalid argument %d" % -rc)
+    return rc
 
 
 def oz2_init():
@@ -214,6 +247,8 @@ class Workspace:
         self.nbytes = workspace_bytes(m, n, k, num_moduli, product_format)
         if self.nbytes == 0:
             raise Oz2Error("invalid problem for a workspace")
+        # enough for the form of the products that the settings in force prefer
+        self.nbytes = max(self.nbytes, workspace_bytes_preferred(m, n, k, num_moduli))
         self.buf = torch.empty(self.nbytes + 256, dtype=torch.uint8, device=device)
         base = self.buf.data_ptr()
         self.offset = (-base) % 256

@@ -15,6 +15,7 @@ struct State {
   int nonfinite_check = 1;
   int bit_split = 0;
   int product_format = OZ2_PRODUCT_RESIDUE_U8;
+  int gemm_algorithm = OZ2_GEMM_AUTO;
   hipEvent_t ev[4] = {nullptr, nullptr, nullptr, nullptr};
   bool ev_on = false;
   Oz2Plan plan;
@@ -71,6 +72,42 @@ int prepare(State& s, int64_t m, int64_t n, int64_t k, int N, const Oz2Plan** pl
   return OZ2_OK;
 }
 
+// The Strassen form pays when the matrix-core work it saves (an eighth of 2 m n k N) outweighs the extra plane
+// traffic of its conversion and CRT passes (three quarters more bytes per plane) and the lower rate of products
+// with a short inner dimension.  Measured on MI355X with 16 moduli: 5 % slower at 8192^3, even at 8192 x 8192 x
+// 12288 and at 12288^3, 2 % faster at 8192 x 8192 x 16384, 4 % at 16384 x 16384 x 12288, 8-10 % from 14336^3 on.
+bool strassen_pays(int64_t m, int64_t n, int64_t k) { return m >= 8192 && n >= 8192 && k >= 12288; }
+
+// Does a general product of this shape use the Strassen form under the current settings?  It needs UINT8 residue
+// planes and, in the INT8-product shift mode, a padded inner dimension below 2^19.  On a yes, *lay is its layout.
+bool strassen_applies(const State& s, int64_t m, int64_t n, int64_t k, int N, Oz2Layout* lay) {
+  if (s.gemm_algorithm == OZ2_GEMM_CLASSICAL || s.product_format != OZ2_PRODUCT_RESIDUE_U8) return false;
+  if (s.gemm_algorithm == OZ2_GEMM_AUTO && !strassen_pays(m, n, k)) return false;
+  oz2_make_layout_strassen(m, n, k, N, lay);
+  if (s.shift_mode == OZ2_SHIFT_INT8_PRODUCT && lay->k_pad >= ((int64_t)1 << 19)) return false;
+  return true;
+}
+
+// prepare() for the general product: *strassen tells which form the call takes.  The automatic choice falls back to
+// the plain form when the workspace only suffices for that; a forced Strassen form reports the workspace as too small.
+int prepare_general(State& s, int64_t m, int64_t n, int64_t k, int N, const Oz2Plan** plan, Oz2Layout* lay, bool* strassen) {
+  *strassen = false;
+  Oz2Layout plain;
+  const int rc = prepare(s, m, n, k, N, plan, &plain);
+  if (rc != OZ2_OK && rc != OZ2_ERR_WORKSPACE) return rc;
+  Oz2Layout sl;
+  if (strassen_applies(s, m, n, k, N, &sl)) {
+    if (s.ws && s.ws_bytes >= sl.total) {
+      *lay = sl;
+      *strassen = true;
+      return OZ2_OK;
+    }
+    if (s.gemm_algorithm == OZ2_GEMM_STRASSEN) return OZ2_ERR_WORKSPACE;
+  }
+  *lay = plain;
+  return rc;
+}
+
 }  // namespace
 
 extern "C" {
@@ -110,6 +147,45 @@ size_t oz2_workspace_bytes_for(int64_t m, int64_t n, int64_t k, int num_moduli, 
 
 size_t oz2_workspace_bytes(int64_t m, int64_t n, int64_t k, int num_moduli) {
   return oz2_workspace_bytes_for(m, n, k, num_moduli, OZ2_PRODUCT_INT32);
+}
+
+size_t oz2_workspace_bytes_strassen(int64_t m, int64_t n, int64_t k, int num_moduli) {
+  if (m < 0 || n < 0 || k < 0 || !n_ok(num_moduli) || !dims_ok(m, n, k)) return 0;
+  Oz2Layout lay;
+  oz2_make_layout_strassen(m, n, k, num_moduli, &lay);
+  return lay.total;
+}
+
+size_t oz2_workspace_bytes_preferred(int64_t m, int64_t n, int64_t k, int num_moduli) {
+  if (m < 0 || n < 0 || k < 0 || !n_ok(num_moduli) || !dims_ok(m, n, k)) return 0;
+  State& s = state();
+  std::lock_guard<std::mutex> lock(s.mu);
+  Oz2Layout lay;
+  if (m > 0 && n > 0 && k > 0 && strassen_applies(s, m, n, k, num_moduli, &lay)) return lay.total;
+  oz2_make_layout(m, n, k, num_moduli, s.product_format == OZ2_PRODUCT_INT32 ? 4 : 1, &lay);
+  return lay.total;
+}
+
+int oz2_set_gemm_algorithm(int algorithm) {
+  if (algorithm != OZ2_GEMM_AUTO && algorithm != OZ2_GEMM_CLASSICAL && algorithm != OZ2_GEMM_STRASSEN) return -1;
+  State& s = state();
+  std::lock_guard<std::mutex> lock(s.mu);
+  s.gemm_algorithm = algorithm;
+  return OZ2_OK;
+}
+
+int oz2_gemm_algorithm_for(int64_t m, int64_t n, int64_t k, int num_moduli) {
+  if (m < 0) return -1;
+  if (n < 0) return -2;
+  if (k < 0) return -3;
+  if (!n_ok(num_moduli)) return -4;
+  if (!dims_ok(m, n, k)) return -1;
+  State& s = state();
+  std::lock_guard<std::mutex> lock(s.mu);
+  Oz2Layout sl;
+  if (m == 0 || n == 0 || k == 0 || !strassen_applies(s, m, n, k, num_moduli, &sl)) return OZ2_GEMM_CLASSICAL;
+  if (s.gemm_algorithm == OZ2_GEMM_AUTO && !(s.ws && s.ws_bytes >= sl.total)) return OZ2_GEMM_CLASSICAL;
+  return OZ2_GEMM_STRASSEN;
 }
 
 int oz2_set_workspace(void* dev_ptr, size_t bytes) {
@@ -217,7 +293,7 @@ int oz2_stage1_convert(int64_t m, int64_t n, int64_t k, const double* A, int64_t
   Oz2Layout lay;
   int rc = prepare(s, m, n, k, num_moduli, &plan, &lay);
   if (rc) return rc;
-  hipError_t e = oz2_launch_stage1(0, 0, m, n, k, A, lda, B, ldb, 0, 0, *plan, s.shift_mode, s.bit_split, lay, s.ws,
+  hipError_t e = oz2_launch_stage1(0, 0, m, n, k, A, lda, B, ldb, 0, 0, *plan, s.shift_mode, s.bit_split, 0, lay, s.ws,
                                    static_cast<hipStream_t>(stream));
   return e == hipSuccess ? OZ2_OK : OZ2_ERR_HIP;
 }
@@ -297,21 +373,30 @@ int oz2_dgemm_ex(char transa, char transb, int64_t m, int64_t n, int64_t k, doub
   std::lock_guard<std::mutex> lock(s.mu);
   const Oz2Plan* plan;
   Oz2Layout lay;
-  int rc = prepare(s, m, n, k, num_moduli, &plan, &lay);
+  bool strassen;
+  int rc = prepare_general(s, m, n, k, num_moduli, &plan, &lay, &strassen);
   if (rc) return rc;
   auto mark = [&](int i) { return !s.ev_on || hipEventRecord(s.ev[i], st) == hipSuccess; };
   if (!mark(0)) return OZ2_ERR_HIP;
-  if (oz2_launch_stage1(ta, tb, m, n, k, A, lda, B, ldb, 0, 0, *plan, s.shift_mode, s.bit_split, lay, s.ws, st) !=
-          hipSuccess ||
+  if (oz2_launch_stage1(ta, tb, m, n, k, A, lda, B, ldb, 0, 0, *plan, s.shift_mode, s.bit_split, strassen ? 1 : 0, lay, s.ws,
+                        st) != hipSuccess ||
       !mark(1))
     return OZ2_ERR_HIP;
-  if (oz2_launch_stage2(*plan, lay, s.ws, s.kblock, s.product_format, 0, OZ2_KRANGE_ALL, s.nonfinite_check, st) != hipSuccess ||
-      !mark(2))
-    return OZ2_ERR_HIP;
-  if (oz2_launch_stage3(m, n, alpha, beta, C, ldc, *plan, lay, s.ws, s.product_format, s.nonfinite_check, 0, st) !=
-          hipSuccess ||
-      !mark(3))
-    return OZ2_ERR_HIP;
+  if (strassen) {
+    if (oz2_launch_strassen_gemm(*plan, lay, s.ws, s.kblock, s.nonfinite_check, st) != hipSuccess || !mark(2))
+      return OZ2_ERR_HIP;
+    if (oz2_launch_strassen_crt(m, n, alpha, beta, C, ldc, *plan, lay, s.ws, s.nonfinite_check, st) != hipSuccess || !mark(3))
+      return OZ2_ERR_HIP;
+  } else {
+    if (oz2_launch_stage2(*plan, lay, s.ws, s.kblock, s.product_format, 0, OZ2_KRANGE_ALL, s.nonfinite_check, st) !=
+            hipSuccess ||
+        !mark(2))
+      return OZ2_ERR_HIP;
+    if (oz2_launch_stage3(m, n, alpha, beta, C, ldc, *plan, lay, s.ws, s.product_format, s.nonfinite_check, 0, st) !=
+            hipSuccess ||
+        !mark(3))
+      return OZ2_ERR_HIP;
+  }
   if (s.nonfinite_check &&
       oz2_launch_fallback(reinterpret_cast<const unsigned long long*>(s.ws + lay.off_flags), ta, tb, m, n, k, alpha, A, lda,
                           B, ldb, beta, C, ldc, 0, 0, 0, st) != hipSuccess)
@@ -350,7 +435,7 @@ int oz2_dsyrk(char uplo, char trans, int64_t n, int64_t k, double alpha, const d
   if (!mark(0)) return OZ2_ERR_HIP;
   // op(A) op(A)^T: the columns of the second operand are the rows of the first, so A is converted once and
   // its planes serve as both operands
-  if (oz2_launch_stage1(ta, 0, n, n, k, A, lda, nullptr, 0, 0, 0, *plan, s.shift_mode, 0, lay, s.ws, st) != hipSuccess ||
+  if (oz2_launch_stage1(ta, 0, n, n, k, A, lda, nullptr, 0, 0, 0, *plan, s.shift_mode, 0, 0, lay, s.ws, st) != hipSuccess ||
       !mark(1))
     return OZ2_ERR_HIP;
   if (oz2_launch_stage2(*plan, lay, s.ws, s.kblock, s.product_format, tri, OZ2_KRANGE_ALL, s.nonfinite_check, st) != hipSuccess ||
@@ -408,7 +493,7 @@ int oz2_dtrmm(char side, char uplo, char transa, char diag, int64_t m, int64_t n
                           : (op_lower ? OZ2_KRANGE_FROM_COL : OZ2_KRANGE_UPTO_COL);
   auto mark = [&](int i) { return !s.ev_on || hipEventRecord(s.ev[i], st) == hipSuccess; };
   if (!mark(0)) return OZ2_ERR_HIP;
-  if (oz2_launch_stage1(tx, ty, m, n, ka, X, ldx, Y, ldy, trix, triy, *plan, s.shift_mode, 0, lay, s.ws, st) != hipSuccess ||
+  if (oz2_launch_stage1(tx, ty, m, n, ka, X, ldx, Y, ldy, trix, triy, *plan, s.shift_mode, 0, 0, lay, s.ws, st) != hipSuccess ||
       !mark(1))
     return OZ2_ERR_HIP;
   if (oz2_launch_stage2(*plan, lay, s.ws, s.kblock, s.product_format, 0, krange, s.nonfinite_check, st) != hipSuccess || !mark(2))

@@ -243,3 +243,38 @@ void oz2_make_layout(int64_t m, int64_t n, int64_t k, int N, int c_elem_bytes, O
   off = up256(off + (size_t)lay->n_pad * 8);
   lay->total = off;
 }
+
+void oz2_make_layout_strassen(int64_t m, int64_t n, int64_t k, int N, Oz2Layout* lay) {
+  auto up = [](int64_t v, int64_t a) { return (v + a - 1) / a * a; };
+  auto up256 = [](size_t v) { return (v + 255) / 256 * 256; };
+  const int64_t mh = up(((m > 0 ? m : 1) + 1) / 2, OZ2_TILE_M);
+  const int64_t nh = up(((n > 0 ? n : 1) + 1) / 2, OZ2_TILE_N);
+  const int64_t kh = up(((k > 0 ? k : 1) + 1) / 2, OZ2_TILE_K);
+  lay->m_pad = 2 * mh;
+  lay->n_pad = 2 * nh;
+  lay->k_pad = 2 * kh;
+  size_t off = 0;
+  lay->off_rowmax = off;
+  off = up256(off + (size_t)lay->m_pad * 8);
+  lay->off_flags = off;
+  off += 256;
+  lay->off_colmax = off;
+  off = up256(off + (size_t)lay->n_pad * 8);
+  lay->off_sa = off;
+  off = up256(off + (size_t)lay->m_pad * 4);
+  lay->off_sb = off;
+  off = up256(off + (size_t)lay->n_pad * 4);
+  // 7 N planes of mh x kh bytes; the single bound plane of the INT8-product shift mode (4 mh kh bytes) fits
+  lay->off_a = off;
+  off = up256(off + (size_t)7 * N * mh * kh);
+  lay->off_b = off;
+  off = up256(off + (size_t)7 * N * nh * kh);
+  // 7 N product planes of mh x nh bytes, and at least the INT32 bound product (16 mh nh bytes)
+  lay->off_c = off;
+  off = up256(off + (size_t)(7 * N > 16 ? 7 * N : 16) * mh * nh);
+  lay->off_rownorm = off;
+  off = up256(off + (size_t)lay->m_pad * 8);
+  lay->off_colnorm = off;
+  off = up256(off + (size_t)lay->n_pad * 8);
+  lay->total = off;
+}

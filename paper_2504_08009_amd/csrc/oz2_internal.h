@@ -11,6 +11,7 @@
 #define OZ2_MIN_N 2
 #define OZ2_MAX_N 26   // greedy table 256 ... 139; M < 2^200
 #define OZ2_MAX_L 5    // 40-bit limbs of M
+#define OZ2_MAX_PLANES (7 * OZ2_MAX_N)  // planes of one GEMM launch: seven per modulus in the Strassen form
 #define OZ2_LIMB_BITS 40
 
 // GEMM tiling (stage 2): workgroup tile TILE_M x TILE_N, k-tile TILE_K bytes.
@@ -63,11 +64,22 @@ struct Oz2Layout {
   size_t off_rowmax, off_colmax, off_sa, off_sb, off_a, off_b, off_c, off_rownorm, off_colnorm, off_flags, total;
 };
 void oz2_make_layout(int64_t m, int64_t n, int64_t k, int N, int c_elem_bytes, Oz2Layout* lay);
+// Layout of the Strassen form (UINT8 residue planes): the padded extents are twice the halves (multiples of 256,
+// 256 and 64), and each plane region holds 7 N planes of a quarter of the padded area.
+void oz2_make_layout_strassen(int64_t m, int64_t n, int64_t k, int N, Oz2Layout* lay);
 
 // Kernel launchers.  Each returns hipSuccess or the launch error.
 hipError_t oz2_launch_stage1(int transa, int transb, int64_t m, int64_t n, int64_t k, const double* A, int64_t lda,
                              const double* B, int64_t ldb, int tri_a, int tri_b, const Oz2Plan& plan, int shift_mode,
-                             int bit_split, const Oz2Layout& lay, char* ws, hipStream_t st);
+                             int bit_split, int strassen, const Oz2Layout& lay, char* ws, hipStream_t st);
+// Strassen form of line 6 (oz2_strassen.hip, oz2_stage2.hip): operand planes, the 7 N products, CRT pass
+hipError_t oz2_launch_strassen_convert(int transa, int transb, int64_t m, int64_t n, int64_t k, const double* A, int64_t lda,
+                                       const double* B, int64_t ldb, const Oz2Plan& plan, const int* kinds,
+                                       const Oz2Layout& lay, char* ws, hipStream_t st);
+hipError_t oz2_launch_strassen_gemm(const Oz2Plan& plan, const Oz2Layout& lay, char* ws, int64_t kblock, int check_flag,
+                                    hipStream_t st);
+hipError_t oz2_launch_strassen_crt(int64_t m, int64_t n, double alpha, double beta, double* C, int64_t ldc,
+                                   const Oz2Plan& plan, const Oz2Layout& lay, char* ws, int check_flag, hipStream_t st);
 // One-time device set-up of the GEMM kernels (function attributes, compute-unit count); also done lazily by the
 // first launch.
 hipError_t oz2_gemm_setup();

@@ -530,9 +530,11 @@ hipError_t launch_convert(const Operand* ops, int nops, const int* kind, const O
 // transa / transb: 0 = the operand is stored as op(X) (column-major), 1 = it is stored transposed.
 // B == nullptr: the symmetric product op(A) op(A)^T (n == m); only A's vectors, shifts and planes are produced.
 // tri_a / tri_b: triangular structure of the stored arrays (0 = full; see tri_value).
+// strassen: lay is the layout of the Strassen form; shifts (and the bound product of the INT8-product mode) are
+// formed as usual on its padded extents, only the residue planes differ.
 hipError_t oz2_launch_stage1(int transa, int transb, int64_t m, int64_t n, int64_t k, const double* A, int64_t lda,
                              const double* B, int64_t ldb, int tri_a, int tri_b, const Oz2Plan& plan, int shift_mode,
-                             int bit_split, const Oz2Layout& lay, char* ws, hipStream_t st) {
+                             int bit_split, int strassen, const Oz2Layout& lay, char* ws, hipStream_t st) {
   // rows of op(A): strided in a stored m x k matrix, contiguous in a stored k x m matrix;
   // columns of op(B): contiguous in a stored k x n matrix, strided in a stored n x k matrix
   // Row maxima, flag words and column maxima are adjacent, and so are the two auxiliary vectors: one fill
@@ -601,6 +603,11 @@ hipError_t oz2_launch_stage1(int transa, int transb, int64_t m, int64_t n, int64
     xbits[1] = kappa_b;
   }
   const int kinds[2] = {xbits[0] > 75 ? 1 : 0, xbits[1] > 75 ? 1 : 0};
+  if (strassen) {
+    // general products only: the planes are the seven block combinations per modulus of the Strassen form
+    if (!B || tri_a || tri_b) return hipErrorInvalidValue;
+    return oz2_launch_strassen_convert(transa, transb, m, n, k, A, lda, B, ldb, plan, kinds, lay, ws, st);
+  }
   if (hipError_t e = launch_convert(ops, nops, kinds, conv, st); e != hipSuccess) return e;
   return hipGetLastError();
 }

@@ -74,7 +74,7 @@ struct GemmArgs {
   const unsigned long long* skip_flag;  // if not null and nonzero on the device: the products are not needed
   unsigned long long* xcd_sync;         // eight counters, one per XCD (zero at launch), or null: no round sync
   int full_rounds;                      // rounds in which every workgroup slot has a tile
-  float p[OZ2_MAX_N];
+  float p[OZ2_MAX_PLANES];             // modulus of every plane
 };
 
 // 16-byte-per-lane direct load global -> LDS.  The wave writes 1024 contiguous bytes starting at the
@@ -449,12 +449,13 @@ hipError_t gemm_setup() {
   return hipSuccess;
 }
 
-// num_moduli planes of A' (off_a) times planes of B' (off_b) -> planes of C' (off_c)
+// num_moduli planes of A' (off_a) times planes of B' (off_b) -> planes of C' (off_c); moduli[t] = modulus of plane t
 // b_is_a: the second operand's planes are the first operand's (symmetric product; m_pad == n_pad)
 hipError_t launch_gemm(const Oz2Layout& lay, char* ws, int num_moduli, const int* moduli, int64_t kblock, int residue_u8,
                        int triangle, int krange, bool b_is_a, bool check_flag, hipStream_t st) {
   hipError_t e = gemm_setup();
   if (e != hipSuccess) return e;
+  if (num_moduli < 1 || num_moduli > OZ2_MAX_PLANES) return hipErrorInvalidValue;
   GemmArgs g;
   g.a = reinterpret_cast<const int8_t*>(ws + lay.off_a);
   g.b = reinterpret_cast<const int8_t*>(ws + (b_is_a ? lay.off_a : lay.off_b));
@@ -476,7 +477,7 @@ hipError_t launch_gemm(const Oz2Layout& lay, char* ws, int num_moduli, const int
   g.superblock = (g.tiles_m % 16 == 0 && g.tiles_n % 16 == 0) ? 1 : 0;
   g.ktiles = (int)(lay.k_pad / BK);
   g.ktiles_per_block = (int)(kblock / BK);
-  for (int t = 0; t < OZ2_MAX_N; ++t) g.p[t] = t < num_moduli ? (float)moduli[t] : 1.0f;
+  for (int t = 0; t < OZ2_MAX_PLANES; ++t) g.p[t] = t < num_moduli ? (float)moduli[t] : 1.0f;
   // General products: one workgroup per compute unit (each holds one: 128 KiB of LDS, 512 registers per lane),
   // every workgroup walks the work indices of its slot in launch order.  Structured products have tiles of
   // unequal length (or none): there the hardware's dynamic placement of one workgroup per index balances better.
@@ -511,6 +512,21 @@ hipError_t oz2_gemm_setup() { return gemm_setup(); }
 hipError_t oz2_launch_stage2(const Oz2Plan& plan, const Oz2Layout& lay, char* ws, int64_t kblock, int residue_u8,
                              int triangle, int krange, int check_flag, hipStream_t st) {
   return launch_gemm(lay, ws, plan.N, plan.moduli, kblock, residue_u8, triangle, krange, triangle != 0, check_flag != 0, st);
+}
+
+// The seven products per modulus of the Strassen form: 7 N planes of half the extents of lay, plane 7 t + s
+// reduced modulo p_t in the epilogue (UINT8 residues).
+hipError_t oz2_launch_strassen_gemm(const Oz2Plan& plan, const Oz2Layout& lay, char* ws, int64_t kblock, int check_flag,
+                                    hipStream_t st) {
+  Oz2Layout half = lay;
+  half.m_pad = lay.m_pad / 2;
+  half.n_pad = lay.n_pad / 2;
+  half.k_pad = lay.k_pad / 2;
+  if (half.m_pad % BM || half.n_pad % BN || half.k_pad % BK) return hipErrorInvalidValue;
+  int moduli[OZ2_MAX_PLANES];
+  for (int t = 0; t < plan.N; ++t)
+    for (int s = 0; s < 7; ++s) moduli[7 * t + s] = plan.moduli[t];
+  return launch_gemm(half, ws, 7 * plan.N, moduli, kblock, 1, 0, OZ2_KRANGE_ALL, false, check_flag != 0, st);
 }
 
 // One plain INT8 product with INT32 output and no modular reduction between k-blocks: the caller guarantees

@@ -243,12 +243,15 @@ def test_c2_sampled_rows_and_error_decay():
     assert errs[16] < native
 
 
-@pytest.mark.parametrize("name,kblock", [("c3", None), ("c5a", None), ("c4", None), ("c5b", 32768)])
-def test_full_size_configs_on_sampled_outputs(name, kblock):
+@pytest.mark.parametrize("name,kblock,algorithm", [
+    ("c3", None, -1), ("c5a", None, -1), ("c4", None, -1), ("c4", None, 0), ("c5b", 32768, 0), ("c5b", 16384, -1)])
+def test_full_size_configs_on_sampled_outputs(name, kblock, algorithm):
     """The benchmark configurations at full size through oz2_dgemm (the call bench.py times); the oracle
     recomputes a sample of output rows and columns (first, last and random ones) with the full inner
-    dimension.  c5b runs with a k-block of 32768 so that the reduction between k-blocks is exercised at
-    k = 65536; the result must still be bit-identical."""
+    dimension.  algorithm -1 is the library's own choice of the form of the INT8 products (the Strassen form at
+    c4 and c5b, which is what bench.py times), 0 the classical form.  c5b runs with k-blocks of half the inner
+    dimension each product walks (32768 of 65536 classical, 16384 of 32768 per half in the Strassen form) so
+    that the reduction between k-blocks is exercised; the result must still be bit-identical."""
     cfg = inputs.CONFIGS[name]
     m, n, k, phi = cfg["m"], cfg["n"], cfg["k"], cfg["phi"]
     N = 16 if name == "c4" else cfg["N"][-1]
@@ -261,15 +264,19 @@ def test_full_size_configs_on_sampled_outputs(name, kblock):
     dA = torch.from_numpy(A.T).cuda().t()
     dB = torch.from_numpy(B.T).cuda().t()
     dC = torch.full((n, m), float("nan"), dtype=torch.float64, device="cuda").t()
-    ws = oz.Workspace(m, n, k, N)
+    oz.oz2_set_gemm_algorithm(algorithm)
     if kblock:
         oz.oz2_set_kblock(kblock)
     try:
-        print("oz2_dgemm", flush=True)
+        ws = oz.Workspace(m, n, k, N)
+        strassen = oz.oz2_gemm_algorithm_for(m, n, k, N) == oz.OZ2_GEMM_STRASSEN
+        assert strassen == (algorithm == -1 and name in ("c4", "c5b"))
+        print("oz2_dgemm (%s form)" % ("Strassen" if strassen else "classical"), flush=True)
         oz.oz2_dgemm(m, n, k, dA.data_ptr(), m, dB.data_ptr(), k, dC.data_ptr(), m, N)
         torch.cuda.synchronize()
     finally:
         oz.oz2_set_kblock(65536)
+        oz.oz2_set_gemm_algorithm(oz.OZ2_GEMM_AUTO)
     assert not bool(torch.isnan(dC).any())
     got = dC[torch.from_numpy(rows).cuda()][:, torch.from_numpy(cols).cuda()].cpu().numpy()
     Asub = np.asfortranarray(A[rows, :])

@@ -220,3 +220,74 @@ def test_host_crt_extreme_int32_products():
         if y >= M - M // 2:
             y -= M
         assert oz.host_crt_element(N, c) == float(y)
+
+
+def test_strassen_form_sizes_and_choice_without_gpu():
+    L = oz.lib()
+    up = lambda v, a: (v + a - 1) // a * a
+    for (m, n, k, N) in [(16384, 16384, 16384, 16), (700, 900, 1100, 14), (1, 1, 1, 2), (8192, 8192, 65536, 18)]:
+        mh, nh, kh = up((m + 1) // 2, 256), up((n + 1) // 2, 256), up((k + 1) // 2, 64)
+        planes = 7 * N * (mh * kh + nh * kh) + max(7 * N, 16) * mh * nh
+        total = oz.workspace_bytes_strassen(m, n, k, N)
+        small = 2 * mh * (8 + 4 + 8) + 2 * nh * (8 + 4 + 8) + 256
+        assert planes + small <= total <= planes + small + 16 * 256
+    assert oz.workspace_bytes_strassen(-1, 4, 4, 4) == 0 and oz.workspace_bytes_strassen(4, 4, 4, 27) == 0
+    assert L.oz2_set_gemm_algorithm(2) == -1 and L.oz2_set_gemm_algorithm(-2) == -1
+    assert L.oz2_gemm_algorithm_for(-1, 4, 4, 4) == -1 and L.oz2_gemm_algorithm_for(4, 4, 4, 1) == -4
+    big = 16384
+    try:
+        oz.set_workspace(None, 0)
+        # automatic: the form is preferred at this size, but nothing is registered that could hold it
+        assert oz.workspace_bytes_preferred(big, big, big, 16) == oz.workspace_bytes_strassen(big, big, big, 16)
+        assert oz.workspace_bytes_preferred(4096, 4096, 4096, 16) == oz.workspace_bytes(4096, 4096, 4096, 16, oz.OZ2_PRODUCT_RESIDUE_U8)
+        assert oz.workspace_bytes_preferred(big, big, 8192, 16) == oz.workspace_bytes(big, big, 8192, 16, oz.OZ2_PRODUCT_RESIDUE_U8)
+        assert oz.oz2_gemm_algorithm_for(big, big, big, 16) == oz.OZ2_GEMM_CLASSICAL
+        oz.oz2_set_gemm_algorithm(oz.OZ2_GEMM_STRASSEN)
+        assert oz.oz2_gemm_algorithm_for(300, 200, 100, 16) == oz.OZ2_GEMM_STRASSEN
+        assert oz.oz2_gemm_algorithm_for(300, 0, 100, 16) == oz.OZ2_GEMM_CLASSICAL
+        oz.oz2_set_product_format(oz.OZ2_PRODUCT_INT32)   # the form needs residues in the product planes
+        assert oz.oz2_gemm_algorithm_for(300, 200, 100, 16) == oz.OZ2_GEMM_CLASSICAL
+        oz.oz2_set_product_format(oz.OZ2_PRODUCT_RESIDUE_U8)
+        oz.oz2_set_gemm_algorithm(oz.OZ2_GEMM_CLASSICAL)
+        assert oz.workspace_bytes_preferred(big, big, big, 16) == oz.workspace_bytes(big, big, big, 16, oz.OZ2_PRODUCT_RESIDUE_U8)
+    finally:
+        oz.oz2_set_product_format(oz.OZ2_PRODUCT_RESIDUE_U8)
+        oz.oz2_set_gemm_algorithm(oz.OZ2_GEMM_AUTO)
+
+
+def test_strassen_identities_reproduce_the_oracles_residues():
+    """The recipe of the Strassen form, carried out with numpy on the oracle's own INT8 planes: seven products of
+    block sums and differences, each operand brought back into [-128, 127] modulo p_t and each product formed in
+    INT32, recombined modulo p_t, must give the oracle's residues c''_t of Algorithm 1 line 7."""
+    rng = np.random.default_rng(31)
+    m, n, k, N = 10, 14, 12, 9
+    A = np.asfortranarray((rng.random((m, k)) - 0.5) * np.exp(rng.standard_normal((m, k))))
+    B = np.asfortranarray((rng.random((k, n)) - 0.5) * np.exp(rng.standard_normal((k, n))))
+    ref = orc.dgemm(A, B, N, want=("C", "Ares", "Bres", "Cres"))
+    mods = orc.moduli(N)
+    mh, nh, kh = m // 2, n // 2, k // 2
+
+    def int8(x, p):   # any representative in [-128, 127]
+        r = np.mod(x, p)
+        return np.where(r >= 128, r - p, r).astype(np.int64)
+
+    for t, p in enumerate(mods):
+        Ar = ref.Ares[t].astype(np.int64)            # m x k
+        Br = ref.Bres[t].astype(np.int64).T          # planes of B hold its columns as rows: back to k x n
+        A11, A12, A21, A22 = Ar[:mh, :kh], Ar[:mh, kh:], Ar[mh:, :kh], Ar[mh:, kh:]
+        B11, B12, B21, B22 = Br[:kh, :nh], Br[:kh, nh:], Br[kh:, :nh], Br[kh:, nh:]
+        ops = [(A11 + A22, B11 + B22), (A21 + A22, B11), (A11, B12 - B22), (A22, B21 - B11), (A11 + A12, B22),
+               (A21 - A11, B11 + B12), (A12 - A22, B21 + B22)]
+        M = []
+        for X, Y in ops:
+            X8, Y8 = int8(X, p), int8(Y, p)
+            assert np.abs(X8).max() <= 128 and np.abs(Y8).max() <= 128
+            prod = X8 @ Y8
+            assert np.abs(prod).max() < 2**31
+            M.append(np.mod(prod, p))
+        Cr = np.empty((m, n), dtype=np.int64)
+        Cr[:mh, :nh] = np.mod(M[0] + M[3] - M[4] + M[6], p)
+        Cr[:mh, nh:] = np.mod(M[2] + M[4], p)
+        Cr[mh:, :nh] = np.mod(M[1] + M[3], p)
+        Cr[mh:, nh:] = np.mod(M[0] - M[1] + M[2] + M[5], p)
+        assert np.array_equal(Cr, ref.Cres[t].astype(np.int64)), "modulus %d" % p
