@@ -36,6 +36,12 @@ __device__ __forceinline__ u16x2 sub_mod(u16x2 a, u16x2 b, u16x2 p) {
   const u16x2 d = a - b;
   return __builtin_elementwise_min(d, (u16x2)(d + p));
 }
+// a + b + c - d modulo p: a + b + c + (p - d) lies in (0, 4p), two conditional subtractions bring it below p
+__device__ __forceinline__ u16x2 sum4_mod(u16x2 a, u16x2 b, u16x2 c, u16x2 d, u16x2 p, u16x2 p2) {
+  u16x2 s = (a + b) + (c + (p - d));
+  s = __builtin_elementwise_min(s, (u16x2)(s - p2));
+  return __builtin_elementwise_min(s, (u16x2)(s - p));
+}
 __device__ __forceinline__ u16x2 as_pair(unsigned w) { return __builtin_bit_cast(u16x2, w); }
 __device__ __forceinline__ unsigned as_word(u16x2 v) { return __builtin_bit_cast(unsigned, v); }
 
@@ -112,8 +118,11 @@ __device__ __forceinline__ void strassen_convert(const StrassenJob& j, const Oz2
     }
   }
   const size_t plane_stride = (size_t)j.vh * j.kh;
-  int8_t* dst = j.planes + (size_t)(rq / kBlkRows) * kBlkRows * j.kh + (size_t)by * (kBlkRows * kBlkK) +
-                (rq % kBlkRows) * kBlkK + 4 * g;
+  // byte offset of this thread's four bytes inside a plane (below 2^32: checked by the launcher); the plane's
+  // base address is the same for the whole workgroup
+  const unsigned off = (unsigned)((size_t)(rq / kBlkRows) * kBlkRows * j.kh + (size_t)by * (kBlkRows * kBlkK) +
+                                  (rq % kBlkRows) * kBlkK + 4 * g);
+  int8_t* plane = j.planes;
   const int side = j.side;
   for (int t = 0; t < cc.N; ++t) {
     const double p = cc.p[t], ip = cc.inv_p[t], c32 = cc.c32[t], c64 = cc.c64[t];
@@ -163,7 +172,8 @@ __device__ __forceinline__ void strassen_convert(const StrassenJob& j, const Oz2
       const u16x2 f0 = c[s][0] + (c[s][0] >> 7) * ADJ;   // low bytes: v, or v - p when v >= 128
       const u16x2 f1 = c[s][1] + (c[s][1] >> 7) * ADJ;
       const unsigned w = __builtin_amdgcn_perm(as_word(f1), as_word(f0), 0x06040200u);
-      *reinterpret_cast<unsigned*>(dst + (size_t)(7 * t + s) * plane_stride) = w;
+      *reinterpret_cast<unsigned*>(plane + off) = w;
+      plane += plane_stride;
     }
   }
 }
@@ -194,11 +204,12 @@ __global__ void __launch_bounds__(kThreads) strassen_crt_kernel(const uint8_t* _
                                                                 double* __restrict__ C, int64_t ldc, int64_t m, int64_t n,
                                                                 const double alpha, const double beta,
                                                                 const unsigned long long* __restrict__ skip_flag,
-                                                                const Oz2CrtConsts cc) {
+                                                                const unsigned row_chunks, const Oz2CrtConsts cc) {
   if (skip_flag != nullptr && *skip_flag != 0ull) return;
   constexpr int R = kCrtRows;
-  const int64_t jq = blockIdx.x;
-  const int64_t i0 = ((int64_t)blockIdx.y * kThreads + threadIdx.x) * R;
+  // consecutive workgroups walk down a column of the half grid: their reads of a plane are adjacent
+  const int64_t jq = blockIdx.x / row_chunks;
+  const int64_t i0 = ((int64_t)(blockIdx.x % row_chunks) * kThreads + threadIdx.x) * R;
   if (i0 >= mh || i0 >= m) return;
   // two bytes = rows i0, i0 + 1 of one product plane (mh is a multiple of 256 and i0 is even: aligned)
   const unsigned short* src = reinterpret_cast<const unsigned short*>(planes + (size_t)jq * mh + i0);
@@ -245,11 +256,12 @@ __global__ void __launch_bounds__(kThreads) strassen_crt_kernel(const uint8_t* _
         u16x2 M[7];
 #pragma unroll
         for (int s = 0; s < 7; ++s) M[s] = as_pair(__builtin_amdgcn_perm(0u, cur[d][s], 0x0c010c00u));  // bytes -> 16-bit lanes
+        const u16x2 P2 = P + P;
         u16x2 c[4];
-        c[0] = add_mod(sub_mod(add_mod(M[0], M[3], P), M[4], P), M[6], P);  // C11 = M1 + M4 - M5 + M7
-        c[1] = add_mod(M[2], M[4], P);                                      // C12 = M3 + M5
-        c[2] = add_mod(M[1], M[3], P);                                      // C21 = M2 + M4
-        c[3] = add_mod(add_mod(sub_mod(M[0], M[1], P), M[2], P), M[5], P);  // C22 = M1 - M2 + M3 + M6
+        c[0] = sum4_mod(M[0], M[3], M[6], M[4], P, P2);  // C11 = M1 + M4 + M7 - M5
+        c[1] = add_mod(M[2], M[4], P);                   // C12 = M3 + M5
+        c[2] = add_mod(M[1], M[3], P);                   // C21 = M2 + M4
+        c[3] = sum4_mod(M[0], M[2], M[5], M[1], P, P2);  // C22 = M1 + M3 + M6 - M2
         double res[4][R];
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
@@ -309,6 +321,7 @@ hipError_t oz2_launch_strassen_convert(int transa, int transb, int64_t m, int64_
                                        const Oz2Layout& lay, char* ws, hipStream_t st) {
   const int64_t mh = lay.m_pad / 2, nh = lay.n_pad / 2, kh = lay.k_pad / 2;
   if (mh % kBlkRows || nh % kBlkRows || kh % kBlkK) return hipErrorInvalidValue;
+  if (mh * kh >= ((int64_t)1 << 32) || nh * kh >= ((int64_t)1 << 32)) return hipErrorInvalidValue;  // 32-bit offsets in a plane
   StrassenJob job[2];
   job[0] = {A, lda, m, k, mh, kh, reinterpret_cast<const int*>(ws + lay.off_sa), reinterpret_cast<int8_t*>(ws + lay.off_a),
             transa == 0 ? 1 : 0, 0, 0u, 0u};
@@ -345,12 +358,14 @@ hipError_t oz2_launch_strassen_crt(int64_t m, int64_t n, double alpha, double be
   const int* sb = reinterpret_cast<const int*>(ws + lay.off_sb);
   const int64_t rows = mh < m ? mh : m;  // rows of the half grid that hold an element of C
   const int64_t cols = nh < n ? nh : n;
-  dim3 grid((unsigned)cols, (unsigned)((rows + kThreads * kCrtRows - 1) / (kThreads * kCrtRows)));
+  const int64_t row_chunks = (rows + kThreads * kCrtRows - 1) / (kThreads * kCrtRows);
+  if (row_chunks * cols >= ((int64_t)1 << 31)) return hipErrorInvalidValue;
+  dim3 grid((unsigned)(row_chunks * cols));
   switch (plan.crt.L) {
 #define OZ2_CASE(LL)                                                                                                 \
   case LL:                                                                                                           \
     hipLaunchKernelGGL((strassen_crt_kernel<LL>), grid, dim3(kThreads), 0, st, planes, mh, nh, sa, sb, C, ldc, m, n, \
-                       alpha, beta, skip, plan.crt);                                                                 \
+                       alpha, beta, skip, (unsigned)row_chunks, plan.crt);                                           \
     break;
     OZ2_CASE(1)
     OZ2_CASE(2)
