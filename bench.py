@@ -144,11 +144,16 @@ def main():
     if strassen:
         roofline["note"] = ("achieved counts the INT8 operations executed (7 half-size products per modulus); "
                             "the classical count 2mnkN over the same time is %.2f TOP/s" % (2.0 * m * n * k * N / (gemm_ms * 1e-3) / 1e12))
-    if args.workload == "c4" and N == 16 and not args.mnk and args.shift_mode == 0 and not strassen:
+    if args.workload == "c4" and N == 16 and not args.mnk and args.shift_mode == 0:
         # HBM-side bytes per launch from the rocprofv3 counter runs summarised in
         # profiles/c4_oz2_dgemm_counters.md: FETCH_SIZE x 2.0 (copy-kernel scale) + WRITE_SIZE, in GiB, for the
-        # UINT8 and the INT32 product format
-        fetch_gib, write_gib, min_gib = (48.658, 8.051, 12) if fmt == oz.OZ2_PRODUCT_RESIDUE_U8 else (54.186, 19.125, 24)
+        # Strassen form (UINT8 planes), the classical form with UINT8 planes and the classical form with INT32 planes
+        if strassen:
+            fetch_gib, write_gib, min_gib = 43.151, 14.010, 21
+        elif fmt == oz.OZ2_PRODUCT_RESIDUE_U8:
+            fetch_gib, write_gib, min_gib = 48.658, 8.051, 12
+        else:
+            fetch_gib, write_gib, min_gib = 54.186, 19.125, 24
         roofline["traffic"] = round((fetch_gib * 2.0 + write_gib) * 2**30)
         roofline["traffic_unit"] = "bytes per launch (L2 misses + write-backs; algorithmic minimum %d GiB)" % min_gib
     stages = {
@@ -224,6 +229,19 @@ def main():
             per_n[str(Nx)] = round(2.0 * m * n * k / ((time.perf_counter() - t0) / 3) / 1e12, 2)
         per_n[str(N)] = round(tflops, 2)
         out["emulated_TFLOPS_per_num_moduli"] = dict(sorted(per_n.items()))
+        if strassen:
+            # the same call with Algorithm 1 line 6 as printed (one full-size INT8 product per modulus)
+            oz.oz2_set_gemm_algorithm(oz.OZ2_GEMM_CLASSICAL)
+            oz.oz2_dgemm(m, n, k, dA.data_ptr(), m, dB.data_ptr(), k, dC.data_ptr(), m, N, stream)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(3):
+                oz.oz2_dgemm(m, n, k, dA.data_ptr(), m, dB.data_ptr(), k, dC.data_ptr(), m, N, stream)
+            torch.cuda.synchronize()
+            cl_t = (time.perf_counter() - t0) / 3
+            oz.oz2_set_gemm_algorithm(args.gemm_algorithm)
+            out["classical_form_%d_moduli" % N] = {"ms_per_call": round(cl_t * 1e3, 3),
+                                                   "emulated_TFLOPS": round(2.0 * m * n * k / cl_t / 1e12, 2)}
         del ws
         ws = oz.Workspace(m, n, k, N, device=dev, product_format=fmt)
         oz.oz2_dgemm(m, n, k, dA.data_ptr(), m, dB.data_ptr(), k, dC.data_ptr(), m, N, stream)
