@@ -82,7 +82,9 @@ size_t oz2_workspace_bytes_for(int64_t m, int64_t n, int64_t k, int num_moduli, 
 int oz2_set_workspace(void* dev_ptr, size_t bytes);
 
 /* Where each intermediate lives inside the workspace for the product format in force, so that a test can read
- * every stage's output.
+ * every stage's output.  This is the layout of the classical form of the products and of the staged entry points;
+ * the Strassen form (oz2_set_gemm_algorithm) keeps the small arrays in this order on its own padded extents and
+ * holds seven planes of a quarter of the padded area per modulus in each plane region.
  * offsets[0..9] (bytes from the workspace start):
  *   0 rowmax  : m_pad uint64, bit pattern of max_l |a_il| per row of A
  *   1 colmax  : n_pad uint64, same per column of B
@@ -106,7 +108,9 @@ int oz2_workspace_layout(int64_t m, int64_t n, int64_t k, int num_moduli, size_t
 /* The whole of Algorithm 1:  C := A*B  with num_moduli INT8 products.
  *   A: m x k, lda >= max(1,m);  B: k x n, ldb >= max(1,k);  C: m x n, ldc >= max(1,m).
  * m == 0 or n == 0: nothing to do.  k == 0: C := 0.  Needs a registered workspace of at least
- * oz2_workspace_bytes(m,n,k,num_moduli).  Row-major callers pass (n,m,k,B,ldb,A,lda,C,ldc). */
+ * oz2_workspace_bytes_for(m,n,k,num_moduli, format in force); with oz2_workspace_bytes_preferred(m,n,k,num_moduli)
+ * large products take the faster Strassen form of line 6 (oz2_set_gemm_algorithm).  Row-major callers pass
+ * (n,m,k,B,ldb,A,lda,C,ldc). */
 int oz2_dgemm(int64_t m, int64_t n, int64_t k, const double* A, int64_t lda, const double* B, int64_t ldb,
               double* C, int64_t ldc, int num_moduli, void* stream);
 
