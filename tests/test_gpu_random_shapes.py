@@ -1,0 +1,76 @@
+"""GPU parity on seeded random problems: shapes, moduli counts, shift modes, transposes, scalars, leading dimensions
+and the form of the INT8 products are drawn at random; every result must be bit-identical with the oracle."""
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+import paper_2504_08009_amd as oz
+from oracle import oracle as orc
+
+
+def _dev(x):
+    return torch.from_numpy(np.ascontiguousarray(x.T)).cuda().t()
+
+
+def _draw(rng):
+    big = rng.random() < 0.25
+    hi = 1400 if big else 300
+    m, n, k = (int(rng.integers(1, hi + 1)) for _ in range(3))
+    N = int(rng.integers(2, 27))
+    mode = int(rng.integers(0, 3))
+    # a budget of at least one bit
+    while orc.kappa(N, k) < 1:
+        N += 1
+    phi = float(rng.choice([0.5, 1.0, 4.0]))
+    ta, tb = (str(rng.choice(["N", "T"])) for _ in range(2))
+    alpha, beta = ((1.0, 0.0) if rng.random() < 0.5 else (float(rng.normal()), float(rng.normal())))
+    algorithm = int(rng.choice([oz.OZ2_GEMM_CLASSICAL, oz.OZ2_GEMM_STRASSEN]))
+    pad = tuple(int(v) for v in rng.integers(0, 4, size=3))
+    return m, n, k, N, mode, phi, ta, tb, alpha, beta, algorithm, pad
+
+
+@pytest.mark.parametrize("seed", range(160))
+def test_random_problem_is_bit_identical_with_the_oracle(seed):
+    rng = np.random.default_rng(7000 + seed)
+    m, n, k, N, mode, phi, ta, tb, alpha, beta, algorithm, pad = _draw(rng)
+    opA = (rng.random((m, k)) - 0.5) * np.exp(phi * rng.standard_normal((m, k)))
+    opB = (rng.random((k, n)) - 0.5) * np.exp(phi * rng.standard_normal((k, n)))
+    # a few structural extremes: zero rows / columns, tiny and huge rows
+    if m > 3:
+        opA[int(rng.integers(m))] = 0.0
+        opA[int(rng.integers(m))] *= 2.0**-300
+    if n > 3:
+        opB[:, int(rng.integers(n))] = 0.0
+        opB[:, int(rng.integers(n))] *= 2.0**200
+    As = np.asfortranarray(opA.T if ta == "T" else opA)
+    Bs = np.asfortranarray(opB.T if tb == "T" else opB)
+    lda, ldb, ldc = As.shape[0] + pad[0], Bs.shape[0] + pad[1], m + pad[2]
+    Abig = np.full((lda, As.shape[1]), np.nan, order="F")
+    Abig[:As.shape[0]] = As
+    Bbig = np.full((ldb, Bs.shape[1]), np.nan, order="F")
+    Bbig[:Bs.shape[0]] = Bs
+    C0 = np.asfortranarray(rng.standard_normal((m, n)))
+    if beta == 0.0:
+        C0[:] = np.nan
+    Cbig = np.full((ldc, n), 3.0, order="F")
+    Cbig[:m] = C0
+    dA, dB, dC = _dev(Abig), _dev(Bbig), _dev(Cbig)
+    print("seed %d: m=%d n=%d k=%d N=%d mode=%d phi=%g op=%s%s alpha=%g beta=%g algorithm=%d ld+%s"
+          % (seed, m, n, k, N, mode, phi, ta, tb, alpha, beta, algorithm, pad), flush=True)
+    oz.oz2_set_gemm_algorithm(algorithm)
+    oz.oz2_set_shift_mode(mode)
+    try:
+        ws = oz.Workspace(m, n, k, N)
+        oz.oz2_dgemm_ex(ta, tb, m, n, k, alpha, dA.data_ptr(), lda, dB.data_ptr(), ldb, beta, dC.data_ptr(), ldc, N)
+        torch.cuda.synchronize()
+    finally:
+        oz.oz2_set_gemm_algorithm(oz.OZ2_GEMM_AUTO)
+        oz.oz2_set_shift_mode(0)
+    got = dC.cpu().numpy()
+    ref = orc.dgemm_ex(ta, tb, alpha, As, Bs, beta, C0, N, mode=mode)
+    assert np.array_equal(got[:m], ref)
+    assert np.all(got[m:] == 3.0)
+    del ws
