@@ -17,6 +17,7 @@
 namespace {
 
 constexpr int kThreads = 256;
+typedef unsigned v4u __attribute__((ext_vector_type(4)));
 
 __global__ void __launch_bounds__(kThreads) fill_u64_kernel(unsigned long long* p, int64_t count) {
   int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
@@ -350,7 +351,8 @@ __device__ __forceinline__ void convert_strided(const double* __restrict__ A, in
     v.y = pack4(r[4], r[5], r[6], r[7]);
     v.z = pack4(r[8], r[9], r[10], r[11]);
     v.w = pack4(r[12], r[13], r[14], r[15]);
-    *reinterpret_cast<uint4*>(dst + (size_t)t * plane_stride) = v;
+    // written once, read by a later kernel: non-temporal store
+    __builtin_nontemporal_store(v4u{v.x, v.y, v.z, v.w}, reinterpret_cast<v4u*>(dst + (size_t)t * plane_stride));
   }
 }
 
@@ -408,7 +410,8 @@ __device__ __forceinline__ void convert_contig(const double* __restrict__ B, int
     v.y = pack4(r[4], r[5], r[6], r[7]);
     v.z = pack4(r[8], r[9], r[10], r[11]);
     v.w = pack4(r[12], r[13], r[14], r[15]);
-    *reinterpret_cast<uint4*>(dst + (size_t)t * plane_stride) = v;
+    // written once, read by a later kernel: non-temporal store
+    __builtin_nontemporal_store(v4u{v.x, v.y, v.z, v.w}, reinterpret_cast<v4u*>(dst + (size_t)t * plane_stride));
   }
 }
 

@@ -17,7 +17,7 @@ struct PlaneLoad;
 template <>
 struct PlaneLoad<false> {
   static constexpr int R = 4;
-  typedef int4 Raw;
+  typedef int Raw __attribute__((ext_vector_type(4)));
   static __device__ __forceinline__ void residues(const Raw& c, double p, double ip, double hip_, double* res) {
     res[0] = oz2_floor_mod(c.x, p, ip, hip_);
     res[1] = oz2_floor_mod(c.y, p, ip, hip_);
@@ -28,7 +28,7 @@ struct PlaneLoad<false> {
 template <>
 struct PlaneLoad<true> {
   static constexpr int R = 8;
-  typedef uint2 Raw;
+  typedef unsigned Raw __attribute__((ext_vector_type(2)));
   static __device__ __forceinline__ void residues(const Raw& c, double, double, double, double* res) {
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
@@ -67,13 +67,13 @@ __global__ void __launch_bounds__(kThreads) crt_kernel(const void* __restrict__ 
 #pragma unroll
     for (int l = 0; l < L; ++l) S[r][l] = 0.0;
 
-  // Planes are read a batch ahead of the arithmetic: kBatch loads per thread in flight keep enough bytes
+  // Planes are read once (non-temporal loads), a batch ahead of the arithmetic: kBatch loads per thread in flight keep enough bytes
   // moving per CU to cover the memory latency (one load ahead does not).
   constexpr int kBatch = 4;
   const int N = cc.N;
   Raw nxt[kBatch];
 #pragma unroll
-  for (int d = 0; d < kBatch; ++d) nxt[d] = src[(size_t)(d < N ? d : N - 1) * stride];
+  for (int d = 0; d < kBatch; ++d) nxt[d] = __builtin_nontemporal_load(src + (size_t)(d < N ? d : N - 1) * stride);
   for (int t0 = 0; t0 < N; t0 += kBatch) {
     Raw cur[kBatch];
 #pragma unroll
@@ -82,7 +82,7 @@ __global__ void __launch_bounds__(kThreads) crt_kernel(const void* __restrict__ 
 #pragma unroll
       for (int d = 0; d < kBatch; ++d) {
         const int t = t0 + kBatch + d;
-        nxt[d] = src[(size_t)(t < N ? t : N - 1) * stride];  // past the end: a harmless repeat of the last plane
+        nxt[d] = __builtin_nontemporal_load(src + (size_t)(t < N ? t : N - 1) * stride);  // past the end: a harmless repeat of the last plane
       }
     }
 #pragma unroll
