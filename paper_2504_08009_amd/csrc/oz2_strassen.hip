@@ -88,7 +88,7 @@ __device__ __forceinline__ void strassen_convert(const StrassenJob& j, const Oz2
       for (int it = 0; it < kBlkK / 4; ++it) {
         const int lc = 4 * it + c0;
         const int64_t l = l0 + lc + b * j.kh;
-        dstq[vv * kPitch + lc] = (v < j.nvec && l < j.k) ? src[l * j.ld] : 0.0;
+        dstq[vv * kPitch + lc] = (v < j.nvec && l < j.k) ? __builtin_nontemporal_load(src + l * j.ld) : 0.0;
       }
     } else {
       const int64_t l = l0 + lane + b * j.kh;
@@ -96,7 +96,7 @@ __device__ __forceinline__ void strassen_convert(const StrassenJob& j, const Oz2
 #pragma unroll 8
       for (int vv = 0; vv < kVecs; ++vv) {
         const int64_t v = r0 + vv + a * j.vh;
-        dstq[vv * kPitch + lane] = (v < j.nvec && l < j.k) ? src[v * j.ld] : 0.0;
+        dstq[vv * kPitch + lane] = (v < j.nvec && l < j.k) ? __builtin_nontemporal_load(src + v * j.ld) : 0.0;
       }
     }
   }
