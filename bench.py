@@ -220,7 +220,7 @@ def main():
     # the metric is quoted per number of moduli: same workload, N = 14 .. 18 (a few calls each, outside the
     # timed region of the headline number above)
     if args.workload == "c4" and not args.no_context and not args.mnk:
-        per_n = {}
+        per_n, err_n = {}, {}
         for Nx in (14, 15, 17, 18):
             del ws
             ws = oz.Workspace(m, n, k, Nx, device=dev, product_format=fmt)
@@ -231,8 +231,15 @@ def main():
                 oz.oz2_dgemm(m, n, k, dA.data_ptr(), m, dB.data_ptr(), k, dC.data_ptr(), m, Nx, stream)
             torch.cuda.synchronize()
             per_n[str(Nx)] = round(2.0 * m * n * k / ((time.perf_counter() - t0) / 3) / 1e12, 2)
+            if not args.no_cpu_baseline:
+                # error of the same sample of C against the exact product (the reference was formed above)
+                gx = dC[torch.from_numpy(rows).to(dev)][:, torch.from_numpy(cols).to(dev)].cpu().numpy()
+                err_n[str(Nx)] = float(np.max(np.abs(gx - Cx) / S))
         per_n[str(N)] = round(tflops, 2)
         out["emulated_TFLOPS_per_num_moduli"] = dict(sorted(per_n.items()))
+        if not args.no_cpu_baseline:
+            err_n[str(N)] = out["accuracy"]["max_componentwise_err_vs_exact"]
+            out["max_componentwise_err_per_num_moduli"] = dict(sorted(err_n.items()))
         if strassen:
             # the same call with Algorithm 1 line 6 as printed (one full-size INT8 product per modulus)
             oz.oz2_set_gemm_algorithm(oz.OZ2_GEMM_CLASSICAL)
