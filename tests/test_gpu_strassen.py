@@ -251,3 +251,30 @@ def test_strassen_form_in_a_hip_graph():
             assert np.array_equal(got, dE.cpu().numpy())
             assert np.array_equal(got, orc.dgemm(A, B, N).C)
         del graph, ws
+
+
+def test_strassen_form_chosen_by_itself_at_a_large_ragged_size():
+    """Just above the sizes from which the library takes the Strassen form by itself, with nothing a multiple of a
+    tile: halves of 17 x 17 tiles (outside the super-block order of the GEMM), a ragged last tile in every
+    dimension, the second halves one element shorter than the first.  Sampled rows and columns, among them both
+    sides of the half boundaries and the last ones, against the oracle."""
+    m, n, k, N, phi = 8193, 8447, 12289, 15, 1.0
+    A = inputs.block(77, 0, m, k, phi)
+    B = inputs.block(77, 1, k, n, phi)
+    rng = np.random.default_rng(13)
+    mh, nh = 4352, 4352   # halves: ceil(m/2), ceil(n/2) rounded up to 256
+    rows = np.unique(np.concatenate([[0, mh - 1, mh, m - 1, 4096, 4097], rng.choice(m, 20, replace=False)]))
+    cols = np.unique(np.concatenate([[0, nh - 1, nh, n - 1, 4223, 4224], rng.choice(n, 20, replace=False)]))
+    dA = torch.from_numpy(A.T).cuda().t()
+    dB = torch.from_numpy(B.T).cuda().t()
+    dC = torch.full((n, m), float("nan"), dtype=torch.float64, device="cuda").t()
+    ws = oz.Workspace(m, n, k, N)
+    assert oz.oz2_gemm_algorithm_for(m, n, k, N) == oz.OZ2_GEMM_STRASSEN
+    print("strassen (automatic) m=%d n=%d k=%d N=%d" % (m, n, k, N), flush=True)
+    oz.oz2_dgemm(m, n, k, dA.data_ptr(), m, dB.data_ptr(), k, dC.data_ptr(), m, N)
+    torch.cuda.synchronize()
+    assert not bool(torch.isnan(dC).any())
+    got = dC[torch.from_numpy(rows).cuda()][:, torch.from_numpy(cols).cuda()].cpu().numpy()
+    ref = orc.dgemm(np.asfortranarray(A[rows, :]), np.asfortranarray(B[:, cols]), N).C
+    assert np.array_equal(got, ref)
+    del ws
