@@ -198,6 +198,7 @@ __global__ void __launch_bounds__(kThreads) strassen_convert_kernel(const Strass
 // plain CRT kernel does (Algorithm 1 lines 9-11).
 // ---------------------------------------------------------------------------------------------------
 constexpr int kCrtRows = 2;  // rows per thread: 8 elements of C, 32 accumulators of two registers at four limbs
+static_assert(kCrtRows == 2, "the kernel below loads two bytes per plane and stores two doubles per block");
 template <int L>
 __global__ void __launch_bounds__(kThreads) strassen_crt_kernel(const uint8_t* __restrict__ planes, int64_t mh, int64_t nh,
                                                                 const int* __restrict__ sa, const int* __restrict__ sb,
