@@ -329,7 +329,22 @@ def main():
         nat_ms = e0.elapsed_time(e1) / 3
         out["context"] = {"native_fp64_gemm_TFLOPS_same_gpu": round(2.0 * m * n * k / (nat_ms * 1e-3) / 1e12, 2),
                           "paper_GH200_OSII_fast_16_n16384_TFLOPS": 70.4, "paper_GH200_DGEMM_n16384_TFLOPS": 60.9}
-        # context only: the same MFMA instruction with no memory traffic, constant vs random INT8 operands
+        # context only: the vendor library's INT8 GEMM with INT32 output on one plane of the same shape (random
+        # bytes, both operands with the inner dimension contiguous: its faster layout)
+        try:
+            ia = torch.randint(-128, 128, (m, k), dtype=torch.int8, device=dev)
+            ib = torch.randint(-128, 128, (n, k), dtype=torch.int8, device=dev).t()
+            torch._int_mm(ia, ib)
+            torch.cuda.synchronize()
+            e0.record()
+            for _ in range(3):
+                torch._int_mm(ia, ib)
+            e1.record()
+            torch.cuda.synchronize()
+            out["context"]["vendor_int8_gemm_TOPs_same_gpu"] = round(2.0 * m * n * k / (e0.elapsed_time(e1) / 3 * 1e-3) / 1e12, 1)
+            del ia, ib
+        except Exception:   # not every build of the framework carries this routine
+            pass
         sink = torch.empty(512 * 256, dtype=torch.int32, device=dev)
         clocks = torch.zeros(2, dtype=torch.int64, device=dev)
         for label, rnd in (("constant", 0), ("random", 1)):
