@@ -291,3 +291,14 @@ def test_strassen_identities_reproduce_the_oracles_residues():
         Cr[mh:, :nh] = np.mod(M[1] + M[3], p)
         Cr[mh:, nh:] = np.mod(M[0] - M[1] + M[2] + M[5], p)
         assert np.array_equal(Cr, ref.Cres[t].astype(np.int64)), "modulus %d" % p
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """The path runs on one GPU: bench.py --gpus N with N above 1 exits with a message and touches no GPU."""
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True,
+                       timeout=120)
+    assert r.returncode != 0
+    assert "one GPU" in r.stderr
+    assert r.stdout.strip() == ""
