@@ -49,6 +49,7 @@ class _Settings:
     (2100, 3, 5000, 16, 0.5, 0),      # long inner dimension against a sliver of C
     (700, 900, 1100, 14, 1.0, 1),     # Cauchy-Schwarz shifts
     (520, 300, 700, 12, 4.0, 2),      # shifts from the INT8 product of bounds (its planes share the regions)
+    (40, 30, 300000, 12, 0.5, 0),     # halves of 150016 > 2^17: three k-blocks per product by INT32 exactness alone
 ])
 def test_strassen_form_is_bit_identical_with_the_oracle(m, n, k, N, phi, mode):
     rng = np.random.default_rng(m * 1000 + n + mode)
