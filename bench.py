@@ -329,6 +329,18 @@ def main():
         nat_ms = e0.elapsed_time(e1) / 3
         out["context"] = {"native_fp64_gemm_TFLOPS_same_gpu": round(2.0 * m * n * k / (nat_ms * 1e-3) / 1e12, 2),
                           "paper_GH200_OSII_fast_16_n16384_TFLOPS": 70.4, "paper_GH200_DGEMM_n16384_TFLOPS": 60.9}
+        # context only: what a plain device copy of A (read 8mk bytes, write 8mk bytes) sustains on this card, the
+        # practical ceiling for the memory-bound stages
+        tmp = torch.empty_like(dA)
+        tmp.copy_(dA)
+        torch.cuda.synchronize()
+        e0.record()
+        for _ in range(5):
+            tmp.copy_(dA)
+        e1.record()
+        torch.cuda.synchronize()
+        out["context"]["device_copy_GBps_same_gpu"] = round(2 * 8.0 * m * k / (e0.elapsed_time(e1) / 5 * 1e-3) / 1e9, 1)
+        del tmp
         # context only: the vendor library's INT8 GEMM with INT32 output on one plane of the same shape (random
         # bytes, both operands with the inner dimension contiguous: its faster layout)
         try:
