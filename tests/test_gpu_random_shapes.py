@@ -74,3 +74,72 @@ def test_random_problem_is_bit_identical_with_the_oracle(seed):
     assert np.array_equal(got[:m], ref)
     assert np.all(got[m:] == 3.0)
     del ws
+
+
+@pytest.mark.parametrize("seed", range(60))
+def test_random_structured_problem_is_bit_identical_with_the_oracle(seed):
+    """Symmetric rank-k updates and in-place triangular products with random shapes and options."""
+    rng = np.random.default_rng(9000 + seed)
+    N = int(rng.integers(4, 27))
+    mode = int(rng.integers(0, 3))
+    phi = float(rng.choice([0.5, 1.0, 4.0]))
+    hi = 700 if rng.random() < 0.3 else 260
+    oz.oz2_set_shift_mode(mode)
+    try:
+        if seed % 2 == 0:
+            n, k = int(rng.integers(1, hi + 1)), int(rng.integers(1, hi + 1))
+            while orc.kappa(N, k) < 1:
+                N += 1
+            uplo, trans = str(rng.choice(["L", "U"])), str(rng.choice(["N", "T"]))
+            alpha, beta = float(rng.normal()), float(rng.choice([0.0, 1.0, rng.normal()]))
+            opA = (rng.random((n, k)) - 0.5) * np.exp(phi * rng.standard_normal((n, k)))
+            As = np.asfortranarray(opA.T if trans == "T" else opA)
+            lda, ldc = As.shape[0] + int(rng.integers(0, 3)), n + int(rng.integers(0, 3))
+            Abig = np.full((lda, As.shape[1]), np.nan, order="F")
+            Abig[:As.shape[0]] = As
+            C0 = np.asfortranarray(rng.standard_normal((n, n)))
+            ii, jj = np.meshgrid(np.arange(n), np.arange(n), indexing="ij")
+            outside = (ii < jj) if uplo == "L" else (ii > jj)
+            Cbig = np.full((ldc, n), -2.0, order="F")
+            Cbig[:n] = np.where(outside, np.nan, C0)        # the other triangle is never read or written
+            dA, dC = _dev(Abig), _dev(Cbig)
+            print("seed %d: dsyrk %s%s n=%d k=%d N=%d mode=%d phi=%g alpha=%g beta=%g" % (seed, uplo, trans, n, k, N, mode, phi, alpha, beta),
+                  flush=True)
+            ws = oz.Workspace(n, n, k, N)
+            oz.oz2_dsyrk(uplo, trans, n, k, alpha, dA.data_ptr(), lda, beta, dC.data_ptr(), ldc, N)
+            torch.cuda.synchronize()
+            got = dC.cpu().numpy()
+            ref = orc.dsyrk(uplo, trans, alpha, As, beta, np.asfortranarray(np.where(outside, 0.0, C0)), N, mode=mode)
+            assert np.all(np.isnan(got[:n][outside])) and np.all(got[n:] == -2.0)
+            assert np.array_equal(got[:n][~outside], ref[~outside])
+        else:
+            m, n = int(rng.integers(1, hi + 1)), int(rng.integers(1, hi + 1))
+            side, uplo = str(rng.choice(["L", "R"])), str(rng.choice(["L", "U"]))
+            transa, diag = str(rng.choice(["N", "T"])), str(rng.choice(["N", "U"]))
+            ka = m if side == "L" else n
+            while orc.kappa(N, ka) < 1:
+                N += 1
+            alpha = float(rng.normal())
+            A = (rng.random((ka, ka)) - 0.5) * np.exp(phi * rng.standard_normal((ka, ka)))
+            B = np.asfortranarray((rng.random((m, n)) - 0.5) * np.exp(phi * rng.standard_normal((m, n))))
+            G = A.copy()                                    # NaN wherever the routine must not look
+            ii, jj = np.meshgrid(np.arange(ka), np.arange(ka), indexing="ij")
+            G[(ii < jj) if uplo == "L" else (ii > jj)] = np.nan
+            if diag == "U":
+                G[np.arange(ka), np.arange(ka)] = np.nan
+            G = np.asfortranarray(G)
+            ldb = m + int(rng.integers(0, 3))
+            hB = np.full((ldb, n), 7.0, order="F")
+            hB[:m] = B
+            dA, dB = _dev(G), _dev(hB)
+            print("seed %d: dtrmm %s%s%s%s m=%d n=%d N=%d mode=%d phi=%g alpha=%g" % (seed, side, uplo, transa, diag, m, n, N, mode, phi, alpha),
+                  flush=True)
+            ws = oz.Workspace(m, n, ka, N)
+            oz.oz2_dtrmm(side, uplo, transa, diag, m, n, alpha, dA.data_ptr(), ka, dB.data_ptr(), ldb, N)
+            torch.cuda.synchronize()
+            got = dB.cpu().numpy()
+            ref = orc.dtrmm(side, uplo, transa, diag, alpha, G, B, N, mode=mode)
+            assert np.array_equal(got[:m], ref) and np.all(got[m:] == 7.0)
+        del ws
+    finally:
+        oz.oz2_set_shift_mode(0)
