@@ -43,8 +43,8 @@ def main():
                     help="also run one plain device copy of A (known size) so that rocprofv3 byte counters can be scaled")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build runs on one GPU only (the path needs no exchange between GPUs; "
-              "see DESIGN.md on sharding). Use --gpus 1.", file=sys.stderr)
+        print("bench.py: this build runs on one GPU only (the path needs no exchange between GPUs: each would take "
+              "its own tile of C with its own panels of A and B). Use --gpus 1.", file=sys.stderr)
         sys.exit(2)
 
     import numpy as np
