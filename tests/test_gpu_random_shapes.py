@@ -143,3 +143,31 @@ def test_random_structured_problem_is_bit_identical_with_the_oracle(seed):
         del ws
     finally:
         oz.oz2_set_shift_mode(0)
+
+
+@pytest.mark.parametrize("algorithm", [0, 1])
+@pytest.mark.parametrize("mode", [0, 1, 2])
+def test_subnormal_inputs_match_the_oracle(algorithm, mode):
+    """Rows and columns of subnormal numbers, subnormals mixed into normal rows, and a huge column: the shifts come
+    from the bit patterns of the maxima, so nothing special happens; the results (some of them subnormal or zero
+    after the final scaling) are the oracle's."""
+    rng = np.random.default_rng(5)
+    m, n, k, N = 70, 50, 90, 14
+    A = np.asfortranarray((rng.random((m, k)) - 0.5) * np.exp(rng.standard_normal((m, k))))
+    B = np.asfortranarray((rng.random((k, n)) - 0.5) * np.exp(rng.standard_normal((k, n))))
+    A[3] *= 2.0**-1040
+    A[5, ::2] *= 2.0**-1060
+    B[:, 7] *= 2.0**-1030
+    B[:, 9] *= 2.0**600
+    assert np.any((A != 0) & (np.abs(A) < 2.0**-1022)) and np.any((B != 0) & (np.abs(B) < 2.0**-1022))
+    oz.oz2_set_gemm_algorithm(algorithm)
+    oz.oz2_set_shift_mode(mode)
+    try:
+        ws = oz.Workspace(m, n, k, N)
+        C = oz.dgemm(_dev(A), _dev(B), N, workspace=ws)
+        torch.cuda.synchronize()
+    finally:
+        oz.oz2_set_gemm_algorithm(oz.OZ2_GEMM_AUTO)
+        oz.oz2_set_shift_mode(0)
+    assert np.array_equal(C.cpu().numpy(), orc.dgemm(A, B, N, mode=mode).C)
+    del ws
