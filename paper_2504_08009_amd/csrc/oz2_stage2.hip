@@ -31,8 +31,11 @@
 // 8 x 4 block of tiles and share A' and B' panels in that XCD's L2.  When the tile grid is a multiple of
 // 16 x 16 the eight XCDs additionally work on the eight 8 x 4 sub-blocks of one 16 x 16 super-block at the
 // same time, so that panels re-read by several XCDs come from the shared last-level cache instead of HBM
-// (measured: same L2 miss count, higher clock under the power cap, +6 % throughput).  Otherwise each XCD
-// walks its own contiguous range of tiles in 8-tile-tall column groups.
+// (measured: same L2 miss count, higher clock under the power cap, +6 % throughput).  Tile grids that are
+// multiples of 8 x 4 only (24 x 24, 40 x 40 tiles ...) get the same effect from a list of all 8 x 4 sub-blocks, of
+// which the eight XCDs take eight consecutive entries per round (a kernel instantiation of its own, LIST_ORDER,
+// so that the tile decoding of the other orders stays as it is; measured: GEMM -2 % at 6144^3, -4 % at 10240^3).
+// Otherwise each XCD walks its own contiguous range of tiles in 8-tile-tall column groups.
 //
 // General products are launched with one workgroup per compute unit; each walks the work indices of its slot in
 // launch order (so the mapping above is unchanged) and issues the first copies of its next tile before the
@@ -119,6 +122,7 @@ struct Tile {
 
 // Work index -> tile.  `slot` counts workgroup slots in launch order: slot % 8 is the XCD a workgroup of a plain
 // launch would land on, and the persistent loop keeps that residue (its stride is a multiple of 8).
+template <bool LIST_ORDER>
 __device__ __forceinline__ Tile decode_tile(const GemmArgs& g, int slot, int wv) {
   Tile T;
   T.valid = false;
@@ -127,7 +131,21 @@ __device__ __forceinline__ Tile decode_tile(const GemmArgs& g, int slot, int wv)
   T.t = T.tm = T.tn = 0;
   if (slot >= g.chunk * 8) return T;
   int t, tm, tn;
-  if (g.superblock) {
+  if constexpr (LIST_ORDER) {
+    // The 8 x 4 sub-blocks of all planes form one list (plane by plane, down the columns of sub-blocks); in a
+    // round the eight XCDs take eight consecutive entries, i.e. neighbouring sub-blocks whose A' and B' panels
+    // they share through the last-level cache.  g.chunk counts whole rounds of 32 tiles per XCD here.
+    const int x = slot & 7, idx = slot >> 3;
+    const int rnd = idx >> 5, within = idx & 31;
+    const int sub_m = g.tiles_m >> 3, per_plane = sub_m * (g.tiles_n >> 2);
+    const int entry = rnd * 8 + x;
+    t = entry / per_plane;
+    if (t >= g.num_moduli) return T;
+    const int r = entry - t * per_plane;
+    const int sn = r / sub_m, sm = r - sn * sub_m;
+    tm = sm * 8 + (within & 7);
+    tn = sn * 4 + (within >> 3);
+  } else if (g.superblock) {
     // all eight XCDs work inside one 16 x 16 super-block of tiles at a time; XCD x owns the 8 x 4
     // sub-block (x & 1, x >> 1), so A' and B' panels missed by one L2 are found in the shared cache
     const int x = slot & 7, idx = slot >> 3;
@@ -185,7 +203,7 @@ __device__ __forceinline__ Tile decode_tile(const GemmArgs& g, int slot, int wv)
   return T;
 }
 
-template <bool RESIDUE_U8>
+template <bool RESIDUE_U8, bool LIST_ORDER>
 __global__ void __launch_bounds__(kThreads) gemm_i8_kernel(const GemmArgs g) {
   extern __shared__ __attribute__((aligned(1024))) char lds[];
 
@@ -201,10 +219,10 @@ __global__ void __launch_bounds__(kThreads) gemm_i8_kernel(const GemmArgs g) {
   // workgroup slots of the chip the loop keeps the launch order and lets the first copies of the next tile
   // fly while the current tile's epilogue runs.
   int slot = blockIdx.x;
-  Tile cur = decode_tile(g, slot, wv);
+  Tile cur = decode_tile<LIST_ORDER>(g, slot, wv);
   while (!cur.valid && slot < g.chunk * 8) {
     slot += gridDim.x;
-    cur = decode_tile(g, slot, wv);
+    cur = decode_tile<LIST_ORDER>(g, slot, wv);
   }
   if (!cur.valid) return;
 
@@ -354,7 +372,7 @@ __global__ void __launch_bounds__(kThreads) gemm_i8_kernel(const GemmArgs g) {
   nxt.valid = false;
   do {
     slot += gridDim.x;
-    nxt = decode_tile(g, slot, wv);
+    nxt = decode_tile<LIST_ORDER>(g, slot, wv);
   } while (!nxt.valid && slot < g.chunk * 8);
   if (nxt.valid) {
     __syncthreads();
@@ -436,11 +454,13 @@ namespace {
 int g_cus = 0;
 hipError_t gemm_setup() {
   if (g_cus) return hipSuccess;
-  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_i8_kernel<false>),
-                                     hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
-  if (e == hipSuccess)
-    e = hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_i8_kernel<true>),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
+  const void* kernels[4] = {reinterpret_cast<const void*>(gemm_i8_kernel<false, false>),
+                            reinterpret_cast<const void*>(gemm_i8_kernel<true, false>),
+                            reinterpret_cast<const void*>(gemm_i8_kernel<false, true>),
+                            reinterpret_cast<const void*>(gemm_i8_kernel<true, true>)};
+  hipError_t e = hipSuccess;
+  for (int i = 0; i < 4 && e == hipSuccess; ++i)
+    e = hipFuncSetAttribute(kernels[i], hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
   if (e != hipSuccess) return e;
   int dev = 0, n = 0;
   if ((e = hipGetDevice(&dev)) != hipSuccess) return e;
@@ -475,6 +495,11 @@ hipError_t launch_gemm(const Oz2Layout& lay, char* ws, int num_moduli, const int
   g.total = (int)total;
   g.chunk = (int)((total + 7) / 8);
   g.superblock = (g.tiles_m % 16 == 0 && g.tiles_n % 16 == 0) ? 1 : 0;
+  // list order of the 8 x 4 sub-blocks: general products whose tile grid is a multiple of 8 x 4 but not of 16 x 16
+  // (and at least eight rounds of them: with a handful of sub-blocks the range order spreads the tiles better)
+  const bool list_order = !g.superblock && triangle == 0 && krange == OZ2_KRANGE_ALL && g.tiles_m % 8 == 0 &&
+                          g.tiles_n % 4 == 0 && total / 32 >= 64;
+  if (list_order) g.chunk = (int)((total / 32 + 7) / 8) * 32;  // whole rounds of 32 tiles per XCD
   g.ktiles = (int)(lay.k_pad / BK);
   g.ktiles_per_block = (int)(kblock / BK);
   for (int t = 0; t < OZ2_MAX_PLANES; ++t) g.p[t] = t < num_moduli ? (float)moduli[t] : 1.0f;
@@ -496,12 +521,21 @@ hipError_t launch_gemm(const Oz2Layout& lay, char* ws, int num_moduli, const int
       const int per_xcd = (int)grid / 8;
       const int last = g.total - 7 * g.chunk;  // work items of XCD 7
       g.full_rounds = g.superblock ? (g.chunk * 8) / (int)grid : (last > 0 ? last / per_xcd : 0);
+      // list order: the rounds in which all eight XCDs have a sub-block, when a round of the launch (32 workgroups
+      // per XCD) is a round of the list
+      if (list_order) g.full_rounds = per_xcd == 32 ? (int)(total / 256) : 0;
     }
   }
-  if (residue_u8)
-    hipLaunchKernelGGL(gemm_i8_kernel<true>, dim3(grid), dim3(kThreads), kLdsBytes, st, g);
-  else
-    hipLaunchKernelGGL(gemm_i8_kernel<false>, dim3(grid), dim3(kThreads), kLdsBytes, st, g);
+  if (list_order) {
+    if (residue_u8)
+      hipLaunchKernelGGL((gemm_i8_kernel<true, true>), dim3(grid), dim3(kThreads), kLdsBytes, st, g);
+    else
+      hipLaunchKernelGGL((gemm_i8_kernel<false, true>), dim3(grid), dim3(kThreads), kLdsBytes, st, g);
+  } else if (residue_u8) {
+    hipLaunchKernelGGL((gemm_i8_kernel<true, false>), dim3(grid), dim3(kThreads), kLdsBytes, st, g);
+  } else {
+    hipLaunchKernelGGL((gemm_i8_kernel<false, false>), dim3(grid), dim3(kThreads), kLdsBytes, st, g);
+  }
   return hipGetLastError();
 }
 

@@ -123,6 +123,18 @@ def test_ragged_shapes(m, n, k, N, phi, fmt):
     check_against_oracle(A, B, N, fmt=fmt)
 
 
+@pytest.mark.parametrize("fmt", [0, 1])
+def test_tile_grid_of_8_by_12_all_stages(fmt):
+    """A tile grid that is a multiple of 8 x 4 but not of 16 x 16, with enough planes that the GEMM takes the list
+    order of its 8 x 4 sub-blocks (3 per plane, 66 in all: eight full rounds of the eight XCDs and a last one with
+    two entries); every plane is compared."""
+    rng = np.random.default_rng(88)
+    m, n, k, N = 2048, 3072, 70, 22
+    A = np.asfortranarray((rng.random((m, k)) - 0.5) * np.exp(rng.standard_normal((m, k))))
+    B = np.asfortranarray((rng.random((k, n)) - 0.5) * np.exp(rng.standard_normal((k, n))))
+    check_against_oracle(A, B, N, fmt=fmt)
+
+
 def test_zero_rows_columns_and_extreme_exponents():
     rng = np.random.default_rng(77)
     m, n, k, N = 70, 90, 200, 16
