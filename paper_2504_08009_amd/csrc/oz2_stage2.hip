@@ -514,7 +514,10 @@ hipError_t launch_gemm(const Oz2Layout& lay, char* ws, int num_moduli, const int
     // General products: the workgroups of an XCD start the tiles of a round together, which keeps them
     // on the same k-tiles of their shared panels (measured: L2 misses 48.7 GiB per launch every time instead of
     // 50-54 GiB, and 83 GiB in some runs).  The counters are words 8..15 of the flag words that stage 1 clears.
-    if (num_moduli > 1) {
+    // Only for inner dimensions above 6144: shorter panels stay in the L2 anyway and the wait for the slowest
+    // workgroup of every round costs more than it saves (measured without it: -10 % at k = 1024, -6 % at 2048,
+    // -4 % at 4096, -3 % at 6144, -1.5 % at 8192 with 64 rounds but +1 % at 8192 with 448 rounds).
+    if (num_moduli > 1 && g.ktiles > 96) {
       g.xcd_sync = reinterpret_cast<unsigned long long*>(ws + lay.off_flags) + 8;
       // rounds in which each of the grid / 8 workgroup slots of every XCD has a tile: all of them in the
       // super-block order (its work count is a multiple of 256); otherwise XCD 7 runs out first
