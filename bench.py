@@ -153,7 +153,7 @@ def main():
         # profiles/c4_oz2_dgemm_counters.md: FETCH_SIZE x 2.0 (copy-kernel scale) + WRITE_SIZE, in GiB, for the
         # Strassen form (UINT8 planes), the classical form with UINT8 planes and the classical form with INT32 planes
         if strassen:
-            fetch_gib, write_gib, min_gib = 43.151, 14.010, 21
+            fetch_gib, write_gib, min_gib = 43.244, 14.064, 21
         elif fmt == oz.OZ2_PRODUCT_RESIDUE_U8:
             fetch_gib, write_gib, min_gib = 48.658, 8.051, 12
         else:
