@@ -371,6 +371,11 @@ def main():
             cyc, ref = [int(v) for v in clocks.cpu()]
             out["context"]["mfma_only_%s_operands_TOPs" % label] = round(512 * 4 * iters * 8 * 65536.0 / (ms * 1e-3) / 1e12, 1)
             out["context"]["mfma_only_%s_operands_GHz" % label] = round(cyc / max(ref, 1) * 0.1, 3)
+        # the GEMM against what the matrix cores of this card sustain on random INT8 operands with no memory
+        # traffic at all (the card is power-capped well below the published peak)
+        cal = out["context"].get("mfma_only_random_operands_TOPs")
+        if cal:
+            out["roofline"]["frac_of_mfma_only_random_operands"] = round(gemm_tops / cal, 4)
         if not args.no_cpu_baseline:
             gotn = Cn[torch.from_numpy(rows).to(dev)][:, torch.from_numpy(cols).to(dev)].cpu().numpy()
             out["context"]["native_fp64_max_componentwise_err_vs_exact"] = float(np.max(np.abs(gotn - Cx) / S))
