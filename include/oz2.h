@@ -184,7 +184,7 @@ int oz2_set_product_format(int format);
  * 7/4 of the plane bytes in stages 1 and 3; C''_t, and therefore C, is the same as in the classical form, bit
  * for bit.  The form needs UINT8 residue planes (OZ2_PRODUCT_RESIDUE_U8) and applies to the general product only:
  * oz2_dsyrk, oz2_dtrmm and the staged entry points always take the classical form.
- *   OZ2_GEMM_AUTO (default): Strassen form when m and n are at least 8192 and k at least 12288 (below, the extra
+ *   OZ2_GEMM_AUTO (default): Strassen form when m and n are at least 8192 and k at least 10240 (below, the extra
  *     bytes cost more than the products save) and the registered workspace holds oz2_workspace_bytes_strassen;
  *     else classical.
  *   OZ2_GEMM_CLASSICAL: never.   OZ2_GEMM_STRASSEN: whenever the form applies, at any size (a workspace below

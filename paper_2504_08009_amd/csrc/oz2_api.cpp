@@ -74,9 +74,10 @@ int prepare(State& s, int64_t m, int64_t n, int64_t k, int N, const Oz2Plan** pl
 
 // The Strassen form pays when the matrix-core work it saves (an eighth of 2 m n k N) outweighs the extra plane
 // traffic of its conversion and CRT passes (three quarters more bytes per plane) and the lower rate of products
-// with a short inner dimension.  Measured on MI355X with 16 moduli: 5 % slower at 8192^3, even at 8192 x 8192 x
-// 12288 and at 12288^3, 2 % faster at 8192 x 8192 x 16384, 4 % at 16384 x 16384 x 12288, 8-10 % from 14336^3 on.
-bool strassen_pays(int64_t m, int64_t n, int64_t k) { return m >= 8192 && n >= 8192 && k >= 12288; }
+// with a short inner dimension.  Measured on MI355X with 16 moduli, Strassen against classical form on one box:
+// even at 8192^3 and at 4096 x 4096 x 32768, -1 % at 6144 x 6144 x 10240, +1 % at 6144 x 6144 x 16384, +2 % at
+// 8192 x 8192 x 10240 and 10240^3, +3 % at 8192 x 8192 x 12288, +4 % at 12288 x 12288 x 10240, 8-11 % from 14336^3 on.
+bool strassen_pays(int64_t m, int64_t n, int64_t k) { return m >= 8192 && n >= 8192 && k >= 10240; }
 
 // Does a general product of this shape use the Strassen form under the current settings?  It needs UINT8 residue
 // planes and, in the INT8-product shift mode, a padded inner dimension below 2^19.  On a yes, *lay is its layout.
