@@ -238,7 +238,7 @@ def test_c2_sampled_rows_and_error_decay():
     Cx, S = orc.exact(A, B, rows=rows, cols=cols)
     dA, dB = _dev(A), _dev(B)
     errs = {}
-    for N in (8, 12, 14, 16, 20):
+    for N in range(8, 21):
         ws = oz.Workspace(m, n, k, N)
         dC = torch.empty((n, m), dtype=torch.float64, device="cuda").t()
         oz.oz2_dgemm(m, n, k, dA.data_ptr(), m, dB.data_ptr(), k, dC.data_ptr(), m, N)
@@ -251,8 +251,10 @@ def test_c2_sampled_rows_and_error_decay():
         del ws
     native = float(np.max(np.abs((dA @ dB).cpu().numpy()[np.ix_(rows, cols)] - Cx) / S))
     print("componentwise error vs exact:", errs, "native FP64:", native, flush=True)
-    assert errs[8] > errs[12] > errs[14] > errs[16]
-    assert errs[16] < native
+    # every modulus more buys about four bits until the final rounding dominates
+    for N in range(8, 16):
+        assert errs[N + 1] < errs[N] / 4, N
+    assert errs[16] < native and max(errs[N] for N in range(17, 21)) <= errs[16]
 
 
 @pytest.mark.parametrize("name,kblock,algorithm", [
