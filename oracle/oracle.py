@@ -39,8 +39,6 @@ def lib():
             ctypes.c_void_p, ctypes.c_int64, ctypes.c_void_p, ctypes.c_int64, ctypes.c_void_p]
         _lib.oz2o_has_nonfinite.argtypes = [ctypes.c_int64, ctypes.c_int64, ctypes.c_void_p, ctypes.c_int64]
         _lib.oz2o_axpby.argtypes = [ctypes.c_int64, ctypes.c_double, ctypes.c_void_p, ctypes.c_double, ctypes.c_void_p]
-        _lib.oz2o_shifts.argtypes = [ctypes.c_int, ctypes.c_int64, ctypes.c_int64, ctypes.c_void_p,
-                                     ctypes.c_int64, ctypes.c_int, ctypes.c_void_p]
         _lib.oz2o_kappa_sum.argtypes = [ctypes.c_int, ctypes.c_void_p, ctypes.c_int64]
         _lib.oz2o_dgemm_sub.argtypes = ([ctypes.c_int64] * 3 + [ctypes.c_void_p, ctypes.c_int64, ctypes.c_void_p,
                                         ctypes.c_int64, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_void_p, ctypes.c_int64,
@@ -108,14 +106,6 @@ def crt_constants(N, mods=None):
     if rc:
         raise ValueError("oz2o_crt_constants -> %d" % rc)
     return _words_to_int(Mw), [_words_to_int(Ww[t]) for t in range(N)]
-
-
-def shifts(X, which, kap):
-    X = np.asfortranarray(X, dtype=np.float64)
-    rows, cols = X.shape
-    out = np.zeros(rows if which == 0 else cols, dtype=np.int32)
-    lib().oz2o_shifts(int(which), rows, cols, _ptr(X), max(1, rows), int(kap), _ptr(out))
-    return out
 
 
 class Result(dict):

@@ -484,25 +484,6 @@ int oz2o_crt_constants(int N, const int* moduli, uint32_t* M_words, uint32_t* W_
 // Symmetric modulo of Section 2.1 for a 64-bit argument.
 int64_t oz2o_sym_mod(int64_t a, int p) { return sym_mod((i128)a, p); }
 
-// Shifts only (Algorithm 1 line 1).  which = 0: rows of the m x k matrix X (ld), count m;
-// which = 1: columns of the k x n matrix X, count n.  All-zero vectors get shift 0.
-int oz2o_shifts(int which, int64_t rows, int64_t cols, const double* X, int64_t ld, int kappa, int32_t* out) {
-  if (which == 0) {
-    for (int64_t i = 0; i < rows; ++i) {
-      double mx = 0.0;
-      for (int64_t l = 0; l < cols; ++l) mx = std::fmax(mx, std::fabs(X[i + l * ld]));
-      out[i] = mx == 0.0 ? 0 : kappa - 1 - ilog2_abs(mx);
-    }
-  } else {
-    for (int64_t j = 0; j < cols; ++j) {
-      double mx = 0.0;
-      for (int64_t l = 0; l < rows; ++l) mx = std::fmax(mx, std::fabs(X[l + j * ld]));
-      out[j] = mx == 0.0 ? 0 : kappa - 1 - ilog2_abs(mx);
-    }
-  }
-  return 0;
-}
-
 // The whole of Algorithm 1 on a subset of outputs: rows I[0..nI) of A and columns J[0..nJ) of B
 // (I == NULL / J == NULL mean "all rows" / "all columns", then nI = m / nJ = n).
 // Every output pointer may be NULL.  Outputs (r = position in I, c = position in J):

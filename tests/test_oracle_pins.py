@@ -202,6 +202,67 @@ def test_every_step_against_exact_rationals(N, phi, use_paper_list):
             assert r.C[i, j] == want
 
 
+def test_subnormal_inputs_are_decomposed_exactly():
+    # Section 2.1 assumes no underflow; the oracle still has to read subnormal inputs for what they are: the
+    # shift comes from floor(log2) of the row maximum and the truncation acts on the exact value (a subnormal has
+    # no hidden bit and the fixed exponent -1074).  Rationals are the independent arithmetic.
+    m, n, k, N = 4, 3, 6, 14
+    A, B = _tiny(77, m, n, k, 0.5)
+    A[0] *= 2.0**-1040            # a row of subnormals only
+    A[1, ::2] *= 2.0**-1065       # subnormals mixed into a normal row (some vanish under truncation)
+    A[2, 1] = 5e-324              # the smallest subnormal
+    B[:, 1] *= 2.0**-1030         # a subnormal column
+    B[0, 2] = -2.0**-1074
+    assert np.any((A != 0) & (np.abs(A) < 2.0**-1022)) and np.any((B != 0) & (np.abs(B) < 2.0**-1022))
+    kap = orc.kappa(N, k)
+    r = orc.dgemm(A, B, N, want=("C", "shifts", "Ap", "Bp", "X"))
+    for i in range(m):
+        mx = max(abs(Fraction(float(x))) for x in A[i, :])
+        e = mx.numerator.bit_length() - mx.denominator.bit_length()
+        e = e if Fraction(2) ** e <= mx else e - 1            # floor(log2 mx) from the exact rational
+        assert Fraction(2) ** e <= mx < Fraction(2) ** (e + 1)
+        assert int(r.sa[i]) == kap - 1 - e
+        for l in range(k):
+            assert r.Ap[i][l] == math.trunc(Fraction(float(A[i, l])) * Fraction(2) ** int(r.sa[i]))
+    for j in range(n):
+        mx = max(abs(Fraction(float(x))) for x in B[:, j])
+        e = mx.numerator.bit_length() - mx.denominator.bit_length()
+        e = e if Fraction(2) ** e <= mx else e - 1
+        assert int(r.sb[j]) == kap - 1 - e
+        for l in range(k):
+            assert r.Bp[l][j] == math.trunc(Fraction(float(B[l, j])) * Fraction(2) ** int(r.sb[j]))
+    for i in range(m):
+        for j in range(n):
+            assert r.X[i][j] == sum(r.Ap[i][l] * r.Bp[l][j] for l in range(k))
+
+
+def test_results_in_the_subnormal_range_are_rounded_to_53_bits_and_then_scaled():
+    # Algorithm 1 line 11 read as FP64 arithmetic would carry it out: X is rounded to FP64 once (53 bits, nearest
+    # even), then multiplied by the power of two 2^-(sa+sb).  Above the subnormal range the scaling is exact and the
+    # result is the correctly rounded X 2^-(sa+sb); below it the scaling is a second rounding (the IEEE result of
+    # that multiplication).  Python's int -> float conversion and math.ldexp are the independent implementations
+    # of the two steps; X itself is pinned against the integer product above.
+    m, n, k, N = 6, 6, 5, 12
+    differs = 0
+    landed = 0
+    for seed in range(40):
+        A, B = _tiny(500 + seed, m, n, k, 0.5)
+        A *= 2.0**-510
+        B *= 2.0**-(510 + seed % 24)   # results from just below 2^-1022 (one bit lost) down to 30 bits lost
+        r = orc.dgemm(A, B, N, want=("C", "shifts", "X"))
+        for i in range(m):
+            for j in range(n):
+                s = int(r.sa[i]) + int(r.sb[j])
+                x = r.X[i][j]
+                want = math.ldexp(float(x), -s)
+                assert r.C[i, j] == want and math.copysign(1.0, r.C[i, j]) == math.copysign(1.0, want)
+                landed += 0.0 < abs(want) < 2.0**-1022
+                differs += want != float(Fraction(x, 2**s))   # one rounding of the exact quotient
+    assert landed > 1000 and differs < landed
+    # the two readings really differ on some elements, so this test tells them apart
+    assert differs > 0
+
+
 def test_small_integer_matrices_are_multiplied_exactly():
     # |a|,|b| < 2^10 and k*2^20 < 2^53: nothing is truncated once kappa >= 11, so C == A B exactly
     rng = np.random.default_rng(7)
@@ -548,6 +609,57 @@ def test_native_fallback_follows_ieee_rules_and_the_textbook_sum():
 
 
 # ------------------------------------------------------------------ Section 2.3: structured products (SYRK shape)
+def _with_signed_zeros(seed, m, n, k):
+    rng = np.random.default_rng(seed)
+    A = (rng.random((m, k)) - 0.5) * np.exp(rng.standard_normal((m, k)))
+    B = (rng.random((k, n)) - 0.5) * np.exp(rng.standard_normal((k, n)))
+    A[rng.random((m, k)) < 0.2] = -0.0
+    A[rng.random((m, k)) < 0.1] = 0.0
+    B[rng.random((k, n)) < 0.2] = -0.0
+    A[1, :] = -0.0                 # a row of negative zeros: every product of that row is a zero
+    A[2, :] = 0.0
+    A[2, ::2] = -0.0               # zeros of both signs
+    B[:, 1] = -0.0
+    B[:, 3] = np.where(B[:, 3] < 0, -0.0, B[:, 3])
+    A[4, :] = np.where(np.arange(k) % 2 == 0, -0.0, 1.0)   # the non-zero entries meet only zeros of column 5
+    B[:, 5] = np.where(np.arange(k) % 2 == 0, -3.0, -0.0)
+    return np.asfortranarray(A), np.asfortranarray(B)
+
+
+def test_signed_zeros_in_the_inputs_change_nothing():
+    # Section 3.1 (closing remark) names signed zeros among the values that need separate handling.  For a
+    # product whose sums start from +0 they need none: in round-to-nearest (+0) + (-0) = +0 and x + (-x) = +0, so
+    # a sum of products that are all zero is +0 whatever their signs, and a zero term never changes a non-zero
+    # sum.  Pinned here on the FP64 routine the fallback stands for (its zeros are all +0, and replacing every
+    # -0 of the inputs by +0 leaves every bit of its result as it is) and on the emulation (same statement):
+    # there is nothing a detection of -0 could route differently.
+    m, n, k, N = 9, 8, 12, 12
+    A, B = _with_signed_zeros(9, m, n, k)
+    assert np.signbit(A[A == 0]).any() and np.signbit(B[B == 0]).any()
+    Ap, Bp = A + 0.0, B + 0.0      # x + (+0): -0 becomes +0, everything else is unchanged
+    assert not np.signbit(Ap[Ap == 0]).any() and np.array_equal(A, Ap)
+    P, Pp = orc.native_gemm(A, B), orc.native_gemm(Ap, Bp)
+    assert np.array_equal(P.view(np.uint64), Pp.view(np.uint64))
+    assert (P == 0).sum() >= m + n - 1 and not np.signbit(P[P == 0]).any()
+    # exact rationals agree on where the zeros are
+    for i in range(m):
+        for j in range(n):
+            s = sum(Fraction(float(A[i, l])) * Fraction(float(B[l, j])) for l in range(k))
+            assert (s == 0) == (P[i, j] == 0) or abs(s) < Fraction(1, 2**60)
+    C, Cp = orc.dgemm(A, B, N).C, orc.dgemm(Ap, Bp, N).C
+    assert np.array_equal(C.view(np.uint64), Cp.view(np.uint64))
+    assert not np.signbit(C[C == 0]).any() and np.array_equal(C == 0, P == 0)
+    # the BLAS update: alpha * (+0) + (+0) is +0 for either sign of alpha; beta * C keeps the sign IEEE gives it
+    C0 = np.asfortranarray(np.where(np.arange(m * n).reshape(m, n) % 3 == 0, -0.0, 1.5))
+    for alpha, beta in [(-0.5, 0.0), (-0.5, 2.0), (1.0, -1.0)]:
+        U = orc.dgemm_ex("N", "N", alpha, A, B, beta, C0, N)
+        for i in range(m):
+            for j in range(n):
+                if C[i, j] == 0.0:          # the product is an exact zero: alpha * (+0) + t with IEEE signs
+                    want = alpha * 0.0 + (0.0 if beta == 0.0 else beta * C0[i, j])
+                    assert U[i, j] == want and np.signbit(U[i, j]) == np.signbit(want)
+
+
 @pytest.mark.parametrize("mode", [0, 1, 2])
 def test_symmetric_product_is_exactly_symmetric_and_touches_one_triangle(mode):
     # A' A'^T is a symmetric integer matrix and the shifts of its columns are those of its rows, so the
