@@ -248,6 +248,15 @@ int oz2_calibrate_mfma(int workgroups, int iters, int random_operands, int* sink
  * Returns 0 or -1. */
 int oz2_set_kblock(int64_t kblock);
 
+/* Tuning and test hook for line 6 (the INT8 products).  For long inner dimensions the workgroups that share an
+ * accelerator die start each of their tiles together, so that they read the same part of their shared operand
+ * panels at the same time; each such wait is bounded by `spins` polls of a counter (default 4096, about a
+ * millisecond).  A workgroup whose wait runs to the bound stops waiting for the rest of the launch: when the
+ * workgroups cannot all be resident at once (another kernel holds compute units) a launch loses one bound,
+ * not one per tile.  Results never depend on this setting.  spins == 0 switches the synchronisation off;
+ * 0 <= spins <= 2^20.  Returns 0 or -1. */
+int oz2_set_round_sync(int spins);
+
 /* Host-side evaluation of the device routine for lines 7-10 and the final rounding (same source,
  * compiled for the host), for unit tests of the exact-arithmetic design: given the num_moduli INT32
  * products of one output element it returns the double nearest to X = (sum_t c''_t W_t) mod M and

@@ -268,6 +268,14 @@ int oz2_set_product_format(int format) {
   return OZ2_OK;
 }
 
+int oz2_set_round_sync(int spins) {
+  if (spins < 0 || spins > (1 << 20)) return -1;
+  State& s = state();
+  std::lock_guard<std::mutex> lock(s.mu);
+  oz2_gemm_set_sync_spins(spins);
+  return OZ2_OK;
+}
+
 int oz2_set_kblock(int64_t kblock) {
   if (kblock < OZ2_TILE_K || kblock > 65536 || kblock % OZ2_TILE_K) return -1;
   State& s = state();
@@ -312,7 +320,10 @@ int oz2_stage2_gemm(int64_t m, int64_t n, int64_t k, int num_moduli, void* strea
   Oz2Layout lay;
   int rc = prepare(s, m, n, k, num_moduli, &plan, &lay);
   if (rc) return rc;
-  hipError_t e = oz2_launch_stage2(*plan, lay, s.ws, s.kblock, s.product_format, 0, OZ2_KRANGE_ALL, 0, static_cast<hipStream_t>(stream));
+  // the counters of the round synchronisation must be zero at launch; in oz2_dgemm stage 1 has cleared them
+  hipError_t e = oz2_launch_clear_sync(lay, s.ws, static_cast<hipStream_t>(stream));
+  if (e == hipSuccess)
+    e = oz2_launch_stage2(*plan, lay, s.ws, s.kblock, s.product_format, 0, OZ2_KRANGE_ALL, 0, static_cast<hipStream_t>(stream));
   return e == hipSuccess ? OZ2_OK : OZ2_ERR_HIP;
 }
 
@@ -377,29 +388,30 @@ int oz2_dgemm_ex(char transa, char transb, int64_t m, int64_t n, int64_t k, doub
   bool strassen;
   int rc = prepare_general(s, m, n, k, num_moduli, &plan, &lay, &strassen);
   if (rc) return rc;
+  char* const ws = s.ws;
   auto mark = [&](int i) { return !s.ev_on || hipEventRecord(s.ev[i], st) == hipSuccess; };
   if (!mark(0)) return OZ2_ERR_HIP;
-  if (oz2_launch_stage1(ta, tb, m, n, k, A, lda, B, ldb, 0, 0, *plan, s.shift_mode, s.bit_split, strassen ? 1 : 0, lay, s.ws,
+  if (oz2_launch_stage1(ta, tb, m, n, k, A, lda, B, ldb, 0, 0, *plan, s.shift_mode, s.bit_split, strassen ? 1 : 0, lay, ws,
                         st) != hipSuccess ||
       !mark(1))
     return OZ2_ERR_HIP;
   if (strassen) {
-    if (oz2_launch_strassen_gemm(*plan, lay, s.ws, s.kblock, s.nonfinite_check, st) != hipSuccess || !mark(2))
+    if (oz2_launch_strassen_gemm(*plan, lay, ws, s.kblock, s.nonfinite_check, st) != hipSuccess || !mark(2))
       return OZ2_ERR_HIP;
-    if (oz2_launch_strassen_crt(m, n, alpha, beta, C, ldc, *plan, lay, s.ws, s.nonfinite_check, st) != hipSuccess || !mark(3))
+    if (oz2_launch_strassen_crt(m, n, alpha, beta, C, ldc, *plan, lay, ws, s.nonfinite_check, st) != hipSuccess || !mark(3))
       return OZ2_ERR_HIP;
   } else {
-    if (oz2_launch_stage2(*plan, lay, s.ws, s.kblock, s.product_format, 0, OZ2_KRANGE_ALL, s.nonfinite_check, st) !=
+    if (oz2_launch_stage2(*plan, lay, ws, s.kblock, s.product_format, 0, OZ2_KRANGE_ALL, s.nonfinite_check, st) !=
             hipSuccess ||
         !mark(2))
       return OZ2_ERR_HIP;
-    if (oz2_launch_stage3(m, n, alpha, beta, C, ldc, *plan, lay, s.ws, s.product_format, s.nonfinite_check, 0, st) !=
+    if (oz2_launch_stage3(m, n, alpha, beta, C, ldc, *plan, lay, ws, s.product_format, s.nonfinite_check, 0, st) !=
             hipSuccess ||
         !mark(3))
       return OZ2_ERR_HIP;
   }
   if (s.nonfinite_check &&
-      oz2_launch_fallback(reinterpret_cast<const unsigned long long*>(s.ws + lay.off_flags), ta, tb, m, n, k, alpha, A, lda,
+      oz2_launch_fallback(reinterpret_cast<const unsigned long long*>(ws + lay.off_flags), ta, tb, m, n, k, alpha, A, lda,
                           B, ldb, beta, C, ldc, 0, 0, 0, st) != hipSuccess)
     return OZ2_ERR_HIP;
   return OZ2_OK;

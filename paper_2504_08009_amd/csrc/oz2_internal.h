@@ -83,6 +83,10 @@ hipError_t oz2_launch_strassen_crt(int64_t m, int64_t n, double alpha, double be
 // One-time device set-up of the GEMM kernels (function attributes, compute-unit count); also done lazily by the
 // first launch.
 hipError_t oz2_gemm_setup();
+// Bound of one wait of the GEMM's round synchronisation in polls (0 switches the synchronisation off), and the
+// clearing of its counters for a GEMM that no stage 1 precedes.
+void oz2_gemm_set_sync_spins(int spins);
+hipError_t oz2_launch_clear_sync(const Oz2Layout& lay, char* ws, hipStream_t st);
 
 // Inner-dimension range of a tile when one operand is triangular (TRMM shape), in units of diagonal blocks:
 //   UPTO_ROW / FROM_ROW: the first operand is lower / upper triangular (only l <= i / l >= i contribute);

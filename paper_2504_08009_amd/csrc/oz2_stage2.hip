@@ -75,8 +75,10 @@ struct GemmArgs {
   int triangle;            // 0: all tiles; 1: only tiles with tm >= tn (lower); 2: only tm <= tn (upper)
   int krange;              // triangular operand: which k-tiles of a tile can be nonzero (see OZ2_KRANGE_*)
   const unsigned long long* skip_flag;  // if not null and nonzero on the device: the products are not needed
-  unsigned long long* xcd_sync;         // eight counters, one per XCD (zero at launch), or null: no round sync
+  unsigned long long* xcd_sync;         // one counter per XCD (zero at launch), or null: no round sync
   int full_rounds;                      // rounds in which every workgroup slot has a tile
+  int xcds;                             // accelerator dies of the chip: workgroup i of a launch runs on die i % xcds
+  int sync_spins;                       // bound of one wait of the round synchronisation, in polls of the counter
   float p[OZ2_MAX_PLANES];             // modulus of every plane
 };
 
@@ -91,7 +93,7 @@ __device__ __forceinline__ void load_to_lds_16(const int8_t* base, unsigned voff
       "global_load_lds_dwordx4 %0, %1"
       :
       : "v"(voff), "s"(base), "s"(lds_addr)
-      : "memory");
+      : "memory", "m0");
 }
 
 // s_waitcnt vmcnt(N) only (gfx9 encoding: vmcnt in bits 3:0 and 15:14, expcnt 6:4, lgkmcnt 11:8)
@@ -282,6 +284,8 @@ __global__ void __launch_bounds__(kThreads) gemm_i8_kernel(const GemmArgs g) {
   prologue_loads(cur);
   bool first = true;
   int round = 0;
+  bool sync_wait = true;  // cleared for the rest of the launch by the first wait that runs to its bound
+  const int xcd = blockIdx.x % g.xcds;
   for (;;) {
   const int ktiles = cur.ktiles;
   const int t = cur.t, tm = cur.tm, tn = cur.tn;
@@ -301,15 +305,24 @@ __global__ void __launch_bounds__(kThreads) gemm_i8_kernel(const GemmArgs g) {
     wait_vmcnt<0>();
   first = false;
   if (g.xcd_sync != nullptr && round < g.full_rounds && threadIdx.x == 0) {
-    // The workgroups of an XCD start their tiles of a round together.  The wait is bounded (about a millisecond):
-    // if the workgroups are not all resident at once, or the counters were not cleared, the round simply starts
-    // unsynchronised.
-    unsigned long long* c = g.xcd_sync + (blockIdx.x & 7);
+    // The workgroups of an XCD start their tiles of a round together.  The wait is bounded (about a millisecond).
+    // If it runs to its bound, the workgroups of this XCD are not all resident at once (another kernel holds
+    // compute units) or the counters were not cleared: this workgroup then stops waiting for the rest of the
+    // launch, so that the launch loses one bound, not one per round.  It keeps counting itself in, so the
+    // others are not held up by it.
+    unsigned long long* c = g.xcd_sync + xcd;
     if (!EARLY_ARRIVAL || round == 0) atomicAdd(c, 1ull);
-    const unsigned long long target = (unsigned long long)(gridDim.x >> 3) * (unsigned long long)(round + 1);
-    for (int spins = 0; spins < 4096; ++spins) {
-      if (__hip_atomic_load(c, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) >= target) break;
-      __builtin_amdgcn_s_sleep(8);
+    if (sync_wait) {
+      const unsigned long long target = (unsigned long long)(gridDim.x / g.xcds) * (unsigned long long)(round + 1);
+      bool arrived = false;
+      for (int spins = 0; spins < g.sync_spins; ++spins) {
+        if (__hip_atomic_load(c, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) >= target) {
+          arrived = true;
+          break;
+        }
+        __builtin_amdgcn_s_sleep(8);
+      }
+      sync_wait = arrived;
     }
   }
   ++round;
@@ -383,7 +396,7 @@ __global__ void __launch_bounds__(kThreads) gemm_i8_kernel(const GemmArgs g) {
       // count in for the next round now: the others then wait for this workgroup's main loop only, not for its
       // epilogue, and the counter's round trip overlaps the epilogue
       if (g.xcd_sync != nullptr && round < g.full_rounds && threadIdx.x == 0)
-        atomicAdd(g.xcd_sync + (blockIdx.x & 7), 1ull);
+        atomicAdd(g.xcd_sync + xcd, 1ull);
     }
   }
 
@@ -453,6 +466,10 @@ __global__ void __launch_bounds__(kThreads) gemm_i8_kernel(const GemmArgs g) {
 #undef OZ2_MFMA
 }
 
+__global__ void clear_sync_kernel(unsigned long long* counters, int count) {
+  if ((int)threadIdx.x < count) counters[threadIdx.x] = 0ull;
+}
+
 }  // namespace
 
 namespace {
@@ -460,6 +477,10 @@ namespace {
 // Once per process: the kernels' dynamic LDS limit and the number of compute units (a multiple of 8, one
 // workgroup slot each).  Callers hold the library's lock.
 int g_cus = 0;
+// The tile orders above are written for the eight accelerator dies (XCDs) of the MI355X, on which the hardware
+// places workgroup i of a launch on die i % 8.
+constexpr int kXcds = 8;
+int g_sync_spins = 4096;  // polls per wait of the round synchronisation (each followed by a short sleep); 0: off
 hipError_t gemm_setup() {
   if (g_cus) return hipSuccess;
   const void* kernels[6] = {reinterpret_cast<const void*>(gemm_i8_kernel<false, false, false>),
@@ -519,6 +540,8 @@ hipError_t launch_gemm(const Oz2Layout& lay, char* ws, int num_moduli, const int
   unsigned grid = (unsigned)(g.chunk * 8);
   g.xcd_sync = nullptr;
   g.full_rounds = 0;
+  g.xcds = kXcds;
+  g.sync_spins = g_sync_spins;
   if (triangle == 0 && krange == OZ2_KRANGE_ALL) {
     if (grid > (unsigned)g_cus) grid = (unsigned)g_cus;
     // General products: the workgroups of an XCD start the tiles of a round together, which keeps them
@@ -527,7 +550,7 @@ hipError_t launch_gemm(const Oz2Layout& lay, char* ws, int num_moduli, const int
     // Only for inner dimensions above 6144: shorter panels stay in the L2 anyway and the wait for the slowest
     // workgroup of every round costs more than it saves (measured without it: -10 % at k = 1024, -6 % at 2048,
     // -4 % at 4096, -3 % at 6144, -1.5 % at 8192 with 64 rounds but +1 % at 8192 with 448 rounds).
-    if (num_moduli > 1 && g.ktiles > 96) {
+    if (num_moduli > 1 && g.ktiles > 96 && g_sync_spins > 0) {
       g.xcd_sync = reinterpret_cast<unsigned long long*>(ws + lay.off_flags) + 8;
       // rounds in which each of the grid / 8 workgroup slots of every XCD has a tile: all of them in the
       // super-block order (its work count is a multiple of 256); otherwise XCD 7 runs out first
@@ -564,6 +587,16 @@ hipError_t launch_gemm(const Oz2Layout& lay, char* ws, int num_moduli, const int
 }  // namespace
 
 hipError_t oz2_gemm_setup() { return gemm_setup(); }
+
+void oz2_gemm_set_sync_spins(int spins) { g_sync_spins = spins; }
+
+// The round synchronisation counts on counters that are zero at launch.  Stage 1 clears them with the row
+// maxima; a GEMM launched without a stage 1 before it (the staged entry point called again) clears them here.
+hipError_t oz2_launch_clear_sync(const Oz2Layout& lay, char* ws, hipStream_t st) {
+  hipLaunchKernelGGL(clear_sync_kernel, dim3(1), dim3(64), 0, st,
+                     reinterpret_cast<unsigned long long*>(ws + lay.off_flags) + 8, kXcds);
+  return hipGetLastError();
+}
 
 hipError_t oz2_launch_stage2(const Oz2Plan& plan, const Oz2Layout& lay, char* ws, int64_t kblock, int residue_u8,
                              int triangle, int krange, int check_flag, hipStream_t st) {
