@@ -10,7 +10,7 @@ SYMBOLS = [
     "oz2_init", "oz2_min_moduli", "oz2_moduli_for_bits", "oz2_max_moduli", "oz2_get_moduli", "oz2_workspace_bytes", "oz2_workspace_bytes_for", "oz2_set_workspace",
     "oz2_workspace_layout", "oz2_dgemm", "oz2_dgemm_ex", "oz2_dsyrk", "oz2_dtrmm", "oz2_stage1_convert", "oz2_stage2_gemm", "oz2_stage3_crt",
     "oz2_set_gemm_algorithm", "oz2_gemm_algorithm_for", "oz2_workspace_bytes_strassen", "oz2_workspace_bytes_preferred",
-    "oz2_set_kblock", "oz2_set_shift_mode", "oz2_set_product_format", "oz2_set_bit_split", "oz2_set_nonfinite_check", "oz2_set_stage_events", "oz2_calibrate_mfma", "oz2_host_crt_element", "oz2_host_residues", "oz2_status_string",
+    "oz2_set_kblock", "oz2_set_round_sync", "oz2_set_shift_mode", "oz2_set_product_format", "oz2_set_bit_split", "oz2_set_nonfinite_check", "oz2_set_stage_events", "oz2_calibrate_mfma", "oz2_host_crt_element", "oz2_host_residues", "oz2_status_string",
 ]
 
 
@@ -50,6 +50,7 @@ def lib():
         L.oz2_stage2_gemm.argtypes = [i64, i64, i64, ci, vp]
         L.oz2_stage3_crt.argtypes = [i64, i64, i64, vp, i64, ci, vp]
         L.oz2_set_kblock.argtypes = [i64]
+        L.oz2_set_round_sync.argtypes = [ci]
         L.oz2_set_shift_mode.argtypes = [ci]
         L.oz2_set_product_format.argtypes = [ci]
         L.oz2_set_nonfinite_check.argtypes = [ci]
@@ -141,8 +142,18 @@ def workspace_layout(m, n, k, num_moduli):
     return out
 
 
+_registered_ptr = None   # what this module last registered with the library (None: nothing)
+
+
 def set_workspace(dev_ptr, nbytes):
+    global _registered_ptr
     _check(lib().oz2_set_workspace(dev_ptr, nbytes), "oz2_set_workspace")
+    _registered_ptr = dev_ptr if dev_ptr else None
+
+
+def oz2_set_round_sync(spins):
+    """Bound (in polls) of a wait of the GEMM's per-die round synchronisation; 0 switches it off (default 4096)."""
+    _check(lib().oz2_set_round_sync(int(spins)), "oz2_set_round_sync")
 
 
 def oz2_set_kblock(kblock):
@@ -254,6 +265,20 @@ class Workspace:
         self.offset = (-base) % 256
         self.ptr = base + self.offset
         set_workspace(self.ptr, self.nbytes)
+
+    def close(self):
+        """Unregister the buffer if the library still points at it.  The library keeps a bare pointer: once this
+        object is gone the memory returns to the allocator, and a later call must find no workspace (status
+        OZ2_ERR_WORKSPACE) instead of writing into memory that belongs to another tensor."""
+        if getattr(self, "ptr", None) is not None and _registered_ptr == self.ptr and _lib is not None:
+            set_workspace(None, 0)
+        self.ptr = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:   # interpreter shutdown: nothing left to protect
+            pass
 
     def view(self, off, count, dtype):
         """1-D torch view of `count` elements of `dtype` starting `off` bytes into the workspace."""

@@ -257,9 +257,10 @@ def test_c2_sampled_rows_and_error_decay():
     assert errs[16] < native and max(errs[N] for N in range(17, 21)) <= errs[16]
 
 
-@pytest.mark.parametrize("name,kblock,algorithm", [
-    ("c3", None, -1), ("c5a", None, -1), ("c4", None, -1), ("c4", None, 0), ("c5b", 32768, 0), ("c5b", 16384, -1)])
-def test_full_size_configs_on_sampled_outputs(name, kblock, algorithm):
+@pytest.mark.parametrize("name,kblock,algorithm,N", [
+    ("c3", None, -1, 14), ("c3", None, -1, 18), ("c5a", None, -1, 18), ("c4", None, -1, 16), ("c4", None, 0, 16),
+    ("c5b", 32768, 0, 18), ("c5b", 16384, -1, 18)])
+def test_full_size_configs_on_sampled_outputs(name, kblock, algorithm, N):
     """The benchmark configurations at full size through oz2_dgemm (the call bench.py times); the oracle
     recomputes a sample of output rows and columns (first, last and random ones) with the full inner
     dimension.  algorithm -1 is the library's own choice of the form of the INT8 products (the Strassen form at
@@ -268,7 +269,7 @@ def test_full_size_configs_on_sampled_outputs(name, kblock, algorithm):
     that the reduction between k-blocks is exercised; the result must still be bit-identical."""
     cfg = inputs.CONFIGS[name]
     m, n, k, phi = cfg["m"], cfg["n"], cfg["k"], cfg["phi"]
-    N = 16 if name == "c4" else cfg["N"][-1]
+    assert N == 16 if name == "c4" else N in cfg["N"]
     print("generating %s: m=%d n=%d k=%d N=%d" % (name, m, n, k, N), flush=True)
     A = inputs.block(cfg["seed"], 0, m, k, phi)
     B = inputs.block(cfg["seed"], 1, k, n, phi)
@@ -301,6 +302,44 @@ def test_full_size_configs_on_sampled_outputs(name, kblock, algorithm):
     assert np.all(np.abs(got - ref) <= 1e-15 * S)
     assert np.array_equal(got, ref), "%s: not bit-identical with the oracle" % name
     del ws
+
+
+_c3_oracle = {}
+
+
+@pytest.mark.parametrize("algorithm", [0, 1])
+def test_c3_every_element_both_forms(algorithm):
+    """Config c3 (4096^3, phi = 1, 16 moduli) through oz2_dgemm with EVERY element of C compared with the oracle,
+    in the classical form (16 x 16 tile grid: the super-block order, 16 tiles per workgroup slot of the persistent
+    loop) and with the Strassen form forced (seven 2048^3 products per modulus on an 8 x 8 tile grid: the list order
+    of the 8 x 4 sub-blocks, 28 tiles per slot).  The oracle forms line 6 as printed either way, so one oracle run
+    (about half a minute on the host cores) serves both."""
+    cfg = inputs.CONFIGS["c3"]
+    m, n, k, phi, N = cfg["m"], cfg["n"], cfg["k"], cfg["phi"], 16
+    A = inputs.block(cfg["seed"], 0, m, k, phi)
+    B = inputs.block(cfg["seed"], 1, k, n, phi)
+    dA = torch.from_numpy(A.T).cuda().t()
+    dB = torch.from_numpy(B.T).cuda().t()
+    dC = torch.full((n, m), float("nan"), dtype=torch.float64, device="cuda").t()
+    oz.oz2_set_gemm_algorithm(algorithm)
+    try:
+        ws = oz.Workspace(m, n, k, N)
+        assert (oz.oz2_gemm_algorithm_for(m, n, k, N) == oz.OZ2_GEMM_STRASSEN) == (algorithm == 1)
+        print("c3 every element, %s form" % ("Strassen" if algorithm else "classical"), flush=True)
+        oz.oz2_dgemm(m, n, k, dA.data_ptr(), m, dB.data_ptr(), k, dC.data_ptr(), m, N)
+        torch.cuda.synchronize()
+    finally:
+        oz.oz2_set_gemm_algorithm(oz.OZ2_GEMM_AUTO)
+    got = dC.cpu().numpy()
+    del ws, dA, dB, dC
+    if "C" not in _c3_oracle:
+        print("oracle on all %d x %d outputs" % (m, n), flush=True)
+        _c3_oracle["C"] = orc.dgemm(A, B, N).C
+    ref = _c3_oracle["C"]
+    bad = np.argwhere(got != ref)
+    assert len(bad) == 0, "%d elements differ from the oracle, first at %s" % (len(bad), bad[:5].tolist())
+    # same zeros with the same signs, and nothing that is not a number
+    assert np.array_equal(np.signbit(got), np.signbit(ref)) and not np.isnan(got).any()
 
 
 @pytest.mark.parametrize("m,n,k,N,phi", [
@@ -533,6 +572,48 @@ def test_nonfinite_inputs_fall_back_to_fp64(ta, tb, where, mode):
     assert _flag(ws, m, n, k, N) == 0
     assert np.array_equal(dC.cpu().numpy(), orc.dgemm_ex(ta, tb, alpha, As, Bs, beta, C0, N))
     del ws
+
+
+@pytest.mark.parametrize("algorithm", [0, 1])
+@pytest.mark.parametrize("mode", [0, 1, 2])
+def test_signed_zeros_every_bit_of_c(algorithm, mode):
+    """Negative zeros in A and B (scattered, whole rows and columns, products that meet only zeros): they count as
+    zeros, an emulated zero is +0 as in an FP64 sum that starts from +0, and the update alpha P + beta C gives its
+    zeros the IEEE signs.  Compared with the oracle on the bit patterns, so the sign of every zero is checked."""
+    rng = np.random.default_rng(31)
+    m, n, k, N = 300, 260, 150, 13
+    A = (rng.random((m, k)) - 0.5) * np.exp(rng.standard_normal((m, k)))
+    B = (rng.random((k, n)) - 0.5) * np.exp(rng.standard_normal((k, n)))
+    A[rng.random((m, k)) < 0.2] = -0.0
+    B[rng.random((k, n)) < 0.2] = -0.0
+    A[1, :] = -0.0
+    A[2, ::2] = -0.0
+    A[2, 1::2] = 0.0
+    B[:, 1] = -0.0
+    A[4, :] = np.where(np.arange(k) % 2 == 0, -0.0, 1.0)
+    B[:, 5] = np.where(np.arange(k) % 2 == 0, -3.0, -0.0)
+    A, B = np.asfortranarray(A), np.asfortranarray(B)
+    C0 = np.asfortranarray(np.where(rng.random((m, n)) < 0.3, -0.0, rng.standard_normal((m, n))))
+    dA, dB = _dev(A), _dev(B)
+    oz.oz2_set_gemm_algorithm(algorithm)
+    oz.oz2_set_shift_mode(mode)
+    try:
+        ws = oz.Workspace(m, n, k, N)
+        for alpha, beta in [(1.0, 0.0), (-0.5, 0.0), (-0.5, 2.0), (1.0, -1.0)]:
+            print("signed zeros: form %d, shift mode %d, alpha %g beta %g" % (algorithm, mode, alpha, beta), flush=True)
+            dC = torch.from_numpy(np.ascontiguousarray(C0.T)).cuda().t()
+            oz.oz2_dgemm_ex("N", "N", m, n, k, alpha, dA.data_ptr(), m, dB.data_ptr(), k, beta, dC.data_ptr(), m, N)
+            torch.cuda.synchronize()
+            assert _flag(ws, m, n, k, N) == 0     # nothing to fall back for
+            got = dC.cpu().numpy()
+            ref = orc.dgemm_ex("N", "N", alpha, A, B, beta, C0, N, mode=mode)
+            assert np.array_equal(got.view(np.uint64), ref.view(np.uint64))
+            if beta == 0.0:
+                assert (got == 0).sum() >= m + n - 1 and not np.signbit(got[got == 0]).any()
+        del ws
+    finally:
+        oz.oz2_set_gemm_algorithm(oz.OZ2_GEMM_AUTO)
+        oz.oz2_set_shift_mode(0)
 
 
 def test_nonfinite_check_can_be_switched_off():

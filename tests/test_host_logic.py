@@ -84,6 +84,28 @@ def test_argument_validation_without_gpu():
     assert oz.lib().oz2_status_string(-3).decode() == "invalid argument"
 
 
+def test_dropped_workspace_is_unregistered():
+    """The library keeps a bare pointer to the workspace; when the Python owner of the buffer goes away the
+    registration must go with it, so that a later call reports a missing workspace instead of writing into memory
+    the allocator has handed to someone else.  Host memory stands in for device memory: nothing is launched."""
+    L = oz.lib()
+    ws = oz.Workspace(64, 64, 64, 8, device="cpu")
+    assert oz.binding._registered_ptr == ws.ptr
+    other = oz.Workspace(32, 32, 32, 8, device="cpu")      # a second registration replaces the first
+    del ws                                                 # ... so dropping the first one changes nothing
+    assert oz.binding._registered_ptr == other.ptr
+    del other
+    assert oz.binding._registered_ptr is None
+    assert L.oz2_stage2_gemm(32, 32, 32, 8, None) == 1     # OZ2_ERR_WORKSPACE, before any launch
+    assert L.oz2_dgemm(32, 32, 32, ctypes.c_void_p(256), 32, ctypes.c_void_p(256), 32, ctypes.c_void_p(256), 32, 8, None) == 1
+
+
+def test_round_sync_setting_is_validated():
+    L = oz.lib()
+    assert L.oz2_set_round_sync(-1) == -1 and L.oz2_set_round_sync((1 << 20) + 1) == -1
+    assert L.oz2_set_round_sync(0) == 0 and L.oz2_set_round_sync(4096) == 0
+
+
 def test_workspace_layout_is_consistent():
     for fmt, bpe in ((oz.OZ2_PRODUCT_RESIDUE_U8, 1), (oz.OZ2_PRODUCT_INT32, 4)):
         oz.oz2_set_product_format(fmt)
