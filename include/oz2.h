@@ -34,6 +34,10 @@ extern "C" {
 #define OZ2_ERR_WORKSPACE 1
 #define OZ2_ERR_BUDGET 2
 #define OZ2_ERR_HIP 3
+#define OZ2_ERR_STATIC_LIMIT 4 /* oz2_dgemm_static only: the problem needs more than OZ2_STATIC_SCRATCH_BYTES */
+
+/* Size of the library's own static workspace (one per GPU, held until the process ends); see oz2_dgemm_static. */
+#define OZ2_STATIC_SCRATCH_BYTES (64u << 20)
 
 #define OZ2_PRODUCT_INT32 0      /* stage 2 writes the INT32 products C'_t (Algorithm 1 line 6) */
 #define OZ2_PRODUCT_RESIDUE_U8 1 /* stage 2 writes C''_t = C'_t mod p_t as UINT8 (lines 6 and 7 together); default */
@@ -46,9 +50,9 @@ extern "C" {
 #define OZ2_SHIFT_CAUCHY_SCHWARZ 1 /* shifts from row/column 2-norms: Section 4.1, the "fast" variant */
 #define OZ2_SHIFT_INT8_PRODUCT 2   /* shifts from an INT8 product of upper bounds: Section 4.1, the "accu" variant */
 
-/* One-time set-up on the current device (kernel attributes, compute-unit count).  The first call that launches
- * the GEMM does the same by itself; call this first when that call would otherwise be made under stream
- * capture, where attributes cannot be set.  Returns 0 or OZ2_ERR_HIP. */
+/* One-time set-up on the current device (kernel attributes, compute-unit count, address of the static workspace
+ * of oz2_dgemm_static).  The first call that launches the GEMM does the same by itself; call this first when that
+ * call would otherwise be made under stream capture, where attributes cannot be set.  Returns 0 or OZ2_ERR_HIP. */
 int oz2_init(void);
 
 /* Smallest and largest supported number of moduli (Section 3.1: the table starts at s = 2). */
@@ -113,6 +117,20 @@ int oz2_workspace_layout(int64_t m, int64_t n, int64_t k, int num_moduli, size_t
  * (n,m,k,B,ldb,A,lda,C,ldc). */
 int oz2_dgemm(int64_t m, int64_t n, int64_t k, const double* A, int64_t lda, const double* B, int64_t ldb,
               double* C, int64_t ldc, int num_moduli, void* stream);
+
+/* oz2_dgemm for callers that cannot allocate device memory or register a workspace of their own: code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same kernels and
+ * the same result, bit for bit, as oz2_dgemm under the settings in force; the intermediates (shift vectors,
+ * residue planes, product planes) live in a static device array of OZ2_STATIC_SCRATCH_BYTES (64 MiB) that is
+ * part of the library's code object, one copy per GPU.  The call allocates and frees nothing (its first use on
+ * a device looks up the array's address; oz2_init does that ahead of time) and does not touch the registered
+ * workspace.  A problem whose workspace -- oz2_workspace_bytes_for(m, n, k, num_moduli, format in force) --
+ * exceeds the array returns OZ2_ERR_STATIC_LIMIT and enqueues nothing: with the default product format that
+ * admits m = n = k = 1024 with up to 21 moduli (63 MiB).  The array keeps the last call's
+ * contents; every call rewrites all it reads.  All calls on a GPU share the one array: calls that overlap in
+ * time on one GPU (two streams, two threads) race -- serialise them.  Always the classical form of line 6. */
+int oz2_dgemm_static(int64_t m, int64_t n, int64_t k, const double* A, int64_t lda, const double* B, int64_t ldb,
+                     double* C, int64_t ldc, int num_moduli, void* stream);
 
 /* BLAS-style general form:  C := alpha * op(A) * op(B) + beta * C,  op(X) = X for 'N', X^T for 'T' or 'C'.
  *   op(A) is m x k: A is stored m x k (lda >= max(1,m)) for 'N' and k x m (lda >= max(1,k)) otherwise;

@@ -8,7 +8,7 @@ _lib = None
 
 SYMBOLS = [
     "oz2_init", "oz2_min_moduli", "oz2_moduli_for_bits", "oz2_max_moduli", "oz2_get_moduli", "oz2_workspace_bytes", "oz2_workspace_bytes_for", "oz2_set_workspace",
-    "oz2_workspace_layout", "oz2_dgemm", "oz2_dgemm_ex", "oz2_dsyrk", "oz2_dtrmm", "oz2_stage1_convert", "oz2_stage2_gemm", "oz2_stage3_crt",
+    "oz2_workspace_layout", "oz2_dgemm", "oz2_dgemm_static", "oz2_dgemm_ex", "oz2_dsyrk", "oz2_dtrmm", "oz2_stage1_convert", "oz2_stage2_gemm", "oz2_stage3_crt",
     "oz2_set_gemm_algorithm", "oz2_gemm_algorithm_for", "oz2_workspace_bytes_strassen", "oz2_workspace_bytes_preferred",
     "oz2_set_kblock", "oz2_set_round_sync", "oz2_set_shift_mode", "oz2_set_product_format", "oz2_set_bit_split", "oz2_set_nonfinite_check", "oz2_set_stage_events", "oz2_calibrate_mfma", "oz2_host_crt_element", "oz2_host_residues", "oz2_status_string",
 ]
@@ -41,6 +41,7 @@ def lib():
         L.oz2_set_workspace.argtypes = [vp, ctypes.c_size_t]
         L.oz2_workspace_layout.argtypes = [i64, i64, i64, ci, vp, vp]
         L.oz2_dgemm.argtypes = [i64, i64, i64, vp, i64, vp, i64, vp, i64, ci, vp]
+        L.oz2_dgemm_static.argtypes = [i64, i64, i64, vp, i64, vp, i64, vp, i64, ci, vp]
         L.oz2_dgemm_ex.argtypes = [ctypes.c_char, ctypes.c_char, i64, i64, i64, ctypes.c_double, vp, i64, vp, i64,
                                    ctypes.c_double, vp, i64, ci, vp]
         L.oz2_dsyrk.argtypes = [ctypes.c_char, ctypes.c_char, i64, i64, ctypes.c_double, vp, i64, ctypes.c_double, vp, i64,
@@ -202,6 +203,15 @@ def _stream_ptr(stream):
 
 def oz2_dgemm(m, n, k, A_ptr, lda, B_ptr, ldb, C_ptr, ldc, num_moduli, stream=None):
     _check(lib().oz2_dgemm(m, n, k, A_ptr, lda, B_ptr, ldb, C_ptr, ldc, num_moduli, _stream_ptr(stream)), "oz2_dgemm")
+
+
+OZ2_STATIC_SCRATCH_BYTES = 64 << 20
+
+
+def oz2_dgemm_static(m, n, k, A_ptr, lda, B_ptr, ldb, C_ptr, ldc, num_moduli, stream=None):
+    """oz2_dgemm on the library's static workspace: allocates nothing, needs no registered workspace."""
+    _check(lib().oz2_dgemm_static(m, n, k, A_ptr, lda, B_ptr, ldb, C_ptr, ldc, num_moduli, _stream_ptr(stream)),
+           "oz2_dgemm_static")
 
 
 def oz2_dgemm_ex(transa, transb, m, n, k, alpha, A_ptr, lda, B_ptr, ldb, beta, C_ptr, ldc, num_moduli, stream=None):

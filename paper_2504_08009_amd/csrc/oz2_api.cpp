@@ -51,7 +51,13 @@ bool dims_ok(int64_t m, int64_t n, int64_t k) {
   return true;
 }
 
-int prepare(State& s, int64_t m, int64_t n, int64_t k, int N, const Oz2Plan** plan, Oz2Layout* lay) {
+// A workspace a call runs in: the registered one, or the library's own static buffer.
+struct WsRef {
+  char* p;
+  size_t bytes;
+};
+
+int prepare(State& s, const WsRef& w, int64_t m, int64_t n, int64_t k, int N, const Oz2Plan** plan, Oz2Layout* lay) {
   int rc = get_plan(s, N, k, plan);
   if (rc == 2 && (s.shift_mode == OZ2_SHIFT_MAX || (*plan)->beta < 1)) return OZ2_ERR_BUDGET;
   if (rc == 2) rc = 0;
@@ -68,8 +74,12 @@ int prepare(State& s, int64_t m, int64_t n, int64_t k, int N, const Oz2Plan** pl
   // the INT8 product of the 6-bit bounds must stay below 2^31
   if (s.shift_mode == OZ2_SHIFT_INT8_PRODUCT && (k + 63) / 64 * 64 >= ((int64_t)1 << 19)) return OZ2_ERR_BUDGET;
   oz2_make_layout(m, n, k, N, s.product_format == OZ2_PRODUCT_INT32 ? 4 : 1, lay);
-  if (!s.ws || s.ws_bytes < lay->total) return OZ2_ERR_WORKSPACE;
+  if (!w.p || w.bytes < lay->total) return OZ2_ERR_WORKSPACE;
   return OZ2_OK;
+}
+
+int prepare(State& s, int64_t m, int64_t n, int64_t k, int N, const Oz2Plan** plan, Oz2Layout* lay) {
+  return prepare(s, WsRef{s.ws, s.ws_bytes}, m, n, k, N, plan, lay);
 }
 
 // The Strassen form pays when the matrix-core work it saves (an eighth of 2 m n k N) outweighs the extra plane
@@ -91,14 +101,15 @@ bool strassen_applies(const State& s, int64_t m, int64_t n, int64_t k, int N, Oz
 
 // prepare() for the general product: *strassen tells which form the call takes.  The automatic choice falls back to
 // the plain form when the workspace only suffices for that; a forced Strassen form reports the workspace as too small.
-int prepare_general(State& s, int64_t m, int64_t n, int64_t k, int N, const Oz2Plan** plan, Oz2Layout* lay, bool* strassen) {
+int prepare_general(State& s, const WsRef& w, int64_t m, int64_t n, int64_t k, int N, const Oz2Plan** plan, Oz2Layout* lay,
+                    bool* strassen) {
   *strassen = false;
   Oz2Layout plain;
-  const int rc = prepare(s, m, n, k, N, plan, &plain);
+  const int rc = prepare(s, w, m, n, k, N, plan, &plain);
   if (rc != OZ2_OK && rc != OZ2_ERR_WORKSPACE) return rc;
   Oz2Layout sl;
   if (strassen_applies(s, m, n, k, N, &sl)) {
-    if (s.ws && s.ws_bytes >= sl.total) {
+    if (w.p && w.bytes >= sl.total) {
       *lay = sl;
       *strassen = true;
       return OZ2_OK;
@@ -116,7 +127,10 @@ extern "C" {
 int oz2_init(void) {
   State& s = state();
   std::lock_guard<std::mutex> lock(s.mu);
-  return oz2_gemm_setup() == hipSuccess ? OZ2_OK : OZ2_ERR_HIP;
+  if (oz2_gemm_setup() != hipSuccess) return OZ2_ERR_HIP;
+  char* p;
+  size_t bytes;
+  return oz2_static_scratch(&p, &bytes) == hipSuccess ? OZ2_OK : OZ2_ERR_HIP;
 }
 
 int oz2_min_moduli(void) { return OZ2_MIN_N; }
@@ -358,8 +372,11 @@ int trans_code(char c) {
 }
 }  // namespace
 
-int oz2_dgemm_ex(char transa, char transb, int64_t m, int64_t n, int64_t k, double alpha, const double* A, int64_t lda,
-                 const double* B, int64_t ldb, double beta, double* C, int64_t ldc, int num_moduli, void* stream) {
+namespace {
+// The general product on the registered workspace (static_ws == false) or on the library's static buffer.
+int dgemm_ex_impl(bool static_ws, char transa, char transb, int64_t m, int64_t n, int64_t k, double alpha, const double* A,
+                  int64_t lda, const double* B, int64_t ldb, double beta, double* C, int64_t ldc, int num_moduli,
+                  void* stream) {
   const int ta = trans_code(transa), tb = trans_code(transb);
   if (ta < 0) return -1;
   if (tb < 0) return -2;
@@ -383,12 +400,18 @@ int oz2_dgemm_ex(char transa, char transb, int64_t m, int64_t n, int64_t k, doub
   if (!B) return -9;
   State& s = state();
   std::lock_guard<std::mutex> lock(s.mu);
+  WsRef w{s.ws, s.ws_bytes};
+  if (static_ws) {
+    // the static buffer of the current device; its address is looked up once per device, nothing is allocated
+    if (oz2_static_scratch(&w.p, &w.bytes) != hipSuccess) return OZ2_ERR_HIP;
+  }
   const Oz2Plan* plan;
   Oz2Layout lay;
   bool strassen;
-  int rc = prepare_general(s, m, n, k, num_moduli, &plan, &lay, &strassen);
+  int rc = prepare_general(s, w, m, n, k, num_moduli, &plan, &lay, &strassen);
+  if (rc == OZ2_ERR_WORKSPACE && static_ws) return OZ2_ERR_STATIC_LIMIT;
   if (rc) return rc;
-  char* const ws = s.ws;
+  char* const ws = w.p;
   auto mark = [&](int i) { return !s.ev_on || hipEventRecord(s.ev[i], st) == hipSuccess; };
   if (!mark(0)) return OZ2_ERR_HIP;
   if (oz2_launch_stage1(ta, tb, m, n, k, A, lda, B, ldb, 0, 0, *plan, s.shift_mode, s.bit_split, strassen ? 1 : 0, lay, ws,
@@ -415,6 +438,29 @@ int oz2_dgemm_ex(char transa, char transb, int64_t m, int64_t n, int64_t k, doub
                           B, ldb, beta, C, ldc, 0, 0, 0, st) != hipSuccess)
     return OZ2_ERR_HIP;
   return OZ2_OK;
+}
+
+// same argument numbering as oz2_dgemm's declaration: map the codes of the general form
+int dgemm_code(int rc) {
+  switch (rc) {
+    case -3: return -1;
+    case -4: return -2;
+    case -5: return -3;
+    case -7: return -4;
+    case -8: return -5;
+    case -9: return -6;
+    case -10: return -7;
+    case -12: return -8;
+    case -13: return -9;
+    case -14: return -10;
+    default: return rc;
+  }
+}
+}  // namespace
+
+int oz2_dgemm_ex(char transa, char transb, int64_t m, int64_t n, int64_t k, double alpha, const double* A, int64_t lda,
+                 const double* B, int64_t ldb, double beta, double* C, int64_t ldc, int num_moduli, void* stream) {
+  return dgemm_ex_impl(false, transa, transb, m, n, k, alpha, A, lda, B, ldb, beta, C, ldc, num_moduli, stream);
 }
 
 int oz2_dsyrk(char uplo, char trans, int64_t n, int64_t k, double alpha, const double* A, int64_t lda, double beta,
@@ -530,21 +576,12 @@ int oz2_dtrmm(char side, char uplo, char transa, char diag, int64_t m, int64_t n
 
 int oz2_dgemm(int64_t m, int64_t n, int64_t k, const double* A, int64_t lda, const double* B, int64_t ldb, double* C,
               int64_t ldc, int num_moduli, void* stream) {
-  // same argument numbering as the declaration: map the codes of the general entry point
-  int rc = oz2_dgemm_ex('N', 'N', m, n, k, 1.0, A, lda, B, ldb, 0.0, C, ldc, num_moduli, stream);
-  switch (rc) {
-    case -3: return -1;
-    case -4: return -2;
-    case -5: return -3;
-    case -7: return -4;
-    case -8: return -5;
-    case -9: return -6;
-    case -10: return -7;
-    case -12: return -8;
-    case -13: return -9;
-    case -14: return -10;
-    default: return rc;
-  }
+  return dgemm_code(dgemm_ex_impl(false, 'N', 'N', m, n, k, 1.0, A, lda, B, ldb, 0.0, C, ldc, num_moduli, stream));
+}
+
+int oz2_dgemm_static(int64_t m, int64_t n, int64_t k, const double* A, int64_t lda, const double* B, int64_t ldb, double* C,
+                     int64_t ldc, int num_moduli, void* stream) {
+  return dgemm_code(dgemm_ex_impl(true, 'N', 'N', m, n, k, 1.0, A, lda, B, ldb, 0.0, C, ldc, num_moduli, stream));
 }
 
 int oz2_calibrate_mfma(int workgroups, int iters, int random_operands, int* sink, long long* clocks, void* stream) {
@@ -584,6 +621,7 @@ const char* oz2_status_string(int status) {
     case OZ2_ERR_WORKSPACE: return "workspace not registered or too small";
     case OZ2_ERR_BUDGET: return "bit budget: moduli product too small for this inner dimension, or a bit split or shift mode it cannot serve";
     case OZ2_ERR_HIP: return "HIP call failed";
+    case OZ2_ERR_STATIC_LIMIT: return "problem needs more workspace than the library's static buffer holds (OZ2_STATIC_SCRATCH_BYTES)";
     default: return status < 0 ? "invalid argument" : "unknown status";
   }
 }

@@ -122,6 +122,10 @@ hipError_t oz2_launch_scale_c(int64_t m, int64_t n, double beta, double* C, int6
 hipError_t oz2_launch_mfma_calibration(int workgroups, int iters, int random_operands, int* sink, long long* clocks,
                                        hipStream_t st);
 
+// The library's own static device buffer (oz2_static.hip): address on the current device and size.  The first call
+// on a device looks the address up; nothing is ever allocated.
+hipError_t oz2_static_scratch(char** ptr, size_t* bytes);
+
 // Host instantiations of the device math (oz2_stage1.hip / oz2_stage3.hip), for unit tests.
 void oz2_host_residues_impl(const Oz2ConvConsts& c, double a, int shift, int8_t* out);
 double oz2_host_crt_impl(const Oz2CrtConsts& c, const int32_t* cprod);
