@@ -284,7 +284,6 @@ __global__ void __launch_bounds__(kThreads) gemm_i8_kernel(const GemmArgs g) {
   prologue_loads(cur);
   bool first = true;
   int round = 0;
-  bool sync_wait = true;  // cleared for the rest of the launch by the first wait that runs to its bound
   const int xcd = blockIdx.x % g.xcds;
   for (;;) {
   const int ktiles = cur.ktiles;
@@ -307,22 +306,23 @@ __global__ void __launch_bounds__(kThreads) gemm_i8_kernel(const GemmArgs g) {
   if (g.xcd_sync != nullptr && round < g.full_rounds && threadIdx.x == 0) {
     // The workgroups of an XCD start their tiles of a round together.  The wait is bounded (about a millisecond).
     // If it runs to its bound, the workgroups of this XCD are not all resident at once (another kernel holds
-    // compute units) or the counters were not cleared: this workgroup then stops waiting for the rest of the
-    // launch, so that the launch loses one bound, not one per round.  It keeps counting itself in, so the
-    // others are not held up by it.
+    // compute units) or the counters were not cleared: the counter is then pushed beyond every target of this
+    // launch, so that no workgroup of the XCD waits again -- the launch loses one bound, not one per round.
+    // (A flag kept in a register instead would live across the main loop, where no register is free.)
     unsigned long long* c = g.xcd_sync + xcd;
     if (!EARLY_ARRIVAL || round == 0) atomicAdd(c, 1ull);
-    if (sync_wait) {
-      const unsigned long long target = (unsigned long long)(gridDim.x / g.xcds) * (unsigned long long)(round + 1);
-      bool arrived = false;
-      for (int spins = 0; spins < g.sync_spins; ++spins) {
-        if (__hip_atomic_load(c, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) >= target) {
-          arrived = true;
-          break;
-        }
-        __builtin_amdgcn_s_sleep(8);
+    const unsigned long long target = (unsigned long long)(gridDim.x / g.xcds) * (unsigned long long)(round + 1);
+    bool arrived = false;
+    for (int spins = 0; spins < g.sync_spins; ++spins) {
+      if (__hip_atomic_load(c, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) >= target) {
+        arrived = true;
+        break;
       }
-      sync_wait = arrived;
+      __builtin_amdgcn_s_sleep(8);
+    }
+    if (!arrived) {
+      atomicAdd(c, 1ull << 40);
+      wait_vmcnt<0>();
     }
   }
   ++round;
