@@ -38,8 +38,13 @@
 // Otherwise each XCD walks its own contiguous range of tiles in 8-tile-tall column groups.
 //
 // General products are launched with one workgroup per compute unit; each walks the work indices of its slot in
-// launch order (so the mapping above is unchanged) and issues the first copies of its next tile before the
-// epilogue of the current one (measured: +6 % at k = 1024, neutral at k = 16384 where the power cap decides).
+// launch order (so the mapping above is unchanged).  The ring of LDS stages runs on from tile to tile: every
+// iteration of the main loop fetches the k-tile NS - 1 ahead of the one it multiplies, and when that runs past the
+// end of the tile it fetches the first k-tiles of the workgroup's next tile, so the copies of a new tile cost no
+// time of their own at the tile boundary (measured against issuing them after the main loop, before the
+// epilogue: GEMM -9 % at k = 1024, -5 % at 4096^3, -1 % at 8192^3, even at 16384^3 where the power cap decides).
+// The loop has one body for every iteration and the same number of copies in flight at every wait: with 256
+// accumulator registers per lane, a second variant of the loop body costs register moves between the variants.
 //
 // Structured products: for the symmetric product op(A) op(A)^T both operands are A's planes and the
 // workgroups of the other triangle of tiles return at once; for a triangular operand a tile walks only the
@@ -236,21 +241,25 @@ __global__ void __launch_bounds__(kThreads) gemm_i8_kernel(const GemmArgs g) {
   const unsigned lds_base = (unsigned)(size_t)(__attribute__((address_space(3))) char*)lds;
   const unsigned lds_wave = __builtin_amdgcn_readfirstlane(lds_base + wv * (64 * BK));
 
-  auto gl = [&](const Tile& T, int stage, int kt, int q) {  // direct load q in 0..7 of T's k-tile kt into `stage`
+  // direct load q in 0..7 of a k-tile (pa, pb: this wave's first bytes of its A' and B' parts) into `stage`
+  auto gl = [&](const int8_t* pa, const int8_t* pb, int stage, int q) {
     const unsigned sa = lds_wave + stage * kStageBytes;
     if (q < 4)
-      load_to_lds_16(T.a_wave + (size_t)kt * (BM * BK) + q * 1024, voff, sa + q * 1024);
+      load_to_lds_16(pa + q * 1024, voff, sa + q * 1024);
     else
-      load_to_lds_16(T.b_wave + (size_t)kt * (BN * BK) + (q - 4) * 1024, voff, sa + BM * BK + (q - 4) * 1024);
+      load_to_lds_16(pb + (q - 4) * 1024, voff, sa + BM * BK + (q - 4) * 1024);
   };
-  // k-tiles 0 .. NS-2 of a tile on their way into stages 0 .. NS-2
-  auto prologue_loads = [&](const Tile& T) {
+  // k-tiles 0 .. NS-2 of a tile on their way into the stages from `base` on (the ring of stages runs on across tiles)
+  // (a tile with fewer k-tiles fetches its k-tile 0 again in the place of those it lacks: every wait below can
+  // then count on the same number of copies in flight)
+  auto prologue_loads = [&](const Tile& T, int base) {
 #pragma unroll
-    for (int pth = 0; pth < NS - 1; ++pth)
-      if (pth < T.ktiles) {
+    for (int pth = 0; pth < NS - 1; ++pth) {
+      const int st = base + pth >= NS ? base + pth - NS : base + pth;
+      const int src = pth < T.ktiles ? pth : 0;
 #pragma unroll
-        for (int q = 0; q < kLoads; ++q) gl(T, pth, pth, q);
-      }
+      for (int q = 0; q < kLoads; ++q) gl(T.a_wave + (size_t)src * (BM * BK), T.b_wave + (size_t)src * (BN * BK), st, q);
+    }
   };
 
   // ---- LDS -> fragments: lane reads row (lane & 31) of a 32-row group, k-chunk (2 s + lane/32)
@@ -281,13 +290,28 @@ __global__ void __launch_bounds__(kThreads) gemm_i8_kernel(const GemmArgs g) {
       RESIDUE_U8 ? __builtin_amdgcn_mfma_i32_32x32x32_i8(F.a[(q)&3], F.b[(q) >> 2], acc[(q)&3][(q) >> 2], 0, 0, 0) \
                  : __builtin_amdgcn_mfma_i32_32x32x32_i8(F.b[(q) >> 2], F.a[(q)&3], acc[(q)&3][(q) >> 2], 0, 0, 0)
 
-  prologue_loads(cur);
+  prologue_loads(cur, 0);
   bool first = true;
   int round = 0;
+  int stage = 0;  // stage that holds k-tile 0 of the current tile
   const int xcd = blockIdx.x % g.xcds;
   for (;;) {
   const int ktiles = cur.ktiles;
   const int t = cur.t, tm = cur.tm, tn = cur.tn;
+  // ---- the next tile of this workgroup, if any.  Every iteration of the main loop below fetches one k-tile, NS - 1
+  // ahead of the one it multiplies.  When that runs past the end of this tile and both tiles are at least NS - 1
+  // k-tiles long, it fetches the first k-tiles of the next tile: its copies then cost no time of their own at the
+  // tile boundary.  Otherwise the slot fetches this tile's k-tile 0 once more into a stage nobody reads again (one
+  // loop body for every iteration, the same number of copies in flight at every wait).
+  Tile nxt;
+  nxt.valid = false;
+  do {
+    slot += gridDim.x;
+    nxt = decode_tile<LIST_ORDER>(g, slot, wv);
+  } while (!nxt.valid && slot < g.chunk * 8);
+  const bool across = nxt.valid && ktiles >= NS - 1 && nxt.ktiles >= NS - 1;
+  const int8_t* const over_a = across ? nxt.a_wave : cur.a_wave;
+  const int8_t* const over_b = across ? nxt.b_wave : cur.b_wave;
 #pragma unroll
   for (int x = 0; x < 4; ++x)
 #pragma unroll
@@ -298,7 +322,7 @@ __global__ void __launch_bounds__(kThreads) gemm_i8_kernel(const GemmArgs g) {
   // ---- k-tiles 0 .. NS-2 are in flight: make tile 0 visible, its first fragments in registers.  After the
   // first tile of the loop the previous epilogue's stores are outstanding as well and cannot be told apart
   // from loads by the counter, so everything is waited for (the loads were issued before that epilogue).
-  if (first && ktiles >= NS - 1)
+  if (first)
     wait_vmcnt<(NS - 2) * kLoads>();
   else
     wait_vmcnt<0>();
@@ -329,11 +353,12 @@ __global__ void __launch_bounds__(kThreads) gemm_i8_kernel(const GemmArgs g) {
   __syncthreads();
   Frag F0, F1;
 #pragma unroll
-  for (int q = 0; q < 8; ++q) rd(F0, lds, off_s0, q);
+  for (int q = 0; q < 8; ++q) rd(F0, lds + stage * kStageBytes, off_s0, q);
 
-  int stage = 0;
-  auto body = [&](int kt, auto more_tag) {
-    constexpr bool more = decltype(more_tag)::value;  // k-tile kt + NS - 1 exists
+  // fa, fb: where the next fetch reads (k-tile kt + NS - 1 of this tile while that exists)
+  const int8_t* fa = NS - 1 < ktiles ? cur.a_wave + (size_t)(NS - 1) * (BM * BK) : cur.a_wave;
+  const int8_t* fb = NS - 1 < ktiles ? cur.b_wave + (size_t)(NS - 1) * (BN * BK) : cur.b_wave;
+  auto body = [&](int kt) {
     const char* base = lds + stage * kStageBytes;
     const int nstage = stage + 1 == NS ? 0 : stage + 1;
     const char* nbase = lds + nstage * kStageBytes;
@@ -343,21 +368,26 @@ __global__ void __launch_bounds__(kThreads) gemm_i8_kernel(const GemmArgs g) {
     for (int q = 0; q < 16; ++q) {
       OZ2_MFMA(F0, q);
       if ((q & 1) == 0) rd(F1, base, off_s1, q >> 1);
+      if (q == 1 && kt + NS - 1 == ktiles) {  // the fetches run past the end of this tile from here on
+        fa = over_a;
+        fb = over_b;
+      }
       __builtin_amdgcn_sched_barrier(0);
     }
     // k-tile kt+1 must be complete in LDS for every wave before anyone reads it; passing this barrier
     // also means every wave has finished reading k-tile kt-1, whose stage is refilled below
-    if (more || kt + 2 < ktiles)
-      wait_vmcnt<(NS - 3) * kLoads>();
-    else
-      wait_vmcnt<0>();
+    wait_vmcnt<(NS - 3) * kLoads>();
     __syncthreads();
     // step 1: MFMAs on F1, fetch F0 = (tile kt+1, step 0), issue the loads of tile kt+NS-1
 #pragma unroll
     for (int q = 0; q < 16; ++q) {
       OZ2_MFMA(F1, q);
       if ((q & 1) == 0) rd(F0, nbase, off_s0, q >> 1);
-      if ((q & 1) == 1 && more) gl(cur, lstage, kt + NS - 1, q >> 1);
+      if ((q & 1) == 1) gl(fa, fb, lstage, q >> 1);
+      if (q == 15 && (kt + NS - 1 < ktiles || across)) {
+        fa += BM * BK;
+        fb += BN * BK;
+      }
       __builtin_amdgcn_sched_barrier(0);
     }
     stage = nstage;
@@ -365,12 +395,10 @@ __global__ void __launch_bounds__(kThreads) gemm_i8_kernel(const GemmArgs g) {
 
   const int p_int = (int)g.p[t];
   const float inv_pf = 1.0f / g.p[t];
-  const int last_full = ktiles - (NS - 1);  // k-tiles below this index still have a tile to prefetch
   for (int kt0 = 0; kt0 < ktiles; kt0 += g.ktiles_per_block) {
     const int kt1 = kt0 + g.ktiles_per_block < ktiles ? kt0 + g.ktiles_per_block : ktiles;
     int kt = kt0;
-    for (; kt < kt1 && kt < last_full; ++kt) body(kt, std::true_type{});
-    for (; kt < kt1; ++kt) body(kt, std::false_type{});
+    for (; kt < kt1; ++kt) body(kt);
     if (kt1 < ktiles) {  // between k-blocks: bring the accumulators back near zero
 #pragma unroll
       for (int x = 0; x < 4; ++x)
@@ -381,17 +409,14 @@ __global__ void __launch_bounds__(kThreads) gemm_i8_kernel(const GemmArgs g) {
     }
   }
 
-  // ---- the next tile of this workgroup, if any: its first copies fly during the epilogue below.  The barrier
-  // makes sure that every wave has left the main loop (all LDS reads of this tile issued) before stages refill.
-  Tile nxt;
-  nxt.valid = false;
-  do {
-    slot += gridDim.x;
-    nxt = decode_tile<LIST_ORDER>(g, slot, wv);
-  } while (!nxt.valid && slot < g.chunk * 8);
+  // ---- a next tile whose first copies were not fetched by the main loop above: they fly during the epilogue
+  // below.  The barrier makes sure that every wave has left the main loop (all LDS reads of this tile issued) before
+  // stages refill.  `stage` is by now the stage after this tile's last k-tile, where the next tile starts.
   if (nxt.valid) {
-    __syncthreads();
-    prologue_loads(nxt);
+    if (!across) {
+      __syncthreads();
+      prologue_loads(nxt, stage);
+    }
     if constexpr (EARLY_ARRIVAL) {
       // count in for the next round now: the others then wait for this workgroup's main loop only, not for its
       // epilogue, and the counter's round trip overlaps the epilogue
@@ -460,7 +485,10 @@ __global__ void __launch_bounds__(kThreads) gemm_i8_kernel(const GemmArgs g) {
         for (int e = 0; e < 16; ++e)
           plane[(col0 + tj * 32 + 8 * (e >> 2) + (e & 3)) * g.m_pad + ti * 32] = acc[ti][tj][e];
   }
-  if (!nxt.valid) break;
+  if (!nxt.valid) {
+    wait_vmcnt<0>();  // the copies fetched beyond the end of the last tile must have landed before the LDS is given back
+    break;
+  }
   cur = nxt;
   }  // loop over this workgroup's tiles
 #undef OZ2_MFMA
