@@ -245,6 +245,123 @@ __global__ void __launch_bounds__(kThreads) shifts_kernel(const ShiftJob ja, con
   j.s[i] = out;
 }
 
+// ---- Small operands: maxima and shifts (Section 3, the simple bound) of both operands in ONE launch and without
+// atomics, so that nothing has to be cleared first: a workgroup owns 16 whole vectors, forms their maxima, writes
+// them and the shifts kappa - 1 - floor(log2 max), and reports in a slot of its own whether it saw an infinity or
+// a NaN.  The conversion launch that follows folds the slots into the flag word.  Three launches fewer than
+// fill + maxima + shifts; used while the operands are small enough that 16 vectors per workgroup still fill the chip.
+constexpr int kScanVecs = 16;
+struct ScanJob {
+  const double* X;
+  int64_t ld, nvec, nvec_pad, k;
+  unsigned long long* vmax;
+  int* shifts;
+  int param;  // kappa of this operand
+  int tri, strided;
+  unsigned nblk;
+};
+__global__ void __launch_bounds__(kThreads) vector_scan_kernel(const ScanJob ja, const ScanJob jb,
+                                                               unsigned long long* __restrict__ slots) {
+  __shared__ unsigned long long part[kThreads];
+  const bool first = blockIdx.x < ja.nblk;
+  const ScanJob& j = first ? ja : jb;
+  const unsigned id = first ? blockIdx.x : blockIdx.x - ja.nblk;
+  const int64_t v0 = (int64_t)id * kScanVecs;
+  unsigned long long mx = 0ull;
+  int vv;  // which of the 16 vectors this thread's partial maximum belongs to
+  if (j.strided) {
+    // element (v, l) at X[v + l ld]: 16 lanes along the vectors (128 contiguous bytes), 16 column phases
+    vv = threadIdx.x & (kScanVecs - 1);
+    const int64_t v = v0 + vv;
+    if (v < j.nvec) {
+      const double* p = j.X + v;
+      int64_t l = threadIdx.x / kScanVecs;
+      for (; l + 7 * (kThreads / kScanVecs) < j.k; l += 8 * (kThreads / kScanVecs)) {
+        unsigned long long b[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+          const int64_t lu = l + u * (kThreads / kScanVecs);
+          b[u] = abs_bits(tri_value(p[lu * j.ld], v, lu, j.tri));
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u) mx = b[u] > mx ? b[u] : mx;
+      }
+      for (; l < j.k; l += kThreads / kScanVecs) {
+        const unsigned long long b = abs_bits(tri_value(p[l * j.ld], v, l, j.tri));
+        mx = b > mx ? b : mx;
+      }
+    }
+    part[threadIdx.x] = mx;
+    __syncthreads();
+    if (threadIdx.x < kScanVecs) {
+#pragma unroll
+      for (int ph = 1; ph < kThreads / kScanVecs; ++ph) {
+        const unsigned long long o = part[threadIdx.x + ph * kScanVecs];
+        mx = o > mx ? o : mx;
+      }
+    }
+  } else {
+    // element (v, l) at X[l + v ld]: a wave takes four vectors in turn, its lanes run down the vector
+    const int wv = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    unsigned long long mine = 0ull;
+#pragma unroll 1
+    for (int q = 0; q < kScanVecs / 4; ++q) {
+      const int64_t v = v0 + wv * (kScanVecs / 4) + q;
+      unsigned long long m = 0ull;
+      if (v < j.nvec) {
+        const double* p = j.X + v * j.ld;
+        int64_t l = lane;
+        for (; l + 7 * 64 < j.k; l += 8 * 64) {
+          unsigned long long b[8];
+#pragma unroll
+          for (int u = 0; u < 8; ++u) b[u] = abs_bits(tri_value(p[l + u * 64], l + u * 64, v, j.tri));
+#pragma unroll
+          for (int u = 0; u < 8; ++u) m = b[u] > m ? b[u] : m;
+        }
+        for (; l < j.k; l += 64) {
+          const unsigned long long b = abs_bits(tri_value(p[l], l, v, j.tri));
+          m = b > m ? b : m;
+        }
+      }
+#pragma unroll
+      for (int off = 32; off >= 1; off >>= 1) {
+        const unsigned long long o = __shfl_xor(m, off, 64);
+        m = o > m ? o : m;
+      }
+      if (lane == q) mine = m;
+    }
+    if (lane < kScanVecs / 4) part[wv * (kScanVecs / 4) + lane] = mine;
+    __syncthreads();
+    if (threadIdx.x < kScanVecs) mx = part[threadIdx.x];
+  }
+  // threads 0 .. 15 hold the maxima of the 16 vectors
+  bool bad = false;
+  if (threadIdx.x < kScanVecs) {
+    const int64_t v = v0 + threadIdx.x;
+    if (v < j.nvec_pad) {
+      j.vmax[v] = mx;
+      j.shifts[v] = mx ? j.param - 1 - exponent_of_bits(mx) : 0;
+    }
+    bad = mx >= kInfBits;
+  }
+  const int any = __syncthreads_or(bad ? 1 : 0);
+  if (threadIdx.x == 0) slots[blockIdx.x] = any ? 1ull : 0ull;
+}
+
+// What the first workgroup of the conversion launch does for the launch above: the flag word (1 when any slot
+// is set) and, cleared, the counters of the GEMM's round synchronisation.
+struct ScanFinish {
+  const unsigned long long* slots;  // null: nothing to do (the maxima came from the atomic kernels)
+  unsigned count;
+  unsigned long long* flags;        // 32 words
+};
+__device__ __forceinline__ void finish_scan(const ScanFinish& f) {
+  int bad = 0;
+  for (unsigned i = threadIdx.x; i < f.count; i += kThreads) bad |= f.slots[i] != 0ull;
+  bad = __syncthreads_or(bad);
+  if (threadIdx.x < 32) f.flags[threadIdx.x] = (threadIdx.x == 0 && bad) ? 1ull : 0ull;
+}
+
 __device__ __forceinline__ unsigned pack4(int r0, int r1, int r2, int r3) {
   return (unsigned)(r0 & 0xff) | ((unsigned)(r1 & 0xff) << 8) | ((unsigned)(r2 & 0xff) << 16) | ((unsigned)r3 << 24);
 }
@@ -431,8 +548,9 @@ constexpr int kConvTileDoubles =
     kConvARows * kConvAPitch > kConvBCols * kConvBColPitch ? kConvARows * kConvAPitch : kConvBCols * kConvBColPitch;
 template <int KA, int KB>
 __global__ void __launch_bounds__(kThreads) operand_convert_kernel(const ConvJob ja, const ConvJob jb,
-                                                                   const Oz2ConvConsts cc) {
+                                                                   const Oz2ConvConsts cc, const ScanFinish fin) {
   __shared__ __attribute__((aligned(16))) double tile[kConvTileDoubles];
+  if (fin.slots != nullptr && blockIdx.x == 0) finish_scan(fin);  // uniform over the workgroup
   if (blockIdx.x < ja.nblk) {
     const unsigned bx = blockIdx.x % ja.gx, by = blockIdx.x / ja.gx;
     if (ja.strided)
@@ -500,7 +618,8 @@ void launch_norm(const Operand& o, hipStream_t st) {
 
 // planes of one or two operands in one launch; kind 0 / 1: residue planes with the one- / two-level split,
 // kind 2: the bound plane
-hipError_t launch_convert(const Operand* ops, int nops, const int* kind, const Oz2ConvConsts& conv, hipStream_t st) {
+hipError_t launch_convert(const Operand* ops, int nops, const int* kind, const Oz2ConvConsts& conv, const ScanFinish& fin,
+                          hipStream_t st) {
   ConvJob job[2] = {};
   int64_t total = 0;
   for (int x = 0; x < nops; ++x) {
@@ -515,7 +634,7 @@ hipError_t launch_convert(const Operand* ops, int nops, const int* kind, const O
   const int ka = kind[0], kb = nops == 2 ? kind[1] : kind[0];
   if (nops == 1) job[1] = job[0], job[1].nblk = 0;
   const dim3 grid((unsigned)total), thr(kThreads);
-#define OZ2_CONV(KA, KB) hipLaunchKernelGGL((operand_convert_kernel<KA, KB>), grid, thr, 0, st, job[0], job[1], conv)
+#define OZ2_CONV(KA, KB) hipLaunchKernelGGL((operand_convert_kernel<KA, KB>), grid, thr, 0, st, job[0], job[1], conv, fin)
   if (ka == 2)
     OZ2_CONV(2, 2);
   else if (ka == 0 && kb == 0)
@@ -572,16 +691,44 @@ hipError_t oz2_launch_stage1(int transa, int transb, int64_t m, int64_t n, int64
   // the odd bit of the sum (bit_split == 0: the equal split; the symmetric product always uses it).
   const int d = bit_split;
   int xbits[2];  // |x'| < 2^xbits decides how deep the conversion kernels split an element
+  ScanFinish fin = {nullptr, 0u, nullptr};
+  // Small operands under the simple bound: maxima and shifts in one launch without atomics (nothing to clear
+  // first); its per-workgroup reports become the flag word in the conversion launch.  "Small": at most 2^25 elements
+  // in both operands together (4096 x 4096 twice), where 16 vectors per workgroup are work enough for the chip
+  // and the launches saved still count.
+  const bool scan = shift_mode == OZ2_SHIFT_MAX && !strassen &&
+                    (lay.m_pad + (nops == 2 ? lay.n_pad : 0)) * lay.k_pad <= ((int64_t)1 << 25);
+  if (scan) {
+    const int kappa_a = plan.kappa - d, kappa_b = d == 0 ? plan.kappa : plan.kappa_sum - kappa_a;
+    ScanJob sj[2] = {};
+    unsigned total = 0;
+    for (int x = 0; x < nops; ++x) {
+      const Operand& o = ops[x];
+      sj[x] = {o.X, o.ld, o.nvec, o.nvec_pad, o.k, o.vmax, o.shifts, x == 0 ? kappa_a : kappa_b, o.tri, o.strided ? 1 : 0,
+               (unsigned)(o.nvec_pad / kScanVecs)};
+      total += sj[x].nblk;
+    }
+    if (nops == 1) sj[1] = sj[0], sj[1].nblk = 0;
+    // the slots live in the auxiliary vectors, which this shift mode does not use (one word per 16 vectors)
+    unsigned long long* slots = ops[0].vaux;
+    hipLaunchKernelGGL(vector_scan_kernel, dim3(total), thr, 0, st, sj[0], sj[1], slots);
+    fin = {slots, total, flag};
+    xbits[0] = kappa_a;
+    xbits[1] = kappa_b;
+  } else {
   fill(ops[0].vmax, n_max);
   if (hipError_t e = launch_max(ops, nops, st); e != hipSuccess) return e;
-  if (shift_mode == OZ2_SHIFT_INT8_PRODUCT) {
+  }
+  if (scan) {
+    // shifts are written
+  } else if (shift_mode == OZ2_SHIFT_INT8_PRODUCT) {
     // bound planes (in the slots of residue plane 0), their INT8 product (in the slot of product plane 0),
     // its row and column maxima, then the shifts.  In the symmetric case the product is A''A''^T and its
     // row maxima are its column maxima (those land in the unused column array).
     shifts(0, 6, 6, 0, 0);  // exponents 5 - e of the bounds
     {
       const int bound[2] = {2, 2};
-      if (hipError_t e = launch_convert(ops, nops, bound, conv, st); e != hipSuccess) return e;
+      if (hipError_t e = launch_convert(ops, nops, bound, conv, ScanFinish{nullptr, 0u, nullptr}, st); e != hipSuccess) return e;
     }
     fill(ops[0].vaux, n_aux);
     hipError_t e = oz2_launch_bound_gemm(lay, ws, B == nullptr, st);
@@ -613,7 +760,7 @@ hipError_t oz2_launch_stage1(int transa, int transb, int64_t m, int64_t n, int64
     if (!B || tri_a || tri_b) return hipErrorInvalidValue;
     return oz2_launch_strassen_convert(transa, transb, m, n, k, A, lda, B, ldb, plan, kinds, lay, ws, st);
   }
-  if (hipError_t e = launch_convert(ops, nops, kinds, conv, st); e != hipSuccess) return e;
+  if (hipError_t e = launch_convert(ops, nops, kinds, conv, fin, st); e != hipSuccess) return e;
   return hipGetLastError();
 }
 
