@@ -19,6 +19,43 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 INT8_MFMA_PEAK_TOPS = 5000.0   # MI355X dense INT8 matrix peak, TOP/s
+HBM_PEAK_GBPS = 8000.0         # MI355X HBM3E peak
+
+GEMM_SOURCE = os.path.join(ROOT, "paper_2504_08009_amd", "csrc", "oz2_stage2.hip")
+TRAFFIC_FILE = os.path.join(ROOT, "profiles", "gemm_hbm_traffic.txt")
+
+
+def gemm_source_hash():
+    import hashlib
+    with open(GEMM_SOURCE, "rb") as f:
+        return hashlib.sha256(f.read()).hexdigest()[:16]
+
+
+def measured_traffic(key):
+    """HBM-side bytes per GEMM launch from the rocprofv3 counter runs summarised in profiles/gemm_hbm_traffic.txt
+    (FETCH_SIZE and WRITE_SIZE, each scaled by what the same counter reads for a plain copy of known size).  The
+    file names the hash of the GEMM source it was taken on; for any other source the figure would be stale and None
+    is returned."""
+    try:
+        entries = {}
+        with open(TRAFFIC_FILE) as f:
+            for line in f:
+                line = line.split("#")[0].strip()
+                if "=" in line:
+                    k, v = [t.strip() for t in line.split("=", 1)]
+                    entries[k] = v
+    except OSError:
+        return None
+    if entries.get("gemm_source_sha256_16") != gemm_source_hash():
+        return None
+    try:
+        fetch = float(entries[key + ".fetch_size_raw_GiB"]) * float(entries["fetch_size_scale"])
+        write = float(entries[key + ".write_size_raw_GiB"]) * float(entries["write_size_scale"])
+        return {"bytes": round((fetch + write) * 2**30), "read_GiB": round(fetch, 2), "written_GiB": round(write, 2),
+                "algorithmic_GiB": float(entries[key + ".algorithmic_GiB"]),
+                "source": "profiles/gemm_hbm_traffic.txt (GEMM source %s)" % entries["gemm_source_sha256_16"]}
+    except (KeyError, ValueError):
+        return None
 
 
 def main():
@@ -93,6 +130,19 @@ def main():
         oz.oz2_set_stage_events(events)
         oz.oz2_dgemm(m, n, k, dA.data_ptr(), m, dB.data_ptr(), k, dC.data_ptr(), m, N, stream)
 
+    def timed_ms(call, reps=5):
+        """average milliseconds of `call` over reps launches, HIP events on the stream the library launches on"""
+        call()
+        torch.cuda.synchronize()
+        a, b = new_event(), new_event()
+        sp = ctypes.c_void_p(stream.cuda_stream)
+        assert hip.hipEventRecord(a, sp) == 0
+        for _ in range(reps):
+            call()
+        assert hip.hipEventRecord(b, sp) == 0
+        torch.cuda.synchronize()
+        return elapsed(a, b) / reps
+
     print("bench: timing %d steps ..." % args.steps, file=sys.stderr, flush=True)
     for _ in range(args.warmup):
         step()
@@ -148,25 +198,35 @@ def main():
         roofline["achieved_as_2mnkN"] = round(alg_tops, 2)
         roofline["frac_as_2mnkN"] = round(alg_tops / INT8_MFMA_PEAK_TOPS, 4)
         roofline["note"] = "achieved counts the INT8 operations executed: 7 half-size products per modulus, 7/8 of 2mnkN"
-    if args.workload == "c4" and N == 16 and not args.mnk and args.shift_mode == 0:
-        # HBM-side bytes per launch from the rocprofv3 counter runs summarised in
-        # profiles/c4_oz2_dgemm_counters.md: FETCH_SIZE x 2.0 (copy-kernel scale) + WRITE_SIZE, in GiB, for the
-        # Strassen form (UINT8 planes), the classical form with UINT8 planes and the classical form with INT32 planes
-        if strassen:
-            fetch_gib, write_gib, min_gib = 43.244, 14.064, 21
-        elif fmt == oz.OZ2_PRODUCT_RESIDUE_U8:
-            fetch_gib, write_gib, min_gib = 48.658, 8.051, 12
+    if not args.mnk and args.shift_mode == 0 and N == (16 if args.workload == "c4" else cfg["N"][len(cfg["N"]) // 2]):
+        # a counter measurement, not made in this run: valid only for the GEMM source it was taken on
+        tr = measured_traffic("%s.%s.%s" % (args.workload, "strassen" if strassen else "classical",
+                                            "u8" if fmt == oz.OZ2_PRODUCT_RESIDUE_U8 else "int32"))
+        if tr:
+            roofline["traffic"] = tr["bytes"]
+            roofline["traffic_unit"] = ("bytes per launch leaving the L2 (reads %.1f GiB + writes %.1f GiB; algorithmic "
+                                        "minimum %g GiB)" % (tr["read_GiB"], tr["written_GiB"], tr["algorithmic_GiB"]))
+            roofline["traffic_source"] = tr["source"]
         else:
-            fetch_gib, write_gib, min_gib = 54.186, 19.125, 24
-        roofline["traffic"] = round((fetch_gib * 2.0 + write_gib) * 2**30)
-        roofline["traffic_unit"] = "bytes per launch (L2 misses + write-backs; algorithmic minimum %d GiB)" % min_gib
+            roofline["traffic_source"] = "none for this build (profiles/gemm_hbm_traffic.txt names another GEMM source or has no entry)"
+    # The memory-bound stages: bytes the launches of this form move (the Strassen form writes and reads 7/4 of the
+    # plane bytes) and the bytes of the method itself, (16 + N)(mk + kn) for lines 1-5 read twice and (N + 8) mn for
+    # lines 8-11, both over the measured stage time and against the HBM peak.  The practical ceiling on this card
+    # is what a plain device copy sustains (context.device_copy_GBps_same_gpu, about 0.62 of the peak).
+    own1 = (16 + N) * (m * k + k * n) + 4 * (m + n)
+    own3 = ((1 if fmt == oz.OZ2_PRODUCT_RESIDUE_U8 else 4) * N + 8) * m * n + 4 * (m + n)
+    gbps = lambda b, ms: b / (ms * 1e-3) / 1e9
     stages = {
         "stage1_convert_ms": round(float(avg[0]), 4),
         "stage2_gemm_ms": round(gemm_ms, 4),
         "stage3_crt_ms": round(float(avg[2]), 4),
-        "stage1_algorithmic_GBps": round(s1_bytes / (avg[0] * 1e-3) / 1e9, 1),
-        "stage3_algorithmic_GBps": round(s3_bytes / (avg[2] * 1e-3) / 1e9, 1),
-        "hbm_peak_GBps": 8000.0,
+        "stage1_algorithmic_GBps": round(gbps(s1_bytes, avg[0]), 1),
+        "stage3_algorithmic_GBps": round(gbps(s3_bytes, avg[2]), 1),
+        "stage1_frac_of_hbm_peak_moved_bytes": round(gbps(s1_bytes, avg[0]) / HBM_PEAK_GBPS, 4),
+        "stage3_frac_of_hbm_peak_moved_bytes": round(gbps(s3_bytes, avg[2]) / HBM_PEAK_GBPS, 4),
+        "stage1_frac_of_hbm_peak_method_bytes": round(gbps(own1, avg[0]) / HBM_PEAK_GBPS, 4),
+        "stage3_frac_of_hbm_peak_method_bytes": round(gbps(own3, avg[2]) / HBM_PEAK_GBPS, 4),
+        "hbm_peak_GBps": HBM_PEAK_GBPS,
     }
 
     out = {
@@ -224,13 +284,8 @@ def main():
         for Nx in (14, 15, 17, 18):
             del ws
             ws = oz.Workspace(m, n, k, Nx, device=dev, product_format=fmt)
-            oz.oz2_dgemm(m, n, k, dA.data_ptr(), m, dB.data_ptr(), k, dC.data_ptr(), m, Nx, stream)
-            torch.cuda.synchronize()
-            t0 = time.perf_counter()
-            for _ in range(3):
-                oz.oz2_dgemm(m, n, k, dA.data_ptr(), m, dB.data_ptr(), k, dC.data_ptr(), m, Nx, stream)
-            torch.cuda.synchronize()
-            per_n[str(Nx)] = round(2.0 * m * n * k / ((time.perf_counter() - t0) / 3) / 1e12, 2)
+            ms_n = timed_ms(lambda: oz.oz2_dgemm(m, n, k, dA.data_ptr(), m, dB.data_ptr(), k, dC.data_ptr(), m, Nx, stream))
+            per_n[str(Nx)] = round(2.0 * m * n * k / (ms_n * 1e-3) / 1e12, 2)
             if not args.no_cpu_baseline:
                 # error of the same sample of C against the exact product (the reference was formed above)
                 gx = dC[torch.from_numpy(rows).to(dev)][:, torch.from_numpy(cols).to(dev)].cpu().numpy()
@@ -243,13 +298,7 @@ def main():
         if strassen:
             # the same call with Algorithm 1 line 6 as printed (one full-size INT8 product per modulus)
             oz.oz2_set_gemm_algorithm(oz.OZ2_GEMM_CLASSICAL)
-            oz.oz2_dgemm(m, n, k, dA.data_ptr(), m, dB.data_ptr(), k, dC.data_ptr(), m, N, stream)
-            torch.cuda.synchronize()
-            t0 = time.perf_counter()
-            for _ in range(3):
-                oz.oz2_dgemm(m, n, k, dA.data_ptr(), m, dB.data_ptr(), k, dC.data_ptr(), m, N, stream)
-            torch.cuda.synchronize()
-            cl_t = (time.perf_counter() - t0) / 3
+            cl_t = timed_ms(lambda: oz.oz2_dgemm(m, n, k, dA.data_ptr(), m, dB.data_ptr(), k, dC.data_ptr(), m, N, stream)) * 1e-3
             oz.oz2_set_gemm_algorithm(args.gemm_algorithm)
             out["classical_form_%d_moduli" % N] = {"ms_per_call": round(cl_t * 1e3, 3),
                                                    "emulated_TFLOPS": round(2.0 * m * n * k / cl_t / 1e12, 2)}
@@ -266,13 +315,7 @@ def main():
         dC2 = torch.empty((n, m), dtype=torch.float64, device=dev).t()
         for mode, label in ((1, "cauchy_schwarz_mode_14_moduli"), (2, "int8_product_mode_14_moduli")):
             oz.oz2_set_shift_mode(mode)
-            oz.oz2_dgemm(m, n, k, dA.data_ptr(), m, dB.data_ptr(), k, dC2.data_ptr(), m, 14, stream)
-            torch.cuda.synchronize()
-            t0 = time.perf_counter()
-            for _ in range(3):
-                oz.oz2_dgemm(m, n, k, dA.data_ptr(), m, dB.data_ptr(), k, dC2.data_ptr(), m, 14, stream)
-            torch.cuda.synchronize()
-            mode_t = (time.perf_counter() - t0) / 3
+            mode_t = timed_ms(lambda: oz.oz2_dgemm(m, n, k, dA.data_ptr(), m, dB.data_ptr(), k, dC2.data_ptr(), m, 14, stream)) * 1e-3
             oz.oz2_set_shift_mode(0)
             g2 = dC2[torch.from_numpy(rows).to(dev)][:, torch.from_numpy(cols).to(dev)].cpu().numpy()
             out[label] = {
@@ -284,26 +327,14 @@ def main():
         # TFLOPS counted with the flops of the full product so that it compares with the lines above
         ws = oz.Workspace(m, m, k, N, device=dev, product_format=fmt)
         dC2 = torch.zeros((m, m), dtype=torch.float64, device=dev).t()
-        oz.oz2_dsyrk("L", "N", m, k, 1.0, dA.data_ptr(), m, 0.0, dC2.data_ptr(), m, N, stream)
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        for _ in range(3):
-            oz.oz2_dsyrk("L", "N", m, k, 1.0, dA.data_ptr(), m, 0.0, dC2.data_ptr(), m, N, stream)
-        torch.cuda.synchronize()
-        syrk_t = (time.perf_counter() - t0) / 3
+        syrk_t = timed_ms(lambda: oz.oz2_dsyrk("L", "N", m, k, 1.0, dA.data_ptr(), m, 0.0, dC2.data_ptr(), m, N, stream)) * 1e-3
         out["dsyrk_lower_%d_moduli" % N] = {"ms_per_call": round(syrk_t * 1e3, 3),
                                             "TFLOPS_as_full_product": round(2.0 * m * m * k / syrk_t / 1e12, 2)}
         # context: the triangular product B := A_lower * B in place (same sizes; half of the inner dimension
         # is zero by structure)
         if m == k:
             dB2 = dB.clone()
-            oz.oz2_dtrmm("L", "L", "N", "N", m, n, 1.0, dA.data_ptr(), m, dB2.data_ptr(), k, N, stream)
-            torch.cuda.synchronize()
-            t0 = time.perf_counter()
-            for _ in range(3):
-                oz.oz2_dtrmm("L", "L", "N", "N", m, n, 1.0, dA.data_ptr(), m, dB2.data_ptr(), k, N, stream)
-            torch.cuda.synchronize()
-            trmm_t = (time.perf_counter() - t0) / 3
+            trmm_t = timed_ms(lambda: oz.oz2_dtrmm("L", "L", "N", "N", m, n, 1.0, dA.data_ptr(), m, dB2.data_ptr(), k, N, stream)) * 1e-3
             out["dtrmm_left_lower_%d_moduli" % N] = {"ms_per_call": round(trmm_t * 1e3, 3),
                                                      "TFLOPS_as_full_product": round(2.0 * m * n * k / trmm_t / 1e12, 2)}
             del dB2
