@@ -74,6 +74,9 @@ def main():
                     help="0: INT32 product planes; 1: UINT8 residue planes (library default)")
     ap.add_argument("--gemm-algorithm", type=int, default=-1,
                     help="-1: library default (Strassen form of the INT8 products for large sizes); 0: classical; 1: Strassen form")
+    ap.add_argument("--round-sync", type=int, default=-1,
+                    help="bound (polls) of a wait of the GEMM's round synchronisation; 0 switches it off, 1 makes every "
+                         "first wait run to its bound (library default 4096)")
     ap.add_argument("--graph", action="store_true",
                     help="time replays of one captured HIP graph of the call instead of eager calls (small sizes)")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -110,6 +113,8 @@ def main():
     oz.oz2_set_product_format(fmt)
     oz.oz2_set_gemm_algorithm(args.gemm_algorithm)
     oz.oz2_set_shift_mode(args.shift_mode)
+    if args.round_sync >= 0:
+        oz.oz2_set_round_sync(args.round_sync)
     ws = oz.Workspace(m, n, k, N, device=dev, product_format=fmt)
     strassen = oz.oz2_gemm_algorithm_for(m, n, k, N) == oz.OZ2_GEMM_STRASSEN
     stream = torch.cuda.current_stream()

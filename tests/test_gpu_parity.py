@@ -304,6 +304,31 @@ def test_full_size_configs_on_sampled_outputs(name, kblock, algorithm, N):
     del ws
 
 
+@pytest.mark.parametrize("spins", [1, 0, 4096])
+def test_round_synchronisation_bound_and_switch(spins):
+    """The GEMM's per-die round synchronisation with its wait bound forced down to one poll (so that waits run to
+    their bound, the die's counter is pushed past every target and the rest of the launch runs unsynchronised),
+    switched off, and at its default: the residues and C are the oracle's every time.  Inner dimension 6400 puts the
+    launch among those that synchronise (more than 96 k-tiles), 22 planes of 3 x 2 tiles give every workgroup
+    several rounds."""
+    rng = np.random.default_rng(61)
+    m, n, k, N = 700, 500, 6400, 22
+    A = np.asfortranarray((rng.random((m, k)) - 0.5) * np.exp(0.5 * rng.standard_normal((m, k))))
+    B = np.asfortranarray((rng.random((k, n)) - 0.5) * np.exp(0.5 * rng.standard_normal((k, n))))
+    oz.oz2_set_round_sync(spins)
+    try:
+        got = run_stages(A, B, N, fmt=1)
+        ws = oz.Workspace(m, n, k, N)
+        C = oz.dgemm(_dev(A), _dev(B), N, workspace=ws)
+        torch.cuda.synchronize()
+    finally:
+        oz.oz2_set_round_sync(4096)
+    ref = orc.dgemm(A, B, N, want=("C", "Cres"))
+    assert np.array_equal(got["Cp"][:, :n, :m].transpose(0, 2, 1), ref.Cres)
+    assert np.array_equal(got["C"], ref.C) and np.array_equal(C.cpu().numpy(), ref.C)
+    del ws
+
+
 _c3_oracle = {}
 
 

@@ -106,6 +106,15 @@ def test_round_sync_setting_is_validated():
     assert L.oz2_set_round_sync(0) == 0 and L.oz2_set_round_sync(4096) == 0
 
 
+def test_traffic_profile_belongs_to_the_gemm_source_in_the_tree():
+    """bench.py reports roofline.traffic from profiles/gemm_hbm_traffic.txt only while that file names the GEMM source
+    it was measured on; this fails when the kernel was edited and the counters were not taken again."""
+    import bench
+    tr = bench.measured_traffic("c4.strassen.u8")
+    assert tr is not None, "profiles/gemm_hbm_traffic.txt was taken on another oz2_stage2.hip: profile again"
+    assert tr["bytes"] > tr["algorithmic_GiB"] * 2**30 and bench.measured_traffic("no.such.entry") is None
+
+
 def test_workspace_layout_is_consistent():
     for fmt, bpe in ((oz.OZ2_PRODUCT_RESIDUE_U8, 1), (oz.OZ2_PRODUCT_INT32, 4)):
         oz.oz2_set_product_format(fmt)
