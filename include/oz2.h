@@ -14,8 +14,10 @@
  *     too small for this inner dimension (kappa < 1), or the inner dimension too long for the shift mode; OZ2_ERR_HIP (3) a HIP call failed.
  *     Nothing is printed and nothing throws across this boundary.
  *   - The method covers finite inputs (Section 3.1, last paragraph).  Infinities and NaNs in A or B are detected
- *     and handled by an FP64 fallback (oz2_set_nonfinite_check, on by default); signed zeros are not tracked
- *     (an emulated zero is +0); results beyond the FP64 range become infinities as in FP64.
+ *     and handled by an FP64 fallback (oz2_set_nonfinite_check, on by default).  Signed zeros need no handling:
+ *     -0 in A or B counts as zero and an emulated zero is +0, which is what an FP64 sum that starts from +0 gives
+ *     for products that are all zero, whatever their signs; a result that underflows keeps its sign.  Results
+ *     beyond the FP64 range become infinities as in FP64.
  *   - One GPU: the library is used from one device per process (kernel attributes are set once).
  *   - The library keeps one workspace registration per process (oz2_set_workspace).  Calls that use it
  *     must not overlap in time on different streams.
