@@ -395,7 +395,7 @@ def main():
             pass
         sink = torch.empty(512 * 256, dtype=torch.int32, device=dev)
         clocks = torch.zeros(2, dtype=torch.int64, device=dev)
-        for label, rnd in (("constant", 0), ("random", 1)):
+        for label, rnd in (("constant", 0), ("random", 1), ("fresh_random", 2)):
             iters = 200000
             oz.oz2_calibrate_mfma(512, 2000, rnd, sink.data_ptr(), clocks.data_ptr(), stream)
             torch.cuda.synchronize()
@@ -409,9 +409,14 @@ def main():
             out["context"]["mfma_only_%s_operands_GHz" % label] = round(cyc / max(ref, 1) * 0.1, 3)
         # the GEMM against what the matrix cores of this card sustain on random INT8 operands with no memory
         # traffic at all (the card is power-capped well below the published peak)
+        # (random: two operand fragments reused by every instruction; fresh_random: eight per operand in changing
+        # pairs, as in a product, where no instruction finds its operands in the matrix core's input latches)
         cal = out["context"].get("mfma_only_random_operands_TOPs")
         if cal:
             out["roofline"]["frac_of_mfma_only_random_operands"] = round(gemm_tops / cal, 4)
+        cal = out["context"].get("mfma_only_fresh_random_operands_TOPs")
+        if cal:
+            out["roofline"]["frac_of_mfma_only_fresh_random_operands"] = round(gemm_tops / cal, 4)
         if not args.no_cpu_baseline:
             gotn = Cn[torch.from_numpy(rows).to(dev)][:, torch.from_numpy(cols).to(dev)].cpu().numpy()
             out["context"]["native_fp64_max_componentwise_err_vs_exact"] = float(np.max(np.abs(gotn - Cx) / S))

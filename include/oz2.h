@@ -255,8 +255,10 @@ int oz2_set_stage_events(void* const events[4]);
 
 /* Measurement support: an MFMA-only kernel (v_mfma_i32_32x32x32_i8, no memory traffic) that shows what
  * the matrix cores of the card sustain under its power cap.  `workgroups` x 256 threads each issue
- * iters x 8 MFMAs (65536 INT8 operations per wave and MFMA); random_operands != 0 fills the operand
- * registers with random bytes, 0 with a constant.  sink: device buffer of workgroups*256 ints (written).
+ * iters x 8 MFMAs (65536 INT8 operations per wave and MFMA); random_operands: 0 fills the operand registers with a
+ * constant, 1 with random bytes (two fragments per operand, reused by every instruction), 2 with random bytes in
+ * eight fragments per operand that meet in changing pairs, as the fragments of a product do (iters should then
+ * be a multiple of 8).  sink: device buffer of workgroups*256 ints (written).
  * clocks: device buffer of two int64: shader-clock cycles and 100 MHz reference ticks spent in the loop by
  * workgroup 0.  The caller times the launch itself.  Returns 0, a negative argument code, or OZ2_ERR_HIP. */
 int oz2_calibrate_mfma(int workgroups, int iters, int random_operands, int* sink, long long* clocks, void* stream);

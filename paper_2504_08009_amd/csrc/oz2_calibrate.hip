@@ -26,11 +26,35 @@ __global__ void __launch_bounds__(256) mfma_only_kernel(int iters, int random_op
   for (int i = 0; i < 8; ++i)
 #pragma unroll
     for (int e = 0; e < 16; ++e) acc[i][e] = 0;
-  const long long c0 = clock64();
-  const long long w0 = wall_clock64();
-  for (int it = 0; it < iters; ++it) {
+  long long c0 = clock64();
+  long long w0 = wall_clock64();
+  if (random_operands == 2) {
+    // eight different fragments per operand, every MFMA with another pair: as in a product, where no operand
+    // register is reused by the next instruction (the two-fragment loop below toggles fewer operand bits)
+    v4i a8[8], b8[8];
 #pragma unroll
-    for (int i = 0; i < 8; ++i) acc[i] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[i & 1], b[(i >> 1) & 1], acc[i], 0, 0, 0);
+    for (int s = 0; s < 8; ++s)
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        h = h * 1664525u + 1013904223u;
+        a8[s][e] = (int)h;
+        h = h * 1664525u + 1013904223u;
+        b8[s][e] = (int)h;
+      }
+    c0 = clock64();
+    w0 = wall_clock64();
+    for (int it = 0; it < iters; it += 8) {
+#pragma unroll
+      for (int u = 0; u < 8; ++u)
+#pragma unroll
+        for (int i = 0; i < 8; ++i)
+          acc[i] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a8[(i + u) & 7], b8[(i + 3 * u) & 7], acc[i], 0, 0, 0);
+    }
+  } else {
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+      for (int i = 0; i < 8; ++i) acc[i] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[i & 1], b[(i >> 1) & 1], acc[i], 0, 0, 0);
+    }
   }
   const long long c1 = clock64();
   const long long w1 = wall_clock64();
