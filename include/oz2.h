@@ -179,6 +179,47 @@ int oz2_stage1_convert(int64_t m, int64_t n, int64_t k, const double* A, int64_t
 int oz2_stage2_gemm(int64_t m, int64_t n, int64_t k, int num_moduli, void* stream);
 int oz2_stage3_crt(int64_t m, int64_t n, int64_t k, double* C, int64_t ldc, int num_moduli, void* stream);
 
+/* Contexts.  The calls above share one process-wide set of settings (shift mode, product format, form of the
+ * products, k-block, bit split, non-finite check), one workspace registration and one plan cache: what a call
+ * computes depends on settings another thread may change, and two calls that use the one workspace must not overlap.
+ * A context is a private copy of all of that: its own settings (at the defaults when created), its own workspace
+ * registration, its own lock.  Calls on different contexts, each with a workspace of its own, may be made from
+ * different threads and may overlap in time on different streams; calls on one context serialise on its lock and,
+ * like the plain calls, must not overlap on the GPU.  A NULL context means the process-wide one, so
+ * oz2_context_dgemm(NULL, ...) is oz2_dgemm_ex.  Nothing in the paper corresponds to this; it is how the
+ * library keeps Algorithm 1's options out of global state.
+ *   oz2_context_create / destroy : host object only, no device memory; destroy does not touch the workspace.
+ *   oz2_context_set_workspace    : as oz2_set_workspace, for this context.
+ *   oz2_context_set / get        : option = OZ2_OPT_*, value as in the oz2_set_* call of the same name.  Returns 0,
+ *                                  -2 for an unknown option, -3 for a value that call rejects.
+ *   oz2_context_workspace_bytes  : bytes with which a general product of this shape takes the form this context's
+ *                                  settings prefer (oz2_workspace_bytes_preferred for the context).
+ *   oz2_context_dgemm / dsyrk / dtrmm : oz2_dgemm_ex / oz2_dsyrk / oz2_dtrmm under this context's settings and
+ *                                  workspace; argument codes are 1-based over their own parameter lists (the
+ *                                  context is argument 1).
+ * The bound of the GEMM's round synchronisation (oz2_set_round_sync), the stage events and the staged entry points
+ * belong to the process-wide context only. */
+typedef struct oz2_context oz2_context;
+#define OZ2_OPT_SHIFT_MODE 0
+#define OZ2_OPT_PRODUCT_FORMAT 1
+#define OZ2_OPT_GEMM_ALGORITHM 2
+#define OZ2_OPT_KBLOCK 3
+#define OZ2_OPT_BIT_SPLIT 4
+#define OZ2_OPT_NONFINITE_CHECK 5
+int oz2_context_create(oz2_context** ctx);
+int oz2_context_destroy(oz2_context* ctx);
+int oz2_context_set_workspace(oz2_context* ctx, void* dev_ptr, size_t bytes);
+int oz2_context_set(oz2_context* ctx, int option, int64_t value);
+int oz2_context_get(oz2_context* ctx, int option, int64_t* value);
+size_t oz2_context_workspace_bytes(oz2_context* ctx, int64_t m, int64_t n, int64_t k, int num_moduli);
+int oz2_context_dgemm(oz2_context* ctx, char transa, char transb, int64_t m, int64_t n, int64_t k, double alpha,
+                      const double* A, int64_t lda, const double* B, int64_t ldb, double beta, double* C, int64_t ldc,
+                      int num_moduli, void* stream);
+int oz2_context_dsyrk(oz2_context* ctx, char uplo, char trans, int64_t n, int64_t k, double alpha, const double* A,
+                      int64_t lda, double beta, double* C, int64_t ldc, int num_moduli, void* stream);
+int oz2_context_dtrmm(oz2_context* ctx, char side, char uplo, char transa, char diag, int64_t m, int64_t n, double alpha,
+                      const double* A, int64_t lda, double* B, int64_t ldb, int num_moduli, void* stream);
+
 /* Exceptional values (Section 3.1, closing remark: the emulation covers products of finite matrices; NaNs
  * and infinities need detection and a fallback to ordinary FP64 arithmetic).  With the check on (default),
  * stage 1 of oz2_dgemm / oz2_dgemm_ex records in the workspace whether A or B holds an infinity or a NaN

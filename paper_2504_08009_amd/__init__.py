@@ -9,5 +9,6 @@ from .binding import (  # noqa: F401
     oz2_set_kblock, oz2_set_round_sync, oz2_set_shift_mode, oz2_set_product_format, oz2_set_bit_split, oz2_set_nonfinite_check, oz2_set_stage_events, oz2_calibrate_mfma,
     oz2_stage1_convert, oz2_stage2_gemm, oz2_stage3_crt, set_workspace, workspace_bytes, workspace_layout,
     oz2_set_gemm_algorithm, oz2_gemm_algorithm_for, workspace_bytes_strassen, workspace_bytes_preferred,
-    Workspace, dgemm,
+    Workspace, dgemm, Context,
+    OZ2_OPT_SHIFT_MODE, OZ2_OPT_PRODUCT_FORMAT, OZ2_OPT_GEMM_ALGORITHM, OZ2_OPT_KBLOCK, OZ2_OPT_BIT_SPLIT, OZ2_OPT_NONFINITE_CHECK,
 )

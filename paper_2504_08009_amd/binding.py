@@ -10,6 +10,8 @@ SYMBOLS = [
     "oz2_init", "oz2_min_moduli", "oz2_moduli_for_bits", "oz2_max_moduli", "oz2_get_moduli", "oz2_workspace_bytes", "oz2_workspace_bytes_for", "oz2_set_workspace",
     "oz2_workspace_layout", "oz2_dgemm", "oz2_dgemm_static", "oz2_dgemm_ex", "oz2_dsyrk", "oz2_dtrmm", "oz2_stage1_convert", "oz2_stage2_gemm", "oz2_stage3_crt",
     "oz2_set_gemm_algorithm", "oz2_gemm_algorithm_for", "oz2_workspace_bytes_strassen", "oz2_workspace_bytes_preferred",
+    "oz2_context_create", "oz2_context_destroy", "oz2_context_set_workspace", "oz2_context_set", "oz2_context_get",
+    "oz2_context_workspace_bytes", "oz2_context_dgemm", "oz2_context_dsyrk", "oz2_context_dtrmm",
     "oz2_set_kblock", "oz2_set_round_sync", "oz2_set_shift_mode", "oz2_set_product_format", "oz2_set_bit_split", "oz2_set_nonfinite_check", "oz2_set_stage_events", "oz2_calibrate_mfma", "oz2_host_crt_element", "oz2_host_residues", "oz2_status_string",
 ]
 
@@ -51,6 +53,18 @@ def lib():
         L.oz2_stage2_gemm.argtypes = [i64, i64, i64, ci, vp]
         L.oz2_stage3_crt.argtypes = [i64, i64, i64, vp, i64, ci, vp]
         L.oz2_set_kblock.argtypes = [i64]
+        L.oz2_context_create.argtypes = [vp]
+        L.oz2_context_destroy.argtypes = [vp]
+        L.oz2_context_set_workspace.argtypes = [vp, vp, ctypes.c_size_t]
+        L.oz2_context_set.argtypes = [vp, ci, i64]
+        L.oz2_context_get.argtypes = [vp, ci, vp]
+        L.oz2_context_workspace_bytes.restype = ctypes.c_size_t
+        L.oz2_context_workspace_bytes.argtypes = [vp, i64, i64, i64, ci]
+        L.oz2_context_dgemm.argtypes = [vp, ctypes.c_char, ctypes.c_char, i64, i64, i64, ctypes.c_double, vp, i64, vp, i64,
+                                        ctypes.c_double, vp, i64, ci, vp]
+        L.oz2_context_dsyrk.argtypes = [vp, ctypes.c_char, ctypes.c_char, i64, i64, ctypes.c_double, vp, i64, ctypes.c_double,
+                                        vp, i64, ci, vp]
+        L.oz2_context_dtrmm.argtypes = [vp] + [ctypes.c_char] * 4 + [i64, i64, ctypes.c_double, vp, i64, vp, i64, ci, vp]
         L.oz2_set_round_sync.argtypes = [ci]
         L.oz2_set_shift_mode.argtypes = [ci]
         L.oz2_set_product_format.argtypes = [ci]
@@ -258,6 +272,66 @@ def host_residues(num_moduli, kappa, a, shift):
     out = (ctypes.c_int8 * num_moduli)()
     _check(lib().oz2_host_residues(num_moduli, kappa, float(a), int(shift), out), "oz2_host_residues")
     return list(out)
+
+
+OZ2_OPT_SHIFT_MODE, OZ2_OPT_PRODUCT_FORMAT, OZ2_OPT_GEMM_ALGORITHM, OZ2_OPT_KBLOCK, OZ2_OPT_BIT_SPLIT, OZ2_OPT_NONFINITE_CHECK = range(6)
+
+
+class Context:
+    """oz2_context: settings, workspace registration and lock of its own (see include/oz2.h).  The device buffer
+    is torch's; the object keeps it alive as long as the context points at it."""
+
+    def __init__(self):
+        self.handle = ctypes.c_void_p()
+        _check(lib().oz2_context_create(ctypes.byref(self.handle)), "oz2_context_create")
+        self.buf = None
+
+    def set(self, option, value):
+        _check(lib().oz2_context_set(self.handle, int(option), int(value)), "oz2_context_set")
+
+    def get(self, option):
+        v = ctypes.c_int64(0)
+        _check(lib().oz2_context_get(self.handle, int(option), ctypes.byref(v)), "oz2_context_get")
+        return v.value
+
+    def workspace_bytes(self, m, n, k, num_moduli):
+        return int(lib().oz2_context_workspace_bytes(self.handle, m, n, k, num_moduli))
+
+    def allocate_workspace(self, m, n, k, num_moduli, device="cuda:0"):
+        import torch
+        nbytes = self.workspace_bytes(m, n, k, num_moduli)
+        if nbytes == 0:
+            raise Oz2Error("invalid problem for a workspace")
+        self.buf = torch.empty(nbytes + 256, dtype=torch.uint8, device=device)
+        off = (-self.buf.data_ptr()) % 256
+        _check(lib().oz2_context_set_workspace(self.handle, self.buf.data_ptr() + off, nbytes), "oz2_context_set_workspace")
+        return nbytes
+
+    def dgemm(self, transa, transb, m, n, k, alpha, A_ptr, lda, B_ptr, ldb, beta, C_ptr, ldc, num_moduli, stream=None):
+        _check(lib().oz2_context_dgemm(self.handle, transa.encode(), transb.encode(), m, n, k, float(alpha), A_ptr, lda,
+                                       B_ptr, ldb, float(beta), C_ptr, ldc, num_moduli, _stream_ptr(stream)),
+               "oz2_context_dgemm")
+
+    def dsyrk(self, uplo, trans, n, k, alpha, A_ptr, lda, beta, C_ptr, ldc, num_moduli, stream=None):
+        _check(lib().oz2_context_dsyrk(self.handle, uplo.encode(), trans.encode(), n, k, float(alpha), A_ptr, lda,
+                                       float(beta), C_ptr, ldc, num_moduli, _stream_ptr(stream)), "oz2_context_dsyrk")
+
+    def dtrmm(self, side, uplo, transa, diag, m, n, alpha, A_ptr, lda, B_ptr, ldb, num_moduli, stream=None):
+        _check(lib().oz2_context_dtrmm(self.handle, side.encode(), uplo.encode(), transa.encode(), diag.encode(), m, n,
+                                       float(alpha), A_ptr, lda, B_ptr, ldb, num_moduli, _stream_ptr(stream)),
+               "oz2_context_dtrmm")
+
+    def close(self):
+        if self.handle:
+            lib().oz2_context_destroy(self.handle)
+            self.handle = ctypes.c_void_p()
+        self.buf = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
 
 
 class Workspace:

@@ -1,5 +1,6 @@
 // C ABI of liboz2 (see include/oz2.h): argument checks, workspace bookkeeping, stage sequencing.
 #include <mutex>
+#include <new>
 
 #include "../../include/oz2.h"
 #include "oz2_internal.h"
@@ -24,10 +25,18 @@ struct State {
   int plan_rc = 0;
 };
 
+// The context the calling thread works on: the process-wide default one, or, inside an oz2_context_* call, the
+// caller's.  Every entry point below reaches its settings, workspace and plan cache through state().
+thread_local State* tl_state = nullptr;
 State& state() {
   static State s;
-  return s;
+  return tl_state ? *tl_state : s;
 }
+struct UseContext {
+  State* prev;
+  explicit UseContext(oz2_context* ctx) : prev(tl_state) { tl_state = reinterpret_cast<State*>(ctx); }
+  ~UseContext() { tl_state = prev; }
+};
 
 // cached plan for (N, k); caller holds the mutex
 int get_plan(State& s, int N, int64_t k, const Oz2Plan** out) {
@@ -38,6 +47,16 @@ int get_plan(State& s, int N, int64_t k, const Oz2Plan** out) {
   }
   *out = &s.plan;
   return s.plan_rc;
+}
+
+// One-time device set-up of the GEMM kernels, made before any launch under a lock of its own: contexts have
+// separate locks, so two of them may reach their first launch together.
+std::mutex g_setup_mu;
+bool g_setup_done = false;
+bool ensure_setup() {
+  std::lock_guard<std::mutex> lock(g_setup_mu);
+  if (!g_setup_done) g_setup_done = oz2_gemm_setup() == hipSuccess;
+  return g_setup_done;
 }
 
 bool n_ok(int N) { return N >= OZ2_MIN_N && N <= OZ2_MAX_N; }
@@ -75,7 +94,7 @@ int prepare(State& s, const WsRef& w, int64_t m, int64_t n, int64_t k, int N, co
   if (s.shift_mode == OZ2_SHIFT_INT8_PRODUCT && (k + 63) / 64 * 64 >= ((int64_t)1 << 19)) return OZ2_ERR_BUDGET;
   oz2_make_layout(m, n, k, N, s.product_format == OZ2_PRODUCT_INT32 ? 4 : 1, lay);
   if (!w.p || w.bytes < lay->total) return OZ2_ERR_WORKSPACE;
-  return OZ2_OK;
+  return ensure_setup() ? OZ2_OK : OZ2_ERR_HIP;
 }
 
 int prepare(State& s, int64_t m, int64_t n, int64_t k, int N, const Oz2Plan** plan, Oz2Layout* lay) {
@@ -112,7 +131,7 @@ int prepare_general(State& s, const WsRef& w, int64_t m, int64_t n, int64_t k, i
     if (w.p && w.bytes >= sl.total) {
       *lay = sl;
       *strassen = true;
-      return OZ2_OK;
+      return ensure_setup() ? OZ2_OK : OZ2_ERR_HIP;
     }
     if (s.gemm_algorithm == OZ2_GEMM_STRASSEN) return OZ2_ERR_WORKSPACE;
   }
@@ -127,7 +146,7 @@ extern "C" {
 int oz2_init(void) {
   State& s = state();
   std::lock_guard<std::mutex> lock(s.mu);
-  if (oz2_gemm_setup() != hipSuccess) return OZ2_ERR_HIP;
+  if (!ensure_setup()) return OZ2_ERR_HIP;
   char* p;
   size_t bytes;
   return oz2_static_scratch(&p, &bytes) == hipSuccess ? OZ2_OK : OZ2_ERR_HIP;
@@ -582,6 +601,85 @@ int oz2_dgemm(int64_t m, int64_t n, int64_t k, const double* A, int64_t lda, con
 int oz2_dgemm_static(int64_t m, int64_t n, int64_t k, const double* A, int64_t lda, const double* B, int64_t ldb, double* C,
                      int64_t ldc, int num_moduli, void* stream) {
   return dgemm_code(dgemm_ex_impl(true, 'N', 'N', m, n, k, 1.0, A, lda, B, ldb, 0.0, C, ldc, num_moduli, stream));
+}
+
+int oz2_context_create(oz2_context** ctx) {
+  if (!ctx) return -1;
+  State* s = new (std::nothrow) State();
+  if (!s) return OZ2_ERR_HIP;
+  *ctx = reinterpret_cast<oz2_context*>(s);
+  return OZ2_OK;
+}
+
+int oz2_context_destroy(oz2_context* ctx) {
+  if (!ctx) return -1;
+  delete reinterpret_cast<State*>(ctx);
+  return OZ2_OK;
+}
+
+int oz2_context_set_workspace(oz2_context* ctx, void* dev_ptr, size_t bytes) {
+  UseContext use(ctx);
+  return oz2_set_workspace(dev_ptr, bytes);
+}
+
+int oz2_context_set(oz2_context* ctx, int option, int64_t value) {
+  UseContext use(ctx);
+  const bool fits = value >= INT32_MIN && value <= INT32_MAX;
+  int rc;
+  switch (option) {
+    case OZ2_OPT_SHIFT_MODE: rc = fits ? oz2_set_shift_mode((int)value) : -1; break;
+    case OZ2_OPT_PRODUCT_FORMAT: rc = fits ? oz2_set_product_format((int)value) : -1; break;
+    case OZ2_OPT_GEMM_ALGORITHM: rc = fits ? oz2_set_gemm_algorithm((int)value) : -1; break;
+    case OZ2_OPT_KBLOCK: rc = oz2_set_kblock(value); break;
+    case OZ2_OPT_BIT_SPLIT: rc = fits ? oz2_set_bit_split((int)value) : -1; break;
+    case OZ2_OPT_NONFINITE_CHECK: rc = fits ? oz2_set_nonfinite_check((int)value) : -1; break;
+    default: return -2;
+  }
+  return rc == OZ2_OK ? OZ2_OK : -3;
+}
+
+int oz2_context_get(oz2_context* ctx, int option, int64_t* value) {
+  if (!value) return -3;
+  UseContext use(ctx);
+  State& s = state();
+  std::lock_guard<std::mutex> lock(s.mu);
+  switch (option) {
+    case OZ2_OPT_SHIFT_MODE: *value = s.shift_mode; break;
+    case OZ2_OPT_PRODUCT_FORMAT: *value = s.product_format; break;
+    case OZ2_OPT_GEMM_ALGORITHM: *value = s.gemm_algorithm; break;
+    case OZ2_OPT_KBLOCK: *value = s.kblock; break;
+    case OZ2_OPT_BIT_SPLIT: *value = s.bit_split; break;
+    case OZ2_OPT_NONFINITE_CHECK: *value = s.nonfinite_check; break;
+    default: return -2;
+  }
+  return OZ2_OK;
+}
+
+size_t oz2_context_workspace_bytes(oz2_context* ctx, int64_t m, int64_t n, int64_t k, int num_moduli) {
+  UseContext use(ctx);
+  return oz2_workspace_bytes_preferred(m, n, k, num_moduli);
+}
+
+int oz2_context_dgemm(oz2_context* ctx, char transa, char transb, int64_t m, int64_t n, int64_t k, double alpha,
+                      const double* A, int64_t lda, const double* B, int64_t ldb, double beta, double* C, int64_t ldc,
+                      int num_moduli, void* stream) {
+  UseContext use(ctx);
+  const int rc = oz2_dgemm_ex(transa, transb, m, n, k, alpha, A, lda, B, ldb, beta, C, ldc, num_moduli, stream);
+  return rc < 0 ? rc - 1 : rc;  // argument codes count the context as the first argument
+}
+
+int oz2_context_dsyrk(oz2_context* ctx, char uplo, char trans, int64_t n, int64_t k, double alpha, const double* A,
+                      int64_t lda, double beta, double* C, int64_t ldc, int num_moduli, void* stream) {
+  UseContext use(ctx);
+  const int rc = oz2_dsyrk(uplo, trans, n, k, alpha, A, lda, beta, C, ldc, num_moduli, stream);
+  return rc < 0 ? rc - 1 : rc;
+}
+
+int oz2_context_dtrmm(oz2_context* ctx, char side, char uplo, char transa, char diag, int64_t m, int64_t n, double alpha,
+                      const double* A, int64_t lda, double* B, int64_t ldb, int num_moduli, void* stream) {
+  UseContext use(ctx);
+  const int rc = oz2_dtrmm(side, uplo, transa, diag, m, n, alpha, A, lda, B, ldb, num_moduli, stream);
+  return rc < 0 ? rc - 1 : rc;
 }
 
 int oz2_calibrate_mfma(int workgroups, int iters, int random_operands, int* sink, long long* clocks, void* stream) {

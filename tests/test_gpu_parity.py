@@ -304,17 +304,64 @@ def test_full_size_configs_on_sampled_outputs(name, kblock, algorithm, N):
     del ws
 
 
+def test_two_contexts_with_different_settings_on_two_streams():
+    """Two contexts, each with its own workspace and settings (Cauchy-Schwarz shifts with 12 moduli and INT32 product
+    planes in one, the simple bound with 15 moduli and a short k-block in the other), called alternately on two
+    streams so that their kernels may overlap: every result is the oracle's for that context's settings, and the
+    process-wide settings are what they were."""
+    rng = np.random.default_rng(71)
+    m, n, k = 700, 520, 900
+    A = np.asfortranarray((rng.random((m, k)) - 0.5) * np.exp(rng.standard_normal((m, k))))
+    B = np.asfortranarray((rng.random((k, n)) - 0.5) * np.exp(rng.standard_normal((k, n))))
+    dA, dB = _dev(A), _dev(B)
+    ca, cb = oz.Context(), oz.Context()
+    ca.set(oz.OZ2_OPT_SHIFT_MODE, oz.OZ2_SHIFT_CAUCHY_SCHWARZ)
+    ca.set(oz.OZ2_OPT_PRODUCT_FORMAT, oz.OZ2_PRODUCT_INT32)
+    cb.set(oz.OZ2_OPT_KBLOCK, 256)
+    ca.allocate_workspace(m, n, k, 12)
+    cb.allocate_workspace(m, n, k, 15)
+    sa, sb = torch.cuda.Stream(), torch.cuda.Stream()
+    Ca = [torch.full((n, m), float("nan"), dtype=torch.float64, device="cuda").t() for _ in range(3)]
+    Cb = [torch.full((n, m), float("nan"), dtype=torch.float64, device="cuda").t() for _ in range(3)]
+    torch.cuda.synchronize()
+    for r in range(3):
+        print("contexts: round %d" % r, flush=True)
+        ca.dgemm("N", "N", m, n, k, 1.0, dA.data_ptr(), m, dB.data_ptr(), k, 0.0, Ca[r].data_ptr(), m, 12, sa)
+        cb.dgemm("N", "N", m, n, k, 1.0, dA.data_ptr(), m, dB.data_ptr(), k, 0.0, Cb[r].data_ptr(), m, 15, sb)
+    torch.cuda.synchronize()
+    ref_a = orc.dgemm(A, B, 12, mode=1).C
+    ref_b = orc.dgemm(A, B, 15, mode=0).C
+    for r in range(3):
+        assert np.array_equal(Ca[r].cpu().numpy(), ref_a), "context a, call %d" % r
+        assert np.array_equal(Cb[r].cpu().numpy(), ref_b), "context b, call %d" % r
+    assert not np.array_equal(ref_a, ref_b)
+    # the process-wide context still has the defaults and no part in this
+    probe = oz.Context()
+    for opt in (oz.OZ2_OPT_SHIFT_MODE, oz.OZ2_OPT_PRODUCT_FORMAT, oz.OZ2_OPT_KBLOCK):
+        v = __import__("ctypes").c_int64(-1)
+        assert oz.lib().oz2_context_get(None, opt, __import__("ctypes").byref(v)) == 0 and v.value == probe.get(opt)
+    ca.close(), cb.close(), probe.close()
+
+
+_sync_case = {}
+
+
 @pytest.mark.parametrize("spins", [1, 0, 4096])
 def test_round_synchronisation_bound_and_switch(spins):
     """The GEMM's per-die round synchronisation with its wait bound forced down to one poll (so that waits run to
     their bound, the die's counter is pushed past every target and the rest of the launch runs unsynchronised),
-    switched off, and at its default: the residues and C are the oracle's every time.  Inner dimension 6400 puts the
-    launch among those that synchronise (more than 96 k-tiles), 22 planes of 3 x 2 tiles give every workgroup
-    several rounds."""
-    rng = np.random.default_rng(61)
-    m, n, k, N = 700, 500, 6400, 22
-    A = np.asfortranarray((rng.random((m, k)) - 0.5) * np.exp(0.5 * rng.standard_normal((m, k))))
-    B = np.asfortranarray((rng.random((k, n)) - 0.5) * np.exp(0.5 * rng.standard_normal((k, n))))
+    switched off, and at its default: the residues and C are the oracle's every time.  2048 x 1024 x 6400 with 22
+    moduli: 704 tiles for 256 workgroups (two or three tiles each, two synchronised rounds, early arrival), an inner
+    dimension of 100 k-tiles, which puts the launch among those that synchronise; every element of every plane is
+    compared."""
+    m, n, k, N = 2048, 1024, 6400, 22
+    if not _sync_case:
+        rng = np.random.default_rng(61)
+        _sync_case["A"] = np.asfortranarray((rng.random((m, k)) - 0.5) * np.exp(0.5 * rng.standard_normal((m, k))))
+        _sync_case["B"] = np.asfortranarray((rng.random((k, n)) - 0.5) * np.exp(0.5 * rng.standard_normal((k, n))))
+        print("oracle for the round-synchronisation case", flush=True)
+        _sync_case["ref"] = orc.dgemm(_sync_case["A"], _sync_case["B"], N, want=("C", "Cres"))
+    A, B, ref = _sync_case["A"], _sync_case["B"], _sync_case["ref"]
     oz.oz2_set_round_sync(spins)
     try:
         got = run_stages(A, B, N, fmt=1)
@@ -323,7 +370,6 @@ def test_round_synchronisation_bound_and_switch(spins):
         torch.cuda.synchronize()
     finally:
         oz.oz2_set_round_sync(4096)
-    ref = orc.dgemm(A, B, N, want=("C", "Cres"))
     assert np.array_equal(got["Cp"][:, :n, :m].transpose(0, 2, 1), ref.Cres)
     assert np.array_equal(got["C"], ref.C) and np.array_equal(C.cpu().numpy(), ref.C)
     del ws

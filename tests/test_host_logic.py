@@ -100,6 +100,47 @@ def test_dropped_workspace_is_unregistered():
     assert L.oz2_dgemm(32, 32, 32, ctypes.c_void_p(256), 32, ctypes.c_void_p(256), 32, ctypes.c_void_p(256), 32, 8, None) == 1
 
 
+def test_contexts_keep_their_own_settings_and_workspace():
+    """A context is a private copy of the settings and of the workspace registration; the process-wide ones stay
+    as they are.  Host side only: calls stop at the missing workspace before anything is launched."""
+    L = oz.lib()
+    a, b = oz.Context(), oz.Context()
+    assert a.get(oz.OZ2_OPT_SHIFT_MODE) == 0 and a.get(oz.OZ2_OPT_PRODUCT_FORMAT) == oz.OZ2_PRODUCT_RESIDUE_U8
+    assert a.get(oz.OZ2_OPT_KBLOCK) == 65536 and a.get(oz.OZ2_OPT_GEMM_ALGORITHM) == oz.OZ2_GEMM_AUTO
+    a.set(oz.OZ2_OPT_SHIFT_MODE, 2)
+    a.set(oz.OZ2_OPT_KBLOCK, 4096)
+    b.set(oz.OZ2_OPT_BIT_SPLIT, -3)
+    assert (a.get(oz.OZ2_OPT_SHIFT_MODE), b.get(oz.OZ2_OPT_SHIFT_MODE)) == (2, 0)
+    assert (a.get(oz.OZ2_OPT_KBLOCK), b.get(oz.OZ2_OPT_KBLOCK)) == (4096, 65536)
+    assert (a.get(oz.OZ2_OPT_BIT_SPLIT), b.get(oz.OZ2_OPT_BIT_SPLIT)) == (0, -3)
+    # the process-wide context saw none of it
+    assert L.oz2_context_set(None, oz.OZ2_OPT_NONFINITE_CHECK, 1) == 0
+    v = ctypes.c_int64(-1)
+    assert L.oz2_context_get(None, oz.OZ2_OPT_SHIFT_MODE, ctypes.byref(v)) == 0 and v.value == 0
+    assert L.oz2_context_set(a.handle, 99, 0) == -2 and L.oz2_context_set(a.handle, oz.OZ2_OPT_SHIFT_MODE, 7) == -3
+    assert L.oz2_context_set(a.handle, oz.OZ2_OPT_KBLOCK, 1 << 40) == -3 and L.oz2_context_get(a.handle, 0, None) == -3
+    # in mode 2 the inner dimension is limited: a's setting decides for a, not for b
+    p = ctypes.c_void_p(256)
+    args = (b"N", b"N", 4, 4, (1 << 19), 1.0, p, 4, p, 1 << 19, 0.0, p, 4, 26, None)
+    assert L.oz2_context_dgemm(a.handle, *args) == 2          # OZ2_ERR_BUDGET under a's shift mode
+    assert L.oz2_context_dgemm(b.handle, *args) == 1          # b: accepted, stops at the missing workspace
+    # workspaces are per context
+    buf = np.zeros(1 << 20, dtype=np.uint8)
+    base = buf.ctypes.data + (-buf.ctypes.data) % 256
+    assert L.oz2_context_set_workspace(b.handle, ctypes.c_void_p(base), 64) == 0
+    small = (b"N", b"N", 4, 4, 4, 1.0, p, 4, p, 4, 0.0, p, 4, 4, None)
+    assert L.oz2_context_dgemm(b.handle, *small) == 1         # registered but too small
+    assert L.oz2_stage2_gemm(4, 4, 4, 4, None) == 1           # the process-wide context has none at all
+    # argument codes count the context as the first argument
+    assert L.oz2_context_dgemm(a.handle, b"X", b"N", 4, 4, 4, 1.0, p, 4, p, 4, 0.0, p, 4, 4, None) == -2
+    assert L.oz2_context_dgemm(a.handle, b"N", b"N", -1, 4, 4, 1.0, p, 4, p, 4, 0.0, p, 4, 4, None) == -4
+    assert L.oz2_context_dsyrk(a.handle, b"Q", b"N", 4, 4, 1.0, p, 4, 0.0, p, 4, 4, None) == -2
+    assert L.oz2_context_dtrmm(a.handle, b"L", b"L", b"N", b"N", -1, 4, 1.0, p, 4, p, 4, 4, None) == -6
+    assert L.oz2_context_create(None) == -1 and L.oz2_context_destroy(None) == -1
+    a.close()
+    b.close()
+
+
 def test_round_sync_setting_is_validated():
     L = oz.lib()
     assert L.oz2_set_round_sync(-1) == -1 and L.oz2_set_round_sync((1 << 20) + 1) == -1
