@@ -326,6 +326,13 @@ int oz2_set_round_sync(int spins);
  * writes nothing else.  No GPU is touched.  Returns 0 or a negative argument code. */
 int oz2_host_crt_element(int num_moduli, const int32_t* cprod, double* x_out);
 
+/* The same for the route stage 3 takes with UINT8 residue planes and at most 16 moduli, where the accumulation of
+ * line 9 runs on the matrix cores: the weights W_t are brought into the symmetric range modulo M and written in
+ * sixteen balanced base-256 digits, the digit sums sum_t c''_t dig_i,t are what one INT8 MFMA delivers (formed
+ * here by a plain integer loop), and the same exact tail rounds X.  residues: num_moduli bytes, residues[t] in
+ * [0, p_t).  num_moduli <= 16.  Returns 0 or a negative argument code. */
+int oz2_host_crt_element_digits(int num_moduli, const uint8_t* residues, double* x_out);
+
 /* Host-side evaluation of the device routine for lines 2-5 on one element: residues of
  * trunc(a * 2^shift) for all moduli (int8, num_moduli entries).  kappa tells the routine which of its
  * two splitting depths to use, as the kernels do.  No GPU is touched. */

@@ -12,7 +12,7 @@ SYMBOLS = [
     "oz2_set_gemm_algorithm", "oz2_gemm_algorithm_for", "oz2_workspace_bytes_strassen", "oz2_workspace_bytes_preferred",
     "oz2_context_create", "oz2_context_destroy", "oz2_context_set_workspace", "oz2_context_set", "oz2_context_get",
     "oz2_context_workspace_bytes", "oz2_context_dgemm", "oz2_context_dsyrk", "oz2_context_dtrmm",
-    "oz2_set_kblock", "oz2_set_round_sync", "oz2_set_shift_mode", "oz2_set_product_format", "oz2_set_bit_split", "oz2_set_nonfinite_check", "oz2_set_stage_events", "oz2_calibrate_mfma", "oz2_host_crt_element", "oz2_host_residues", "oz2_status_string",
+    "oz2_set_kblock", "oz2_set_round_sync", "oz2_set_shift_mode", "oz2_set_product_format", "oz2_set_bit_split", "oz2_set_nonfinite_check", "oz2_set_stage_events", "oz2_calibrate_mfma", "oz2_host_crt_element", "oz2_host_crt_element_digits", "oz2_host_residues", "oz2_status_string",
 ]
 
 
@@ -73,6 +73,7 @@ def lib():
         L.oz2_set_stage_events.argtypes = [vp]
         L.oz2_calibrate_mfma.argtypes = [ci, ci, ci, vp, vp, vp]
         L.oz2_host_crt_element.argtypes = [ci, vp, vp]
+        L.oz2_host_crt_element_digits.argtypes = [ci, vp, vp]
         L.oz2_host_residues.argtypes = [ci, ci, ctypes.c_double, ci, vp]
         L.oz2_status_string.restype = ctypes.c_char_p
         L.oz2_status_string.argtypes = [ci]
@@ -265,6 +266,13 @@ def host_crt_element(num_moduli, cprod):
     arr = (ctypes.c_int32 * num_moduli)(*[int(c) for c in cprod])
     out = ctypes.c_double(0.0)
     _check(lib().oz2_host_crt_element(num_moduli, arr, ctypes.byref(out)), "oz2_host_crt_element")
+    return out.value
+
+
+def host_crt_element_digits(num_moduli, residues):
+    arr = (ctypes.c_uint8 * num_moduli)(*[int(c) for c in residues])
+    out = ctypes.c_double(0.0)
+    _check(lib().oz2_host_crt_element_digits(num_moduli, arr, ctypes.byref(out)), "oz2_host_crt_element_digits")
     return out.value
 
 

@@ -14,6 +14,14 @@ HIP_FLAGS = [
 ]
 
 
+# Per-file additions.  The CRT kernels use the matrix cores for a few instructions among vector arithmetic on their
+# results: there the MFMA results belong in ordinary vector registers (otherwise every result is copied out of the
+# accumulation registers, and the accumulator start copied in, one instruction per register).
+EXTRA_FLAGS = {
+    "oz2_stage3.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form"],
+}
+
+
 def sources():
     return sorted(glob.glob(os.path.join(CSRC, "*.hip")) + glob.glob(os.path.join(CSRC, "*.cpp")))
 
@@ -25,7 +33,7 @@ def build(verbose=False):
     procs = []
     for src in sources():
         obj = os.path.join(bdir, os.path.basename(src) + ".o")
-        cmd = ["hipcc"] + HIP_FLAGS + ["-c", src, "-o", obj]
+        cmd = ["hipcc"] + HIP_FLAGS + EXTRA_FLAGS.get(os.path.basename(src), []) + ["-c", src, "-o", obj]
         if verbose:
             print(" ".join(cmd))
         procs.append((subprocess.Popen(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT), cmd))

@@ -702,6 +702,18 @@ int oz2_host_crt_element(int num_moduli, const int32_t* cprod, double* x_out) {
   return OZ2_OK;
 }
 
+int oz2_host_crt_element_digits(int num_moduli, const uint8_t* residues, double* x_out) {
+  if (!n_ok(num_moduli) || num_moduli > 16) return -1;
+  if (!residues) return -2;
+  if (!x_out) return -3;
+  Oz2Plan plan;
+  if (oz2_build_plan(num_moduli, 1, &plan) < 0 || !plan.digits.valid) return -1;
+  for (int t = 0; t < num_moduli; ++t)
+    if (residues[t] >= plan.moduli[t]) return -2;
+  *x_out = oz2_host_crt_digits_impl(plan.crt, plan.digits, residues);
+  return OZ2_OK;
+}
+
 int oz2_host_residues(int num_moduli, int kappa, double a, int shift, int8_t* res_out) {
   if (!n_ok(num_moduli)) return -1;
   if (kappa < 1 || kappa > 110) return -2;

@@ -204,6 +204,36 @@ int oz2_build_plan(int N, int64_t k, Oz2Plan* plan) {
     Wide W = Mt;
     wide_mul_small(W, (uint32_t)y);
     for (int l = 0; l < OZ2_MAX_L; ++l) cc.w[t][l] = l < L ? wide_limb(W, OZ2_LIMB_BITS * l) : 0.0;
+    if (N <= 16) {
+      // balanced base-256 digits of the weight brought into (-M/2, M/2]: two's complement on 128 bits (M < 2^128,
+      // |Ws| <= M/2 < 2^127, so the top byte leaves room for the last carry), then digit by digit: a byte of 128
+      // or more becomes byte - 256 and carries one into the next
+      unsigned __int128 w128 = 0, m128 = 0, h128 = 0;
+      for (int i = 3; i >= 0; --i) {
+        w128 = (w128 << 32) | W.d[i];
+        m128 = (m128 << 32) | M.d[i];
+        h128 = (h128 << 32) | half.d[i];
+      }
+      if (w128 > h128) w128 -= m128;  // wraps: the two's complement of the negative value
+      int carry = 0;
+      for (int i = 0; i < 16; ++i) {
+        int b = (int)((w128 >> (8 * i)) & 0xff) + carry;
+        carry = b >= 128 ? 1 : 0;
+        plan->digits.dig[i][t] = (int8_t)(b >= 128 ? b - 256 : b);
+      }
+    }
+  }
+  plan->digits.valid = N <= 16 ? 1 : 0;
+  for (int i = 0; i < 16; ++i) {
+    int sum = 0;
+    for (int t = 0; t < N && N <= 16; ++t) sum += plan->digits.dig[i][t];
+    plan->digits.init[i] = 128 * sum;
+  }
+  for (int l = 0; l < 4; ++l) {
+    double v = 0.0;  // exact: |init| < 2^19, at most eleven digits' worth of them, all far below 2^53 in the limbs in use
+    const int first = 5 * l, last = l + 1 < L ? 5 * l + 4 : 15;
+    for (int i = last; i >= first && l < L; --i) v = v * 256.0 + (double)plan->digits.init[i];
+    plan->digits.sinit[l] = v;
   }
   return plan->kappa < 1 ? 2 : 0;  // 2: the simple bound of Section 3 leaves no bits for this k
 }

@@ -42,6 +42,19 @@ struct Oz2CrtConsts {
   double rinv[OZ2_MAX_L];              // RN(2^(40 l) / M)
 };
 
+// Constants of the matrix-core form of lines 8-9 (at most 16 moduli, M < 2^128): the weights in the symmetric range,
+// Ws_t = W_t or W_t - M with |Ws_t| <= M/2, as sixteen balanced base-256 digits each,
+//   Ws_t = sum_i dig[i][t] 256^i,  dig in [-128, 127],
+// so that one INT8 MFMA forms sum_t (c''_t - 128) dig[i][t] for all sixteen digits of 64 output elements at once;
+// init[i] = 128 sum_t dig[i][t] makes up for the 128: sum_t c''_t dig[i][t] = (MFMA result) + init[i].
+struct Oz2CrtDigits {
+  int valid;            // 1 when the plan has them (N <= 16)
+  int init[16];
+  int8_t dig[16][16];   // [digit][modulus], zero beyond N
+  double sinit[4];      // sum_i init[i] 256^i as 40-bit limbs (digits 5 l .. 5 l + 4 in limb l, the rest in the top one
+                        // of the L in use): added after the MFMA, whose accumulator then starts at the inline zero
+};
+
 struct Oz2Plan {
   int N;
   int kappa;
@@ -51,6 +64,7 @@ struct Oz2Plan {
   int moduli[OZ2_MAX_N];
   Oz2ConvConsts conv;
   Oz2CrtConsts crt;
+  Oz2CrtDigits digits;
 };
 
 // Host constants (oz2_host.cpp).  Returns 0, or -1 for an unsupported N, or 2 when kappa < 1.
@@ -129,5 +143,7 @@ hipError_t oz2_static_scratch(char** ptr, size_t* bytes);
 // Host instantiations of the device math (oz2_stage1.hip / oz2_stage3.hip), for unit tests.
 void oz2_host_residues_impl(const Oz2ConvConsts& c, double a, int shift, int8_t* out);
 double oz2_host_crt_impl(const Oz2CrtConsts& c, const int32_t* cprod);
+// the same element by the digit route of the matrix-core CRT kernel (res: num_moduli residues in [0, p_t))
+double oz2_host_crt_digits_impl(const Oz2CrtConsts& c, const Oz2CrtDigits& d, const uint8_t* res);
 
 #endif

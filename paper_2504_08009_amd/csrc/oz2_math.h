@@ -91,6 +91,25 @@ OZ2_HD void oz2_carry(double* T) {
   }
 }
 
+// ---------------------------------------------------------------------------------------------------
+// Digit route to the same S[l] (matrix-core CRT kernel): D[i] = sum_t c''_t dig[i][t] for the sixteen balanced
+// base-256 digits of the weights in the symmetric range, |D[i]| <= 16 * 255 * 128 < 2^20, so that
+//   Y' = sum_i D[i] 256^i  is congruent to  Y = sum_t c''_t W_t  modulo M,  |Y'| <= 2^11 M.
+// Limb l collects the digits 5 l .. 5 l + 4 (the top limb all that remain): integers below 2^53, exact.  In a
+// top limb with few digits in use the upper D[i] are zero (|Ws| <= M/2 < 2^(40 L - 1)).
+// ---------------------------------------------------------------------------------------------------
+template <int L>
+OZ2_HD void oz2_digits_to_limbs(const int* D, const double* start, double* S) {
+#pragma unroll
+  for (int l = 0; l < L; ++l) {
+    const int first = 5 * l, last = l + 1 < L ? 5 * l + 4 : 15;
+    double v = (double)D[last];
+#pragma unroll
+    for (int i = last - 1; i >= first; --i) v = fma(v, 256.0, (double)D[i]);
+    S[l] = v + start[l];  // the digit sums were formed on c'' - 128: start holds 128 sum_t dig in limb form
+  }
+}
+
 template <int L>
 OZ2_HD double oz2_crt_reduce(const double* S, const Oz2CrtConsts& cc, int* e2) {
   double yest = 0.0;

@@ -131,6 +131,127 @@ __global__ void __launch_bounds__(kThreads) crt_kernel(const void* __restrict__ 
   }
 }
 
+// ---------------------------------------------------------------------------------------------------
+// Lines 8-11 on UINT8 residue planes with the accumulation of line 9 on the matrix cores (at most 16 moduli).
+// Y = sum_t c''_t W_t is a product of the residues (elements x moduli, bytes) with the weights (moduli x digits,
+// bytes once the weights are written in balanced base-256 digits): one v_mfma_i32_32x32x32_i8 forms all sixteen
+// digit sums of 64 output elements.  Operand roles: the 32 "rows" of the first operand run over the result
+// registers and hold the digits, rows 0-15 with their weights on inner positions 0-15 and rows 16-31 with the same
+// weights on inner positions 16-31; a lane of the second operand supplies inner positions 16 (lane / 32) + 0..15 of
+// column lane % 32, i.e. the sixteen residues of ITS OWN element.  Lanes 0-31 therefore multiply against rows 0-15,
+// lanes 32-63 against rows 16-31, and every lane's element gets its sixteen digit sums, half of them in the lane
+// itself and half in the lane 32 away (result register e of lane l is row 8 (e / 4) + 4 (l / 32) + e % 4); eight
+// v_permlane32_swap bring them together.  The residues enter as c'' - 128 (signed bytes); 128 sum_t dig, in limb
+// form, is added when the digits become the 40-bit limbs the exact tail works on.
+// A thread owns four consecutive rows (one 32-bit load per plane, transposed to four 16-byte operands with byte
+// permutes) of kCrtCols consecutive columns, so that the set-up of the constant operand is spread over 64 elements.
+// Against the FP64 accumulation: 120 instead of 156 instructions per element.
+// ---------------------------------------------------------------------------------------------------
+typedef int v4i_t __attribute__((ext_vector_type(4)));
+typedef int v16i_t __attribute__((ext_vector_type(16)));
+constexpr int kCrtCols = 16;
+
+// digit held by row rb (0..15) of a 16-row block: rows 0-3 and 8-11 land in lanes 0-31 (digits 0-7), rows 4-7 and
+// 12-15 in lanes 32-63 (digits 8-15)
+__device__ __forceinline__ constexpr int digit_of_row(int rb) { return ((rb >> 2) & 1) * 8 + (rb >> 3) * 4 + (rb & 3); }
+
+template <int L>
+__global__ void __launch_bounds__(kThreads) crt_mfma_kernel(const uint8_t* __restrict__ planes, int64_t m_pad, int64_t n_pad,
+                                                            const int* __restrict__ sa, const int* __restrict__ sb,
+                                                            double* __restrict__ C, int64_t ldc, int64_t m, int64_t n,
+                                                            const double alpha, const double beta,
+                                                            const unsigned long long* __restrict__ skip_flag,
+                                                            const int triangle, const Oz2CrtConsts cc, const Oz2CrtDigits dg) {
+  if (skip_flag != nullptr && *skip_flag != 0ull) return;
+  const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6, half = lane >> 5;
+  const int64_t i0 = ((int64_t)blockIdx.y * (kThreads / 64) + wv) * 256 + 4 * lane;  // this thread's four rows
+  if (i0 - 4 * lane >= m) return;  // the whole wave (planes are padded to multiples of 256 rows: what it reads exists)
+  const int64_t j0 = (int64_t)blockIdx.x * kCrtCols;
+  const int N = cc.N;
+
+  // first operand: row lane % 32, inner positions 16 (lane / 32) .. + 15; nonzero where the row's block is the half
+  const v16i_t zero16 = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+  v4i_t wop = {0, 0, 0, 0};
+  {
+    const int row = lane & 31;
+    const int mine = (row >> 4) == half ? digit_of_row(row & 15) : -1;
+#pragma unroll
+    for (int d = 0; d < 16; ++d) {
+      const int* w = reinterpret_cast<const int*>(dg.dig[d]);
+      if (mine == d) wop = v4i_t{w[0], w[1], w[2], w[3]};
+    }
+  }
+
+  const size_t plane_words = (size_t)n_pad * m_pad / 4;
+  const unsigned* src = reinterpret_cast<const unsigned*>(planes) + ((size_t)j0 * m_pad + i0) / 4;
+  unsigned nx[16];
+  auto fetch = [&](int jj) {
+#pragma unroll
+    for (int t = 0; t < 16; ++t)
+      nx[t] = (t < N && j0 + jj < n) ? __builtin_nontemporal_load(src + (size_t)t * plane_words + (size_t)jj * (m_pad / 4)) : 0x80808080u;
+  };
+  fetch(0);
+  for (int jj = 0; jj < kCrtCols; ++jj) {
+    const int64_t j = j0 + jj;
+    if (j >= n) break;  // uniform
+    unsigned x[16];
+#pragma unroll
+    for (int t = 0; t < 16; ++t) x[t] = nx[t] ^ 0x80808080u;  // c'' - 128 as signed bytes
+    if (jj + 1 < kCrtCols) fetch(jj + 1);
+    // 16 words [modulus](4 rows) -> 4 operands [row](16 moduli)
+    v4i_t y[4];
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+      const unsigned a = __builtin_amdgcn_perm(x[4 * g + 1], x[4 * g], 0x05010400u);  // x0.b0 x1.b0 x0.b1 x1.b1
+      const unsigned b = __builtin_amdgcn_perm(x[4 * g + 1], x[4 * g], 0x07030602u);  // x0.b2 x1.b2 x0.b3 x1.b3
+      const unsigned c = __builtin_amdgcn_perm(x[4 * g + 3], x[4 * g + 2], 0x05010400u);
+      const unsigned d = __builtin_amdgcn_perm(x[4 * g + 3], x[4 * g + 2], 0x07030602u);
+      y[0][g] = (int)__builtin_amdgcn_perm(c, a, 0x05040100u);  // a.lo16 c.lo16
+      y[1][g] = (int)__builtin_amdgcn_perm(c, a, 0x07060302u);  // a.hi16 c.hi16
+      y[2][g] = (int)__builtin_amdgcn_perm(d, b, 0x05040100u);
+      y[3][g] = (int)__builtin_amdgcn_perm(d, b, 0x07060302u);
+    }
+    const int sbj = sb[j];
+    double out[4];
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      const v16i_t acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(wop, y[r], zero16, 0, 0, 0);
+      int D[16];
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        // lanes 0-31 keep register e (digit e) and get the other half's register e (digit 8 + e) in the place of
+        // register 8 + e; lanes 32-63 the other way round
+        const auto sw = __builtin_amdgcn_permlane32_swap((unsigned)acc[e], (unsigned)acc[8 + e], false, false);
+        D[e] = (int)sw[0];
+        D[8 + e] = (int)sw[1];
+      }
+      double S[L];
+      oz2_digits_to_limbs<L>(D, dg.sinit, S);
+      int e2;
+      const double xv = oz2_crt_reduce<L>(S, cc, &e2);
+      out[r] = ldexp(xv, e2 - sa[i0 + r] - sbj);
+    }
+    double* dst = C + i0 + j * ldc;
+    if (alpha != 1.0 || beta != 0.0) {
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        const bool mine = i0 + r < m && !(triangle == 1 && i0 + r < j) && !(triangle == 2 && i0 + r > j);
+        const double tt = (beta == 0.0 || !mine) ? 0.0 : beta * dst[r];
+        out[r] = fma(alpha, out[r], tt);
+      }
+    }
+    const bool whole = triangle == 0 || (triangle == 1 && i0 >= j) || (triangle == 2 && i0 + 3 <= j);
+    if (whole && i0 + 4 <= m && ((reinterpret_cast<uintptr_t>(dst) & 15) == 0)) {
+      *reinterpret_cast<double2*>(dst) = make_double2(out[0], out[1]);
+      *reinterpret_cast<double2*>(dst + 2) = make_double2(out[2], out[3]);
+    } else {
+#pragma unroll
+      for (int r = 0; r < 4; ++r)
+        if (i0 + r < m && !(triangle == 1 && i0 + r < j) && !(triangle == 2 && i0 + r > j)) dst[r] = out[r];
+    }
+  }
+}
+
 // C := beta * C (zero without reading C when beta is zero): the k == 0 and alpha == 0 cases
 __global__ void __launch_bounds__(kThreads) scale_c_kernel(double* __restrict__ C, int64_t ldc, int64_t m, double beta,
                                                            int triangle) {
@@ -166,6 +287,27 @@ hipError_t oz2_launch_stage3(int64_t m, int64_t n, double alpha, double beta, do
   const int* sb = triangle ? sa : reinterpret_cast<const int*>(ws + lay.off_sb);  // symmetric: columns are A's rows
   const int64_t per_block = (int64_t)kThreads * (residue_u8 ? PlaneLoad<true>::R : PlaneLoad<false>::R);
   dim3 grid((unsigned)n, (unsigned)((m + per_block - 1) / per_block));
+  // (from 2^25 elements on: below, a thread's 64 elements leave too few threads for the chip and the other kernel wins)
+  if (residue_u8 && plan.digits.valid && m * n >= ((int64_t)1 << 25)) {
+    // at most 16 moduli: the accumulation of line 9 on the matrix cores
+    const uint8_t* p8 = static_cast<const uint8_t*>(cplanes);
+    dim3 g2((unsigned)((n + kCrtCols - 1) / kCrtCols), (unsigned)((m + 1023) / 1024));
+    switch (plan.crt.L) {
+#define OZ2_CASE(LL)                                                                                                  \
+  case LL:                                                                                                            \
+    hipLaunchKernelGGL((crt_mfma_kernel<LL>), g2, dim3(kThreads), 0, st, p8, lay.m_pad, lay.n_pad, sa, sb, C, ldc, m, \
+                       n, alpha, beta, skip, triangle, plan.crt, plan.digits);                                         \
+    break;
+      OZ2_CASE(1)
+      OZ2_CASE(2)
+      OZ2_CASE(3)
+      OZ2_CASE(4)
+#undef OZ2_CASE
+      default:
+        return hipErrorInvalidValue;
+    }
+    return hipGetLastError();
+  }
   switch (plan.crt.L) {
 #define OZ2_CASE(LL)                                                                                              \
   case LL:                                                                                                        \
@@ -192,6 +334,30 @@ hipError_t oz2_launch_scale_c(int64_t m, int64_t n, double beta, double* C, int6
   dim3 grid((unsigned)n, (unsigned)((m + kThreads - 1) / kThreads));
   hipLaunchKernelGGL(scale_c_kernel, grid, dim3(kThreads), 0, st, C, ldc, m, beta, triangle);
   return hipGetLastError();
+}
+
+template <int L>
+double host_crt_digits(const Oz2CrtConsts& cc, const Oz2CrtDigits& dg, const uint8_t* res) {
+  int D[16];
+  for (int i = 0; i < 16; ++i) {
+    int acc = 0;  // what the matrix core computes: signed bytes c'' - 128 against the digits
+    for (int t = 0; t < cc.N; ++t) acc += ((int)res[t] - 128) * (int)dg.dig[i][t];
+    D[i] = acc;
+  }
+  double S[L];
+  oz2_digits_to_limbs<L>(D, dg.sinit, S);
+  int e2;
+  double x = oz2_crt_reduce<L>(S, cc, &e2);
+  return ldexp(x, e2);
+}
+
+double oz2_host_crt_digits_impl(const Oz2CrtConsts& cc, const Oz2CrtDigits& dg, const uint8_t* res) {
+  switch (cc.L) {
+    case 1: return host_crt_digits<1>(cc, dg, res);
+    case 2: return host_crt_digits<2>(cc, dg, res);
+    case 3: return host_crt_digits<3>(cc, dg, res);
+    default: return host_crt_digits<4>(cc, dg, res);
+  }
 }
 
 double oz2_host_crt_impl(const Oz2CrtConsts& cc, const int32_t* cprod) {

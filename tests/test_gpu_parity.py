@@ -375,6 +375,36 @@ def test_round_synchronisation_bound_and_switch(spins):
     del ws
 
 
+@pytest.mark.parametrize("N,alpha,beta", [(16, 1.0, 0.0), (13, 1.0, 0.0), (9, 1.0, 0.0), (4, 1.0, 0.0), (16, -0.75, 2.0)])
+def test_matrix_core_crt_every_element_ragged(N, alpha, beta):
+    """Alg. 1 line 9 on the matrix cores (the kernel taken from 2^25 elements of C on, classical form, up to 16
+    moduli): a ragged shape just above that size with a short inner dimension, EVERY element of C compared with the
+    oracle, for moduli counts whose product needs one, two, three and four 40-bit limbs, and once as the update
+    with alpha and beta."""
+    m, n, k, phi = 5801, 5791, 40, 1.0
+    assert m * n >= 1 << 25
+    A = inputs.block(77, 0, m, k, phi)
+    B = inputs.block(77, 1, k, n, phi)
+    C0 = inputs.block(77, 2, m, n, 0.5)
+    dA = torch.from_numpy(A.T).cuda().t()
+    dB = torch.from_numpy(B.T).cuda().t()
+    dC = torch.from_numpy(C0.T).cuda().t()
+    oz.oz2_set_gemm_algorithm(oz.OZ2_GEMM_CLASSICAL)
+    try:
+        ws = oz.Workspace(m, n, k, N)
+        print("matrix-core CRT, every element of %d x %d, N=%d alpha=%g beta=%g" % (m, n, N, alpha, beta), flush=True)
+        oz.oz2_dgemm_ex("N", "N", m, n, k, alpha, dA.data_ptr(), m, dB.data_ptr(), k, beta, dC.data_ptr(), m, N)
+        torch.cuda.synchronize()
+    finally:
+        oz.oz2_set_gemm_algorithm(oz.OZ2_GEMM_AUTO)
+    got = dC.cpu().numpy()
+    del ws, dA, dB, dC
+    ref = orc.dgemm_ex("N", "N", alpha, A, B, beta, C0, N)
+    bad = np.argwhere(got != ref)
+    assert len(bad) == 0, "%d elements differ from the oracle, first at %s" % (len(bad), bad[:5].tolist())
+    assert not np.isnan(got).any()
+
+
 _c3_oracle = {}
 
 

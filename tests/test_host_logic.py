@@ -281,6 +281,26 @@ def test_host_crt_element_is_correctly_rounded(N):
         assert got == float(x), (N, x, got, float(x))
 
 
+@pytest.mark.parametrize("N", [2, 3, 5, 8, 11, 13, 14, 15, 16])
+def test_host_crt_element_by_digits_is_correctly_rounded(N):
+    """The route of the matrix-core CRT kernel (weights in the symmetric range as balanced base-256 digits, digit
+    sums, the same exact tail) on the same random and adversarial values of X, and on all-equal residues at both
+    ends of their range, where the digit sums are largest."""
+    rng = random.Random(177 + N)
+    mods, M, xs = _crt_cases(N, rng)
+    for x in xs:
+        got = oz.host_crt_element_digits(N, [x % p for p in mods])
+        assert got == float(x), (N, x, got, float(x))
+    _, W = orc.crt_constants(N)
+    half = M // 2
+    for res in ([p - 1 for p in mods], [0] * N, [p - 1 if t % 2 else 0 for t, p in enumerate(mods)],
+                [0 if t % 2 else p - 1 for t, p in enumerate(mods)], [1] * N):
+        y = sum(r * w for r, w in zip(res, W)) % M
+        y = y - M if y >= M - half else y
+        assert oz.host_crt_element_digits(N, res) == float(y)
+    assert oz.lib().oz2_host_crt_element_digits(17, None, None) == -1
+
+
 def test_host_crt_extreme_int32_products():
     # products at the INT32 limits and negative values: floor-mod must stay in [0, p)
     N = 16
