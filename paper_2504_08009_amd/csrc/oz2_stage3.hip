@@ -287,8 +287,8 @@ hipError_t oz2_launch_stage3(int64_t m, int64_t n, double alpha, double beta, do
   const int* sb = triangle ? sa : reinterpret_cast<const int*>(ws + lay.off_sb);  // symmetric: columns are A's rows
   const int64_t per_block = (int64_t)kThreads * (residue_u8 ? PlaneLoad<true>::R : PlaneLoad<false>::R);
   dim3 grid((unsigned)n, (unsigned)((m + per_block - 1) / per_block));
-  // (from 2^25 elements on: below, a thread's 64 elements leave too few threads for the chip and the other kernel wins)
-  if (residue_u8 && plan.digits.valid && m * n >= ((int64_t)1 << 25)) {
+  // (from 2^24 elements on: below, a thread's 64 elements leave too few threads for the chip and the other kernel wins)
+  if (residue_u8 && plan.digits.valid && m * n >= ((int64_t)1 << 24)) {
     // at most 16 moduli: the accumulation of line 9 on the matrix cores
     const uint8_t* p8 = static_cast<const uint8_t*>(cplanes);
     dim3 g2((unsigned)((n + kCrtCols - 1) / kCrtCols), (unsigned)((m + 1023) / 1024));

@@ -375,12 +375,13 @@ def test_round_synchronisation_bound_and_switch(spins):
     del ws
 
 
-@pytest.mark.parametrize("N,alpha,beta", [(16, 1.0, 0.0), (13, 1.0, 0.0), (9, 1.0, 0.0), (4, 1.0, 0.0), (16, -0.75, 2.0)])
+@pytest.mark.parametrize("N,alpha,beta", [(16, 1.0, 0.0), (13, 1.0, 0.0), (9, 1.0, 0.0), (4, 1.0, 0.0), (16, -0.75, 2.0),
+                                          (17, 1.0, 0.0)])
 def test_matrix_core_crt_every_element_ragged(N, alpha, beta):
-    """Alg. 1 line 9 on the matrix cores (the kernel taken from 2^25 elements of C on, classical form, up to 16
-    moduli): a ragged shape just above that size with a short inner dimension, EVERY element of C compared with the
-    oracle, for moduli counts whose product needs one, two, three and four 40-bit limbs, and once as the update
-    with alpha and beta."""
+    """Alg. 1 line 9 on the matrix cores (the kernel taken from 2^24 elements of C on, classical form, up to 16
+    moduli): a ragged shape above that size with a short inner dimension, EVERY element of C compared with the
+    oracle, for moduli counts whose product needs one, two, three and four 40-bit limbs, as the update with alpha
+    and beta, and with 17 moduli (the first count that stays with the FP64 accumulation at this size)."""
     m, n, k, phi = 5801, 5791, 40, 1.0
     assert m * n >= 1 << 25
     A = inputs.block(77, 0, m, k, phi)
