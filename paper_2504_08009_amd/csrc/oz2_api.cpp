@@ -447,6 +447,15 @@ int dgemm_ex_impl(bool static_ws, char transa, char transb, int64_t m, int64_t n
             hipSuccess ||
         !mark(2))
       return OZ2_ERR_HIP;
+    // up to 2^18 elements of C the blocks of the fallback ride in the launch of stage 3: one launch less where
+    // launches are what the call costs (from 1024 x 1024 on the wider kernel's lower occupancy costs as much)
+    if (s.nonfinite_check && s.product_format == OZ2_PRODUCT_RESIDUE_U8 && m * n <= ((int64_t)1 << 18)) {
+      if (oz2_launch_stage3_or_fallback(ta, tb, m, n, k, alpha, A, lda, B, ldb, beta, C, ldc, *plan, lay, ws, st) !=
+              hipSuccess ||
+          !mark(3))
+        return OZ2_ERR_HIP;
+      return OZ2_OK;
+    }
     if (oz2_launch_stage3(m, n, alpha, beta, C, ldc, *plan, lay, ws, s.product_format, s.nonfinite_check, 0, st) !=
             hipSuccess ||
         !mark(3))

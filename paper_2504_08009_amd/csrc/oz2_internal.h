@@ -123,6 +123,11 @@ hipError_t oz2_launch_bound_gemm(const Oz2Layout& lay, char* ws, bool symmetric,
 hipError_t oz2_launch_stage3(int64_t m, int64_t n, double alpha, double beta, double* C, int64_t ldc,
                              const Oz2Plan& plan, const Oz2Layout& lay, char* ws, int residue_u8, int check_flag,
                              int triangle, hipStream_t st);
+// Stage 3 on UINT8 residue planes of a general product and, in the same launch, the blocks of the FP64 fallback
+// below: stage 1's flag decides on the device which of the two sets of blocks forms C.  For small problems.
+hipError_t oz2_launch_stage3_or_fallback(int transa, int transb, int64_t m, int64_t n, int64_t k, double alpha,
+                                         const double* A, int64_t lda, const double* B, int64_t ldb, double beta, double* C,
+                                         int64_t ldc, const Oz2Plan& plan, const Oz2Layout& lay, char* ws, hipStream_t st);
 // C := alpha * op(A) * op(B) + beta * C in plain FP64, only if *flag != 0 (checked on the device)
 // tri_a / tri_b: triangular structure of the stored A / B (0 = full).  C must not overlap A or B.
 hipError_t oz2_launch_fallback(const unsigned long long* flag, int transa, int transb, int64_t m, int64_t n, int64_t k,

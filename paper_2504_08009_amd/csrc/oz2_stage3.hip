@@ -4,11 +4,13 @@
 //   scaling by 2^-(sa_i + sb_j) (line 11).
 // 4N (INT32 planes) or N (UINT8 residue planes, line 7 already taken by the GEMM epilogue) bytes read and 8
 // written per element: bound by HBM traffic with INT32 planes, by FP64 instruction issue with UINT8 planes.
+#include "oz2_fallback_tile.h"
 #include "oz2_math.h"
 
 namespace {
 
 constexpr int kThreads = 256;
+static_assert(kThreads == kFallbackThreads, "the small-problem kernel runs both bodies with one block size");
 
 // One plane's values for R consecutive rows: INT32 products (16-byte loads, R = 4) or UINT8 residues that
 // the GEMM epilogue already reduced (8-byte loads, R = 8).
@@ -38,21 +40,16 @@ struct PlaneLoad<true> {
   }
 };
 
-// One thread: R consecutive rows i of one column j.
+// One thread: R consecutive rows i of one column j (chunk: which kThreads * R rows of the column the block takes).
 template <int L, bool U8>
-__global__ void __launch_bounds__(kThreads) crt_kernel(const void* __restrict__ cplanes, int64_t m_pad, int64_t n_pad,
-                                                       const int* __restrict__ sa, const int* __restrict__ sb,
-                                                       double* __restrict__ C, int64_t ldc, int64_t m, int64_t n,
-                                                       const double alpha, const double beta,
-                                                       const unsigned long long* __restrict__ skip_flag,
-                                                       const int triangle, const Oz2CrtConsts cc) {
-  // a non-finite input was found in stage 1: C is left to the FP64 fallback (uniform over the grid)
-  if (skip_flag != nullptr && *skip_flag != 0ull) return;
+__device__ __forceinline__ void crt_rows(const void* __restrict__ cplanes, int64_t m_pad, int64_t n_pad,
+                                         const int* __restrict__ sa, const int* __restrict__ sb, double* __restrict__ C,
+                                         int64_t ldc, int64_t m, int64_t n, const double alpha, const double beta,
+                                         const int triangle, const Oz2CrtConsts& cc, const int64_t j, const int64_t chunk) {
   typedef PlaneLoad<U8> PL;
   typedef typename PL::Raw Raw;
   constexpr int R = PL::R;
-  const int64_t j = blockIdx.x;
-  const int64_t i0 = ((int64_t)blockIdx.y * kThreads + threadIdx.x) * R;
+  const int64_t i0 = (chunk * kThreads + threadIdx.x) * R;
   if (i0 >= m) return;
   // symmetric product: only the lower (1: i >= j) or upper (2: i <= j) triangle of C exists and is written
   if ((triangle == 1 && i0 + R - 1 < j) || (triangle == 2 && i0 > j)) return;
@@ -128,6 +125,39 @@ __global__ void __launch_bounds__(kThreads) crt_kernel(const void* __restrict__ 
 #pragma unroll
     for (int r = 0; r < R; ++r)
       if (i0 + r < m && !(triangle == 1 && i0 + r < j) && !(triangle == 2 && i0 + r > j)) dst[r] = out[r];
+  }
+}
+
+template <int L, bool U8>
+__global__ void __launch_bounds__(kThreads) crt_kernel(const void* __restrict__ cplanes, int64_t m_pad, int64_t n_pad,
+                                                       const int* __restrict__ sa, const int* __restrict__ sb,
+                                                       double* __restrict__ C, int64_t ldc, int64_t m, int64_t n,
+                                                       const double alpha, const double beta,
+                                                       const unsigned long long* __restrict__ skip_flag,
+                                                       const int triangle, const Oz2CrtConsts cc) {
+  // a non-finite input was found in stage 1: C is left to the FP64 fallback (uniform over the grid)
+  if (skip_flag != nullptr && *skip_flag != 0ull) return;
+  crt_rows<L, U8>(cplanes, m_pad, n_pad, sa, sb, C, ldc, m, n, alpha, beta, triangle, cc, blockIdx.x, blockIdx.y);
+}
+
+// Small problems, where every launch counts: the blocks of the FP64 fallback ride in the same launch.  Rows of
+// blocks below crt_chunks are the kernel above; the rows after them are the fallback's tiles, numbered along x
+// first.  Which of the two sets works is decided by the flag of stage 1, the other returns at once.
+template <int L>
+__global__ void __launch_bounds__(kThreads, 2) crt_or_fallback_kernel(const void* __restrict__ cplanes, int64_t m_pad,
+                                                                   int64_t n_pad, const int* __restrict__ sa,
+                                                                   const int* __restrict__ sb,
+                                                                   const unsigned long long* __restrict__ flag,
+                                                                   const unsigned crt_chunks, const int64_t tiles,
+                                                                   const Oz2FallbackArgs f, const Oz2CrtConsts cc) {
+  const bool nonfinite = *flag != 0ull;
+  if (blockIdx.y < crt_chunks) {
+    if (nonfinite) return;
+    crt_rows<L, true>(cplanes, m_pad, n_pad, sa, sb, f.C, f.ldc, f.m, f.n, f.alpha, f.beta, 0, cc, blockIdx.x, blockIdx.y);
+  } else {
+    const int64_t tile = (int64_t)(blockIdx.y - crt_chunks) * gridDim.x + blockIdx.x;
+    if (!nonfinite || tile >= tiles) return;
+    oz2_fallback_tile(f, tile);
   }
 }
 
@@ -317,6 +347,39 @@ hipError_t oz2_launch_stage3(int64_t m, int64_t n, double alpha, double beta, do
     else                                                                                                          \
       hipLaunchKernelGGL((crt_kernel<LL, false>), grid, dim3(kThreads), 0, st, cplanes, lay.m_pad, lay.n_pad, sa, \
                          sb, C, ldc, m, n, alpha, beta, skip, triangle, plan.crt);                                \
+    break;
+    OZ2_CASE(1)
+    OZ2_CASE(2)
+    OZ2_CASE(3)
+    OZ2_CASE(4)
+    OZ2_CASE(5)
+#undef OZ2_CASE
+    default:
+      return hipErrorInvalidValue;
+  }
+  return hipGetLastError();
+}
+
+// Stage 3 on UINT8 residue planes and the FP64 fallback in one launch (general product, full C).
+hipError_t oz2_launch_stage3_or_fallback(int transa, int transb, int64_t m, int64_t n, int64_t k, double alpha,
+                                         const double* A, int64_t lda, const double* B, int64_t ldb, double beta, double* C,
+                                         int64_t ldc, const Oz2Plan& plan, const Oz2Layout& lay, char* ws, hipStream_t st) {
+  const void* cplanes = ws + lay.off_c;
+  const unsigned long long* flag = reinterpret_cast<const unsigned long long*>(ws + lay.off_flags);
+  const int* sa = reinterpret_cast<const int*>(ws + lay.off_sa);
+  const int* sb = reinterpret_cast<const int*>(ws + lay.off_sb);
+  const int64_t per_block = (int64_t)kThreads * PlaneLoad<true>::R;
+  const int64_t chunks = (m + per_block - 1) / per_block;
+  const int64_t tiles_m = (m + kFallbackTile - 1) / kFallbackTile, tiles_n = (n + kFallbackTile - 1) / kFallbackTile;
+  const int64_t tiles = tiles_m * tiles_n, tile_rows = (tiles + n - 1) / n;
+  if (chunks + tile_rows > 65535) return hipErrorInvalidValue;
+  const Oz2FallbackArgs f = {transa, transb, m, n, k, alpha, A, lda, B, ldb, beta, C, ldc, tiles_m, 0, 0, 0};
+  dim3 grid((unsigned)n, (unsigned)(chunks + tile_rows));
+  switch (plan.crt.L) {
+#define OZ2_CASE(LL)                                                                                                 \
+  case LL:                                                                                                           \
+    hipLaunchKernelGGL((crt_or_fallback_kernel<LL>), grid, dim3(kThreads), 0, st, cplanes, lay.m_pad, lay.n_pad, sa, \
+                       sb, flag, (unsigned)chunks, tiles, f, plan.crt);                                              \
     break;
     OZ2_CASE(1)
     OZ2_CASE(2)

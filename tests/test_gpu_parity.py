@@ -625,8 +625,15 @@ def _flag(ws, m, n, k, N):
 @pytest.mark.parametrize("where", ["A", "B"])
 @pytest.mark.parametrize("mode", [0, 1, 2])
 def test_nonfinite_inputs_fall_back_to_fp64(ta, tb, where, mode):
+    # two sizes of C: up to 2^18 elements the blocks of the fallback ride in the launch of stage 3, above that
+    # the fallback is a launch of its own
+    for m, n in ((300, 200), (700, 600)):
+        _nonfinite_case(ta, tb, where, mode, m, n)
+
+
+def _nonfinite_case(ta, tb, where, mode, m, n):
     rng = np.random.default_rng(21)
-    m, n, k, N = 300, 200, 150, 12
+    k, N = 150, 12
     opA = (rng.random((m, k)) - 0.5) * np.exp(rng.standard_normal((m, k)))
     opB = (rng.random((k, n)) - 0.5) * np.exp(rng.standard_normal((k, n)))
     X = opA if where == "A" else opB
