@@ -304,6 +304,42 @@ def test_full_size_configs_on_sampled_outputs(name, kblock, algorithm, N):
     del ws
 
 
+@pytest.mark.parametrize("N,algorithm", [(8, 0), (17, 0), (8, 1)])
+def test_more_than_2_to_the_32_elements_of_c(N, algorithm):
+    """A product whose C (and, in the classical form, every residue plane) has more than 2^32 elements, so that an
+    element index does not fit 32 bits: 66000 x 65600 with a short inner dimension, 8 moduli (matrix-core CRT
+    kernel) and 17 (FP64 accumulation) in the classical form, 8 moduli with the Strassen form forced (56 planes of
+    2^30 elements).  Every element is written (C starts as NaN), and a sample of rows and columns including the last
+    ones is compared with the oracle."""
+    m, n, k, phi = 66000, 65600, 64 if algorithm == 0 else 128, 0.5
+    assert m * n > 1 << 32
+    A = inputs.block(91, 0, m, k, phi)
+    B = inputs.block(91, 1, k, n, phi)
+    rng = np.random.default_rng(5)
+    rows = np.unique(np.concatenate([[0, 255, 256, 65535, 65536, m - 1], rng.choice(m, 42, replace=False)]))
+    cols = np.unique(np.concatenate([[0, 255, 256, 65535, 65536, n - 1], rng.choice(n, 42, replace=False)]))
+    dA = torch.from_numpy(A.T).cuda().t()
+    dB = torch.from_numpy(B.T).cuda().t()
+    dC = torch.full((n, m), float("nan"), dtype=torch.float64, device="cuda").t()
+    oz.oz2_set_gemm_algorithm(algorithm)
+    try:
+        ws = oz.Workspace(m, n, k, N, product_format=oz.OZ2_PRODUCT_RESIDUE_U8)   # 8, 17 or 14 bytes per element of C
+        assert (oz.oz2_gemm_algorithm_for(m, n, k, N) == oz.OZ2_GEMM_STRASSEN) == (algorithm == 1)
+        print("C of %d x %d = %.2f * 2^32 elements, N=%d, form %d" % (m, n, m * n / 2.0**32, N, algorithm), flush=True)
+        oz.oz2_dgemm(m, n, k, dA.data_ptr(), m, dB.data_ptr(), k, dC.data_ptr(), m, N)
+        torch.cuda.synchronize()
+    finally:
+        oz.oz2_set_gemm_algorithm(oz.OZ2_GEMM_AUTO)
+    del ws
+    # column by column blocks, to keep the temporaries of the check small
+    for j0 in range(0, n, 8192):
+        assert not bool(torch.isnan(dC[:, j0:j0 + 8192]).any()), j0
+    got = dC[torch.from_numpy(rows).cuda()][:, torch.from_numpy(cols).cuda()].cpu().numpy()
+    del dC
+    ref = orc.dgemm(np.asfortranarray(A[rows, :]), np.asfortranarray(B[:, cols]), N).C
+    assert np.array_equal(got, ref)
+
+
 def test_two_contexts_with_different_settings_on_two_streams():
     """Two contexts, each with its own workspace and settings (Cauchy-Schwarz shifts with 12 moduli and INT32 product
     planes in one, the simple bound with 15 moduli and a short k-block in the other), called alternately on two
