@@ -340,6 +340,39 @@ def test_more_than_2_to_the_32_elements_of_c(N, algorithm):
     assert np.array_equal(got, ref)
 
 
+def test_operand_planes_beyond_2_to_the_32_bytes():
+    """An operand whose every residue plane is larger than 2^32 bytes (A: 66000 x 66000, 35 GB of FP64), so that a
+    byte offset inside one plane does not fit 32 bits, against a narrow B.  A is drawn on the device with torch's
+    seeded generator (on the host the 4.4e9 values would take minutes), the sampled rows are copied back for the
+    oracle; all columns of those rows are compared."""
+    m, k, n, N, phi = 66000, 66000, 192, 4, 0.5
+    assert m * k > 1 << 32
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(20250408)
+    dAt = torch.empty((k, m), dtype=torch.float64, device="cuda")   # column-major m x k
+    for c0 in range(0, k, 2048):
+        c1 = min(k, c0 + 2048)
+        u = torch.rand((c1 - c0, m), dtype=torch.float64, device="cuda", generator=gen)
+        z = torch.randn((c1 - c0, m), dtype=torch.float64, device="cuda", generator=gen)
+        dAt[c0:c1] = (u - 0.5) * torch.exp(phi * z)
+        del u, z
+    B = inputs.block(92, 1, k, n, phi)
+    dB = torch.from_numpy(B.T).cuda().t()
+    dC = torch.full((n, m), float("nan"), dtype=torch.float64, device="cuda").t()
+    rng = np.random.default_rng(6)
+    rows = np.unique(np.concatenate([[0, 255, 256, 65535, 65536, 65792, m - 1], rng.choice(m, 25, replace=False)]))
+    Asub = np.asfortranarray(dAt[:, torch.from_numpy(rows).cuda()].t().cpu().numpy())
+    ws = oz.Workspace(m, n, k, N, product_format=oz.OZ2_PRODUCT_RESIDUE_U8)
+    print("A planes of %.2f * 2^32 bytes each" % (m * k / 2.0**32), flush=True)
+    oz.oz2_dgemm(m, n, k, dAt.data_ptr(), m, dB.data_ptr(), k, dC.data_ptr(), m, N)
+    torch.cuda.synchronize()
+    del ws, dAt
+    assert not bool(torch.isnan(dC).any())
+    got = dC[torch.from_numpy(rows).cuda()].cpu().numpy()
+    ref = orc.dgemm(Asub, B, N).C
+    assert np.array_equal(got, ref)
+
+
 def test_two_contexts_with_different_settings_on_two_streams():
     """Two contexts, each with its own workspace and settings (Cauchy-Schwarz shifts with 12 moduli and INT32 product
     planes in one, the simple bound with 15 moduli and a short k-block in the other), called alternately on two
