@@ -752,6 +752,41 @@ def _nonfinite_case(ta, tb, where, mode, m, n):
     del ws
 
 
+@pytest.mark.parametrize("m,n,k", [(1, 5000, 7), (5000, 1, 7), (1, 1, 1), (129, 2031, 3), (262144, 1, 2)])
+def test_nonfinite_fallback_on_skinny_shapes(m, n, k):
+    """The fallback's tiles ride in the launch of stage 3 for small C: shapes where its tile grid and the CRT grid
+    have nothing in common (one row, one column, one element), an infinity in A and a NaN in B."""
+    rng = np.random.default_rng(m + 3 * n)
+    A = np.asfortranarray(rng.standard_normal((m, k)))
+    B = np.asfortranarray(rng.standard_normal((k, n)))
+    A[m - 1, k - 1] = np.inf
+    B[0, n // 2] = np.nan
+    N = 10
+    dA, dB = _dev(A), _dev(B)
+    dC = torch.full((n, m), 7.0, dtype=torch.float64, device="cuda").t()
+    ws = oz.Workspace(m, n, k, N)
+    oz.oz2_dgemm(m, n, k, dA.data_ptr(), m, dB.data_ptr(), k, dC.data_ptr(), m, N)
+    torch.cuda.synchronize()
+    assert _flag(ws, m, n, k, N) == 1
+    got = dC.cpu().numpy()
+    with np.errstate(invalid="ignore"):
+        ref = A @ B
+    assert np.array_equal(np.isnan(got), np.isnan(ref))
+    inf = np.isinf(ref)
+    assert np.array_equal(np.isinf(got), inf) and np.array_equal(got[inf], ref[inf])
+    fin = np.isfinite(ref)
+    assert np.allclose(got[fin], ref[fin], rtol=1e-13, atol=1e-13)
+    # and finite again: the emulation, bit for bit
+    A[m - 1, k - 1] = 1.0
+    B[0, n // 2] = -1.0
+    dA, dB = _dev(A), _dev(B)
+    oz.oz2_dgemm(m, n, k, dA.data_ptr(), m, dB.data_ptr(), k, dC.data_ptr(), m, N)
+    torch.cuda.synchronize()
+    assert _flag(ws, m, n, k, N) == 0
+    assert np.array_equal(dC.cpu().numpy(), orc.dgemm(A, B, N).C)
+    del ws
+
+
 @pytest.mark.parametrize("algorithm", [0, 1])
 @pytest.mark.parametrize("mode", [0, 1, 2])
 def test_signed_zeros_every_bit_of_c(algorithm, mode):
