@@ -212,7 +212,11 @@ __device__ __forceinline__ Tile decode_tile(const GemmArgs& g, int slot, int wv)
 
 // EARLY_ARRIVAL: a workgroup counts itself into the next round of the XCD synchronisation before its epilogue
 // instead of after it (see the launcher).
-template <bool RESIDUE_U8, bool LIST_ORDER, bool EARLY_ARRIVAL>
+// KBLOCKED: the inner dimension of a tile is walked in several k-blocks with a modular reduction of the
+// accumulators between them (inner dimensions beyond the INT32 exactness bound, or a smaller block on request).
+// A kernel of its own: the reduction's 256 x 8 instructions need so many registers at once that the compiler parks
+// 48 accumulators in scratch memory around it, on the path of every tile, and the instantiation without it does not.
+template <bool RESIDUE_U8, bool LIST_ORDER, bool EARLY_ARRIVAL, bool KBLOCKED>
 __global__ void __launch_bounds__(kThreads) gemm_i8_kernel(const GemmArgs g) {
   extern __shared__ __attribute__((aligned(1024))) char lds[];
 
@@ -317,7 +321,8 @@ __global__ void __launch_bounds__(kThreads) gemm_i8_kernel(const GemmArgs g) {
 #pragma unroll
     for (int y = 0; y < 4; ++y)
 #pragma unroll
-      for (int e = 0; e < 16; ++e) acc[x][y][e] = 0;
+      for (int e = 0; e < 16; ++e) acc[x][y][e] = RESIDUE_U8 ? (int)0x80000000 : 0;
+  // (the residue epilogue works on c' + 2^31 as an unsigned word: the accumulators start there, modulo 2^32)
 
   // ---- k-tiles 0 .. NS-2 are in flight: make tile 0 visible, its first fragments in registers.  After the
   // first tile of the loop the previous epilogue's stores are outstanding as well and cannot be told apart
@@ -395,18 +400,24 @@ __global__ void __launch_bounds__(kThreads) gemm_i8_kernel(const GemmArgs g) {
 
   const int p_int = (int)g.p[t];
   const float inv_pf = 1.0f / g.p[t];
-  for (int kt0 = 0; kt0 < ktiles; kt0 += g.ktiles_per_block) {
-    const int kt1 = kt0 + g.ktiles_per_block < ktiles ? kt0 + g.ktiles_per_block : ktiles;
-    int kt = kt0;
-    for (; kt < kt1; ++kt) body(kt);
-    if (kt1 < ktiles) {  // between k-blocks: bring the accumulators back near zero
+  if constexpr (KBLOCKED) {
+    for (int kt0 = 0; kt0 < ktiles; kt0 += g.ktiles_per_block) {
+      const int kt1 = kt0 + g.ktiles_per_block < ktiles ? kt0 + g.ktiles_per_block : ktiles;
+      int kt = kt0;
+      for (; kt < kt1; ++kt) body(kt);
+      if (kt1 < ktiles) {  // between k-blocks: bring the accumulators back near zero
 #pragma unroll
-      for (int x = 0; x < 4; ++x)
+        for (int x = 0; x < 4; ++x)
 #pragma unroll
-        for (int y = 0; y < 4; ++y)
+          for (int y = 0; y < 4; ++y)
 #pragma unroll
-          for (int e = 0; e < 16; ++e) acc[x][y][e] = reduce_mod(acc[x][y][e], p_int, inv_pf);
+            for (int e = 0; e < 16; ++e)
+              acc[x][y][e] = RESIDUE_U8 ? (reduce_mod(acc[x][y][e] ^ (int)0x80000000, p_int, inv_pf) ^ (int)0x80000000)
+                                        : reduce_mod(acc[x][y][e], p_int, inv_pf);
+      }
     }
+  } else {
+    for (int kt = 0; kt < ktiles; ++kt) body(kt);
   }
 
   // ---- a next tile whose first copies were not fetched by the main loop above: they fly during the epilogue
@@ -439,8 +450,16 @@ __global__ void __launch_bounds__(kThreads) gemm_i8_kernel(const GemmArgs g) {
     const unsigned two31 = (((k3 * 128u) % pu));            // 2^31 = 2^24 * 2^7
     const unsigned bias = (pu - two31) % pu;
     const float pf = g.p[t], ipf = 1.0f / pf, hipf = 0.5f / pf;
-    const size_t col = (size_t)tn * BN + wn * 128 + (lane & 31);       // + tj*32
-    uint8_t* plane = reinterpret_cast<uint8_t*>(g.c) + (size_t)t * g.n_pad * g.m_pad;
+    // the wave's corner of the tile (uniform over the wave) and the lane's own offset from it (column lane % 32,
+    // rows 16 half ..: below 2^32, m_pad is below 2^27)
+    uint8_t* const corner = reinterpret_cast<uint8_t*>(g.c) + (size_t)t * g.n_pad * g.m_pad +
+                            ((size_t)tn * BN + wn * 128) * g.m_pad + (size_t)tm * BM + wm * 128;
+    // (formed again for every tile from the lane number as the hardware counts it: a value kept across the main
+    // loop, where no register is free, would be parked in scratch memory and fetched per tile)
+    unsigned start = 0u;
+    asm volatile("" : "+s"(start));  // opaque zero: the count below is taken here, in every tile
+    const unsigned lane_now = __builtin_amdgcn_mbcnt_hi(~0u, __builtin_amdgcn_mbcnt_lo(~0u, start));
+    const unsigned lane_off = (lane_now & 31u) * (unsigned)g.m_pad + 16u * (lane_now >> 5);
 #pragma unroll
     for (int tj = 0; tj < 4; ++tj) {
       // w[ti][a]: rows ti*32 + 8a + 4*half + (0..3) of column j, one byte each
@@ -452,7 +471,7 @@ __global__ void __launch_bounds__(kThreads) gemm_i8_kernel(const GemmArgs g) {
           unsigned v = 0;
 #pragma unroll
           for (int b = 0; b < 4; ++b) {
-            const unsigned u = (unsigned)acc[ti][tj][4 * a + b] ^ 0x80000000u;
+            const unsigned u = (unsigned)acc[ti][tj][4 * a + b];
             const float x = (float)__builtin_amdgcn_udot4(u, kpack, bias, false);
             const float q = floorf(fmaf(x, ipf, hipf));
             v = __builtin_amdgcn_cvt_pk_u8_f32(fmaf(-q, pf, x), b, v);
@@ -463,13 +482,13 @@ __global__ void __launch_bounds__(kThreads) gemm_i8_kernel(const GemmArgs g) {
       // of w[ti][a] with the lower half of w[ti][a+2] leaves lane l with rows 0..15 and lane l + 32 with
       // rows 16..31 of the 32-row group, 16 contiguous bytes each: one 16-byte store per lane and group,
       // issued together so that the cache lines of the column are complete at once.
-      uint8_t* cj = plane + (col + tj * 32) * g.m_pad + (size_t)tm * BM + wm * 128 + 16 * half;
+      uint8_t* cj = corner + (size_t)(tj * 32) * g.m_pad;  // uniform; + ti*32 + lane_off below
 #pragma unroll
       for (int ti = 0; ti < 4; ++ti) {
         const auto s0 = __builtin_amdgcn_permlane32_swap(w[ti][0], w[ti][2], false, false);
         const auto s1 = __builtin_amdgcn_permlane32_swap(w[ti][1], w[ti][3], false, false);
         v4i o = {(int)s0[0], (int)s0[1], (int)s1[0], (int)s1[1]};
-        *reinterpret_cast<v4i*>(cj + ti * 32) = o;
+        *reinterpret_cast<v4i*>(cj + ti * 32 + lane_off) = o;
       }
     }
   } else {
@@ -511,14 +530,14 @@ constexpr int kXcds = 8;
 int g_sync_spins = 4096;  // polls per wait of the round synchronisation (each followed by a short sleep); 0: off
 hipError_t gemm_setup() {
   if (g_cus) return hipSuccess;
-  const void* kernels[6] = {reinterpret_cast<const void*>(gemm_i8_kernel<false, false, false>),
-                            reinterpret_cast<const void*>(gemm_i8_kernel<true, false, false>),
-                            reinterpret_cast<const void*>(gemm_i8_kernel<false, true, false>),
-                            reinterpret_cast<const void*>(gemm_i8_kernel<true, true, false>),
-                            reinterpret_cast<const void*>(gemm_i8_kernel<true, false, true>),
-                            reinterpret_cast<const void*>(gemm_i8_kernel<true, true, true>)};
+#define OZ2_BOTH(U8, LIST, EARLY)                                              \
+  reinterpret_cast<const void*>(gemm_i8_kernel<U8, LIST, EARLY, false>),       \
+      reinterpret_cast<const void*>(gemm_i8_kernel<U8, LIST, EARLY, true>)
+  const void* kernels[12] = {OZ2_BOTH(false, false, false), OZ2_BOTH(true, false, false), OZ2_BOTH(false, true, false),
+                             OZ2_BOTH(true, true, false),   OZ2_BOTH(true, false, true),  OZ2_BOTH(true, true, true)};
+#undef OZ2_BOTH
   hipError_t e = hipSuccess;
-  for (int i = 0; i < 6 && e == hipSuccess; ++i)
+  for (int i = 0; i < 12 && e == hipSuccess; ++i)
     e = hipFuncSetAttribute(kernels[i], hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
   if (e != hipSuccess) return e;
   int dev = 0, n = 0;
@@ -546,6 +565,7 @@ hipError_t launch_gemm(const Oz2Layout& lay, char* ws, int num_moduli, const int
   g.m_pad = lay.m_pad;
   g.n_pad = lay.n_pad;
   g.k_pad = lay.k_pad;
+  if (lay.m_pad >= ((int64_t)1 << 27)) return hipErrorInvalidValue;  // the epilogue's lane offsets: 31 m_pad + 16 in 32 bits
   g.tiles_m = (int)(lay.m_pad / BM);
   g.tiles_n = (int)(lay.n_pad / BN);
   g.num_moduli = num_moduli;
@@ -595,7 +615,15 @@ hipError_t launch_gemm(const Oz2Layout& lay, char* ws, int num_moduli, const int
   // together on their panels and is the faster one.  UINT8 epilogue only.
   const bool early = residue_u8 && g.xcd_sync != nullptr && g.ktiles <= 128;
   const dim3 grd(grid), thr(kThreads);
-#define OZ2_GEMM(U8, LIST, EARLY) hipLaunchKernelGGL((gemm_i8_kernel<U8, LIST, EARLY>), grd, thr, kLdsBytes, st, g)
+  // tiles walked in one k-block (the usual case) take the instantiation without the reduction between k-blocks
+  const bool kblocked = g.ktiles_per_block < g.ktiles;
+#define OZ2_GEMM(U8, LIST, EARLY)                                                                   \
+  do {                                                                                              \
+    if (kblocked)                                                                                   \
+      hipLaunchKernelGGL((gemm_i8_kernel<U8, LIST, EARLY, true>), grd, thr, kLdsBytes, st, g);      \
+    else                                                                                            \
+      hipLaunchKernelGGL((gemm_i8_kernel<U8, LIST, EARLY, false>), grd, thr, kLdsBytes, st, g);     \
+  } while (0)
   if (!residue_u8 && list_order)
     OZ2_GEMM(false, true, false);
   else if (!residue_u8)
