@@ -887,6 +887,33 @@ def test_dsyrk_matches_the_oracle_and_leaves_the_other_triangle(uplo, trans, mod
     del ws
 
 
+@pytest.mark.parametrize("uplo", ["L", "U"])
+def test_dsyrk_every_element_where_the_crt_runs_on_the_matrix_cores(uplo):
+    """A symmetric update with more than 2^24 elements of C and 12 moduli: stages 3 and 4 run in the matrix-core
+    kernel, which has to keep to the triangle (rows of a thread's four on both sides of the diagonal, ragged last
+    rows); every element of the triangle against the oracle, the other triangle untouched."""
+    rng = np.random.default_rng(33)
+    n, k, N = 4100, 48, 12
+    assert n * n >= 1 << 24
+    A = np.asfortranarray((rng.random((n, k)) - 0.5) * np.exp(rng.standard_normal((n, k))))
+    alpha, beta = -0.5, 1.25
+    C0 = np.asfortranarray(rng.standard_normal((n, n)))
+    ii, jj = np.meshgrid(np.arange(n), np.arange(n), indexing="ij")
+    outside = (ii < jj) if uplo == "L" else (ii > jj)
+    C0[outside] = np.nan            # never read, never written
+    dA = _dev(A)
+    dC = torch.from_numpy(np.ascontiguousarray(C0.T)).cuda().t()
+    ws = oz.Workspace(n, n, k, N)
+    print("dsyrk %d x %d, uplo=%s" % (n, n, uplo), flush=True)
+    oz.oz2_dsyrk(uplo, "N", n, k, alpha, dA.data_ptr(), n, beta, dC.data_ptr(), n, N)
+    torch.cuda.synchronize()
+    got = dC.cpu().numpy()
+    del ws, dC
+    assert np.all(np.isnan(got[outside])) and not np.any(np.isnan(got[~outside]))
+    ref = orc.dsyrk(uplo, "N", alpha, A, beta, np.asfortranarray(np.where(outside, 0.0, C0)), N)
+    assert np.array_equal(got[~outside], ref[~outside])
+
+
 def test_dsyrk_degenerate_and_nonfinite():
     rng = np.random.default_rng(32)
     n, k, N = 70, 40, 9
@@ -1019,6 +1046,27 @@ def test_dtrmm_matches_the_oracle_in_place(side, uplo, transa, diag, mode):
     assert np.array_equal(got[:m, :], ref)
     assert np.all(got[m:, :] == 7.0)            # the padding rows of B's array are untouched
     del ws
+
+
+def test_dtrmm_every_element_where_the_crt_runs_on_the_matrix_cores():
+    """A triangular product with more than 2^24 elements of B and 12 moduli (stages 3 and 4 in the matrix-core
+    kernel, written into the staging buffer of the in-place product): every element against the oracle."""
+    rng = np.random.default_rng(52)
+    m, n, N = 16390, 1030, 12       # B := alpha * B * op(A), A of order 1030
+    assert m * n >= 1 << 24
+    A = (rng.random((n, n)) - 0.5) * np.exp(rng.standard_normal((n, n)))
+    B = np.asfortranarray((rng.random((m, n)) - 0.5) * np.exp(rng.standard_normal((m, n))))
+    G = _garbage_outside(A, "L", "N")
+    dA = _dev(G)
+    dB = _dev(B)
+    ws = oz.Workspace(m, n, n, N)
+    print("dtrmm %d x %d, right lower" % (m, n), flush=True)
+    oz.oz2_dtrmm("R", "L", "N", "N", m, n, 0.75, dA.data_ptr(), n, dB.data_ptr(), m, N)
+    torch.cuda.synchronize()
+    got = dB.cpu().numpy()
+    del ws, dA, dB
+    ref = orc.dtrmm("R", "L", "N", "N", 0.75, G, B, N)
+    assert np.array_equal(got, ref)
 
 
 def test_dtrmm_degenerate_nonfinite_and_arguments():
